@@ -1,0 +1,163 @@
+"""The oracle's closed forms against brute force.
+
+The loop-nest simulator (oracle/sim.c) executes the dataflow stage by stage on
+tiny shapes and counts words and MACs; it contains no closed form.  The oracle
+must reproduce its counts for every loop order, every buffering-level
+combination and every recompute/fusion choice.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle as O
+from inputs import SplitMix64
+
+HW = dict(pe_rows=4, pe_cols=4, n_arrays=1, rf_bytes=64, gb_bytes=1 << 40,
+          e_dram=200.0, e_gb=6.0, e_rf=1.0, e_mac=1.0, dram_bw=64.0, gb_bw=256.0)
+
+
+def wl(N, d):
+    return dict(B=1, H=1, N=N, d=d, word_bytes=2, tiling_mode=1, c_softmax=10)
+
+
+CASES = [
+    # (N, d, inter-tile counts i,k,l,j)
+    (4, 4, [2, 2, 2, 2]), (4, 4, [4, 2, 2, 4]), (4, 4, [2, 4, 4, 2]),
+    (8, 2, [4, 2, 2, 2]), (8, 2, [2, 2, 8, 2]),
+    (6, 3, [2, 3, 3, 3]), (6, 3, [3, 3, 2, 3]),            # not powers of two
+    (4, 4, [1, 2, 2, 2]), (4, 4, [2, 1, 4, 2]), (4, 4, [2, 2, 1, 2]), (4, 4, [4, 2, 2, 1]),
+    (4, 4, [1, 1, 1, 1]), (4, 4, [1, 4, 1, 4]), (6, 3, [6, 1, 2, 3]), (6, 3, [1, 3, 6, 1]),
+]
+
+
+@pytest.mark.parametrize("N,d,xD", CASES)
+def test_every_order_level_recompute_fusion(N, d, xD):
+    w, h = O.workload(wl(N, d)), O.hw(HW)
+    X = [N, d, N, d]
+    xG = [X[q] // xD[q] for q in range(4)]
+    all_ge2 = all(v >= 2 for v in xD)
+    n = n_tight = 0
+    for order in itertools.permutations(range(4)):
+        pos = {q: 3 - a for a, q in enumerate(order)}
+        for level in itertools.product(range(5), repeat=4):
+            for r, f in ((0, 1), (1, 1), (0, 0), (1, 0)):
+                m = O.Mapping()
+                for q in range(4):
+                    m.xG[q], m.xD[q], m.order[q], m.level[q] = xG[q], xD[q], order[q], level[q]
+                m.recompute, m.fused = r, f
+                c, dt = O.evaluate_mapping(w, h, m)
+                # recomputation needs j outside k and a fused intermediate
+                structurally_ok = not r or (f and pos[3] > pos[1])
+                assert (c.reason != 1) == structurally_ok
+                if not structurally_ok:
+                    continue
+                s = O.simulate(xG, xD, order, level, r, f)
+                assert s.psum_violation == 0 and s.coverage_error == 0
+                da_o, da_s = list(dt.da), list(s.da)
+                if all_ge2:
+                    assert da_o == da_s, (order, level, r, f)
+                else:
+                    # a loop with a single iteration still counts as a blocker in the closed form
+                    assert all(a >= b for a, b in zip(da_o, da_s)), (order, level, r, f)
+                assert sum(da_o) == c.da_words
+                assert s.max_occupancy <= c.bs_words, (order, level, r, f)
+                n_tight += s.max_occupancy == c.bs_words
+                assert s.macs1 + s.macs2 == c.mac_total
+                assert s.softmax_elems == dt.softmax_elems
+                assert s.stages1 == dt.rho * xD[0] * xD[1] * xD[2]
+                assert s.stages2 == xD[0] * xD[2] * xD[3]
+                n += 1
+    assert n == 24 * 625 * 2 + 12 * 625
+    if all_ge2:
+        assert n_tight > 0.8 * n      # the reservation is attained by most dataflows
+
+
+def test_tile_matmul_words_and_cycles_against_fold_enumeration():
+    """Buffer<->RF words and cycles of one tile-level matmul, all three stationary
+    modes, against an explicit enumeration of the folds onto the PE array."""
+    rng = SplitMix64(7)
+    w = O.workload(wl(64, 32))
+    for trial in range(300):
+        R = 1 << (rng.next() % 4)
+        Cc = 1 << (rng.next() % 4)
+        g = 1 + rng.next() % 5
+        hw_ = O.hw(dict(HW, pe_rows=R, pe_cols=Cc, rf_bytes=2 * 2 * g))
+        if 2 * 2 * g < 6:
+            continue
+        S = O.space_size(w, hw_)
+        idx = rng.next() % S
+        m, c, dt = O.evaluate(w, hw_, idx)
+        if c.reason == 1:
+            continue
+        iG, kG, lG, jG = list(m.xG)
+        w1, c1, mac1 = O.sim_tile_matmul(iG, kG, lG, m.stat1, R, Cc, g)
+        w2, c2, mac2 = O.sim_tile_matmul(iG, lG, jG, m.stat2, R, Cc, g)
+        assert (dt.br_tile1, dt.cyc_tile1) == (w1, c1)
+        assert (dt.br_tile2, dt.cyc_tile2) == (w2, c2)
+        assert mac1 == iG * kG * lG and mac2 == iG * lG * jG
+        iD, kD, lD, jD = list(m.xD)
+        st1, st2 = dt.rho * iD * kD * lD, iD * lD * jD
+        assert c.br_words == st1 * w1 + st2 * w2
+        assert c.comp_cycles == st1 * c1 + st2 * c2
+        # an array that the tiles fill exactly runs at one MAC per PE per cycle
+        if all(v % R == 0 and v % Cc == 0 for v in (iG, kG, lG, jG)):
+            assert c.comp_cycles * R * Cc == c.mac_total
+
+
+def test_decode_is_the_documented_mixed_radix():
+    """Digits, least significant first: t_i t_k t_l t_j p_A p_B p_D p_E order r s1 s2 f;
+    the order digit is the lexicographic rank of the outer->inner loop sequence."""
+    w, h = O.workload(wl(12, 6)), O.hw(HW)
+    divs_N = [1, 2, 3, 4, 6, 12]
+    divs_d = [1, 2, 3, 6]
+    perms = sorted(itertools.permutations(range(4)))
+    S = O.space_size(w, h)
+    assert S == 6 * 4 * 6 * 4 * 540000
+    rng = SplitMix64(3)
+    for idx in [0, S - 1] + [rng.next() % S for _ in range(2000)]:
+        m, _, _ = O.evaluate(w, h, idx)
+        digits = [divs_N.index(m.xG[0]), divs_d.index(m.xG[1]), divs_N.index(m.xG[2]), divs_d.index(m.xG[3]),
+                  m.level[0], m.level[1], m.level[2], m.level[3],
+                  perms.index(tuple(m.order)), m.recompute, m.stat1, m.stat2, m.fused]
+        radix = [6, 4, 6, 4, 5, 5, 5, 5, 24, 2, 3, 3, 2]
+        back = 0
+        for dg, rd in reversed(list(zip(digits, radix))):
+            back = back * rd + dg
+        assert back == idx
+        assert [m.xG[q] * m.xD[q] for q in range(4)] == [12, 6, 12, 6]
+
+
+@pytest.mark.parametrize("objective", [0, 1, 2])
+def test_search_is_argmin_of_eval_batch(objective):
+    """The exhaustive search returns the lexicographic minimum of (key, index)
+    over the per-candidate costs, on a space small enough to sort."""
+    hw_ = O.hw(dict(HW, gb_bytes=96, dram_bw=2.0, gb_bw=64.0))
+    w = O.workload(dict(wl(8, 2), H=2))
+    S = O.space_size(w, hw_)
+    costs = O.eval_batch(w, hw_, 0, S)
+    valid = costs["valid"] == 1
+    assert valid.any() and (~valid).any()
+    E = np.where(valid, costs["energy_pj"], np.inf)
+    L = np.where(valid, costs["latency_cycles"], np.inf)
+    idx = np.arange(S)
+    if objective == 0:
+        order = np.lexsort((idx, E))
+    elif objective == 1:
+        order = np.lexsort((idx, L))
+    else:
+        order = np.lexsort((idx, E, L))
+    rc, best, c, nvalid, _ = O.search(w, hw_, objective)
+    assert rc == 0 and best == order[0]
+    assert nvalid == int(valid.sum())
+    assert c.energy_pj == costs["energy_pj"][best] and c.latency_cycles == costs["latency_cycles"][best]
+    # the latency objective really has ties, and they go to the lowest index
+    if objective == 1:
+        assert (L == L[best]).sum() > 1 and best == np.flatnonzero(L == L[best])[0]
+
+
+def test_search_reports_infeasible():
+    hw_ = O.hw(dict(HW, gb_bytes=4))
+    w = O.workload(wl(8, 2))
+    rc, _, c, nvalid, _ = O.search(w, hw_, 0, 0, 200000)
+    assert rc == -3 and nvalid == 0 and c.valid == 0
