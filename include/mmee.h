@@ -1,0 +1,170 @@
+/*
+ * mmee.h -- C ABI of the MI355X (gfx950) implementation of the hot path of MMEE,
+ * "Matrix Multiplication Encoded Enumeration" (Fast Cross-Operator Optimization
+ * of Attention Dataflow): exhaustive, pruned evaluation of the paper's analytical
+ * buffer/DRAM/energy/latency model (Sec. V) over every fused-attention dataflow
+ * (Sec. III-IV: tiling, loop order, buffering levels, recomputation, stationary
+ * modes, fused or unfused softmax) and reduction to the optimum (Sec. VI).
+ *
+ * Conventions
+ *  - Two chained matmuls per head (Sec. III-A):  C[i,l] = sum_k A[i,k] B[k,l],
+ *    E[i,j] = sum_l C[i,l] D[l,j];  for attention A=Q, B=K^T, D=V, E=O, so the
+ *    loop extents are I = L = N and K = J = d.  Dimensions are indexed
+ *    i=0, k=1, l=2, j=3 everywhere.  Each extent is split in two levels,
+ *    X = x_D * x_G: inter-tile count times intra-tile size (Sec. IV-A).
+ *  - A candidate is one index in [0, space).  Mixed-radix digits, least
+ *    significant first:
+ *        t_i, t_k, t_l, t_j   position of x_G in the ascending divisor list of I,K,L,J
+ *        p_A, p_B, p_D, p_E   buffering level 0..4 = number of innermost inter-tile
+ *                             loops the operand's buffer spans (0 = one tile; the
+ *                             paper's layers L3..L7, Sec. IV-B)
+ *        order  0..23         lexicographic rank of the inter-tile loop sequence,
+ *                             written outer -> inner over the symbols i<k<l<j
+ *        r      0..1          recomputation of C tiles (Sec. III-C)
+ *        s1,s2  0..2          stationary mode of Op1 / Op2: 0 weight, 1 input, 2 output (Sec. V-D)
+ *        f      0..1          1 = softmax fused (C stays on chip), 0 = C staged through DRAM
+ *    so space = (#tilings) * 540000.
+ *  - All pointers are HOST pointers unless stated otherwise.  The library keeps
+ *    none of them after a call returns.  Device scratch is cached inside the
+ *    library and released by mmee_shutdown().
+ *  - Every function returns 0 on success or a negative MMEE_E* code; nothing is
+ *    thrown across this boundary.  Calls are serialised by an internal lock.
+ *  - All the arithmetic runs in HIP kernels on the current HIP device; there is
+ *    no CPU fallback: without a usable GPU the calls return MMEE_EDEVICE.
+ */
+#ifndef MMEE_H
+#define MMEE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Attention workload (Sec. II-A): B batches of H heads, sequence length N, head dim d. */
+typedef struct mmee_workload {
+    uint32_t B, H, N, d;
+    uint32_t word_bytes;    /* bytes per element, 2 for fp16                              */
+    uint32_t tiling_mode;   /* 0: x_G ranges over power-of-two divisors, 1: all divisors   */
+    uint32_t c_softmax;     /* softmax cost per element of C in MAC-energy units (Sec. V-D; the paper uses 10) */
+    uint32_t reserved;      /* must be 0                                                   */
+} mmee_workload;
+
+/* Spatial accelerator (Sec. II-B): PE arrays with register files, one global buffer, DRAM. */
+typedef struct mmee_hw {
+    uint32_t pe_rows, pe_cols;  /* one PE array                                            */
+    uint32_t n_arrays;          /* heads are spread over the arrays (Sec. V)               */
+    uint32_t rf_bytes;          /* register file per PE; half of it holds stationary data  */
+    uint64_t gb_bytes;          /* global buffer capacity: BS * word_bytes <= gb_bytes     */
+    double e_dram, e_gb, e_rf, e_mac;   /* pJ per word access at each level, pJ per MAC     */
+    double dram_bw, gb_bw;      /* bytes per cycle; 0 drops that stream from the latency   */
+} mmee_hw;
+
+/* One decoded candidate (Sec. IV-A: loop boundaries, loop order, buffering levels). */
+typedef struct mmee_mapping {
+    uint64_t idx;
+    uint32_t xG[4], xD[4];      /* i,k,l,j                                                 */
+    uint8_t order[4];           /* inter-tile loops, outer -> inner, values 0..3 = i,k,l,j */
+    uint8_t level[4];           /* p_A, p_B, p_D, p_E                                      */
+    uint8_t recompute, stat1, stat2, fused;
+} mmee_mapping;
+
+/* Cost of one candidate.  The integer fields are per head (the model omits the head
+ * dimension, Sec. V); energy and latency cover all B*H heads.  64 bytes. */
+typedef struct mmee_cost {
+    uint64_t bs_words;          /* buffer size requirement, Eq. (4)                        */
+    uint64_t da_words;          /* DRAM access, Eq. (7) (+ DA_C when f = 0)                */
+    uint64_t br_words;          /* buffer <-> register-file traffic                        */
+    uint64_t mac_total;         /* N_op1 + N_op2, or j_D*N_op1 + N_op2 with recomputation  */
+    uint64_t comp_cycles;       /* compute cycles on one array                             */
+    double energy_pj;           /* +inf when valid == 0                                    */
+    double latency_cycles;      /* +inf when valid == 0                                    */
+    uint32_t valid;             /* 1 = feasible dataflow                                   */
+    uint32_t reason;            /* 0 ok; 1 not a dataflow (r=1 with k outside j, or r=1 with f=0):
+                                   all integer fields are 0; 2 exceeds the buffer capacity */
+} mmee_cost;
+
+typedef struct mmee_result {
+    mmee_mapping best;
+    mmee_cost cost;
+    uint64_t space;             /* size of the index space                                 */
+    uint64_t evaluated;         /* candidates whose cost the search actually formed        */
+    double seconds;             /* host wall time of the call (upload, kernels, readback)  */
+    double kernel_seconds;      /* device time of the search kernel alone (HIP events)     */
+} mmee_result;
+
+/* Counts of the offline stage (Sec. VI-B): loop-order x buffering-level rows per
+ * (recompute, fused) group before and after symbolic pruning.  Group g = r + 2 f. */
+typedef struct mmee_row_stats {
+    uint32_t rows_total[4];     /* 15000 each                                              */
+    uint32_t rows_valid[4];     /* rows that denote a dataflow                             */
+    uint32_t rows_kept[4];      /* survivors of the dominance test                         */
+} mmee_row_stats;
+
+enum {
+    MMEE_OBJ_ENERGY = 0,                /* key (energy, idx)            */
+    MMEE_OBJ_LATENCY = 1,               /* key (latency, idx)           */
+    MMEE_OBJ_LATENCY_THEN_ENERGY = 2    /* key (latency, energy, idx)   */
+};
+
+enum {
+    MMEE_SEARCH_PRUNED = 0,             /* offline symbolic pruning on (the paper's method) */
+    MMEE_SEARCH_EXHAUSTIVE = 1          /* cost every candidate that denotes a dataflow     */
+};
+
+enum {
+    MMEE_OK = 0,
+    MMEE_EINVAL = -1,       /* null pointer, zero dimension, unsupported size, bad enum       */
+    MMEE_ERANGE = -2,       /* index range outside [0, space)                                 */
+    MMEE_ENOFEASIBLE = -3,  /* every candidate is masked; out->cost.valid = 0                 */
+    MMEE_EDEVICE = -4       /* HIP error or no device                                         */
+};
+
+/* Number of candidates of (workload, hw): #tilings (integer factorisations, Sec. VI-A)
+ * times 540000.  Pure host arithmetic. */
+int mmee_space_size(const mmee_workload *w, const mmee_hw *hw, uint64_t *out);
+
+/* On-device mixed-radix decode of n candidate indices (host arrays in and out). */
+int mmee_decode(const mmee_workload *w, const mmee_hw *hw, const uint64_t *idx, uint64_t n,
+                mmee_mapping *out);
+
+/* Cost of the n consecutive candidates first_idx .. first_idx+n-1 (Sec. V, Eq. (1)-(7),
+ * energy and latency of Sec. V-D).  out_costs holds n records and may be host memory or
+ * device memory of the current device (detected); device results are not copied back. */
+int mmee_eval_batch(const mmee_workload *w, const mmee_hw *hw, uint64_t first_idx, uint64_t n,
+                    mmee_cost *out_costs);
+
+/* Optimal mapping under one objective; ties go to the lowest index (Sec. VI).
+ * mmee_search uses the pruned row set. */
+int mmee_search(const mmee_workload *w, const mmee_hw *hw, int objective, mmee_result *out);
+int mmee_search_ex(const mmee_workload *w, const mmee_hw *hw, int objective, uint32_t flags,
+                   mmee_result *out);
+
+/* One pass over the space that reduces n_obj (1..3, distinct) objectives at once: all
+ * metrics of a candidate are formed once and shared (Sec. VII-C).  out holds n_obj results. */
+int mmee_search_multi(const mmee_workload *w, const mmee_hw *hw, const int *objectives,
+                      uint32_t n_obj, uint32_t flags, mmee_result *out);
+
+/* count independent searches (arrays of count workloads, hws, objectives, results) enqueued
+ * back to back on one stream with a single synchronisation at the end.  Neighbouring entries
+ * with identical workload and hw share one pass.  Returns the first non-zero per-entry code
+ * (per-entry codes are stored in rc[i] when rc is not null). */
+int mmee_search_many(const mmee_workload *w, const mmee_hw *hw, const int *objectives,
+                     uint32_t count, uint32_t flags, mmee_result *out, int *rc);
+
+/* Runs the offline stage if needed (row encoding + symbolic pruning, once per process) and
+ * reports its counts. */
+int mmee_offline_stats(mmee_row_stats *out);
+
+/* Use this HIP stream (a hipStream_t passed as void*) for all later launches; NULL = default. */
+int mmee_set_stream(void *hip_stream);
+
+/* Free all cached device memory.  The library re-initialises itself on the next call. */
+void mmee_shutdown(void);
+
+const char *mmee_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MMEE_H */

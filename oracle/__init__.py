@@ -91,13 +91,15 @@ def lib() -> C.CDLL:
                                        P(C.c_uint64), P(Cost), P(C.c_uint64), P(C.c_int)]
         L.orc_search.argtypes = [P(Workload), P(Hw), C.c_int,
                                  P(C.c_uint64), P(Cost), P(C.c_uint64), P(C.c_int)]
+        L.orc_search_all.argtypes = [P(Workload), P(Hw), C.c_uint64, C.c_uint64,
+                                     C.c_uint64 * 3, Cost * 3, P(C.c_uint64), P(C.c_int)]
         L.sim_run.argtypes = [C.c_uint32 * 4, C.c_uint32 * 4, C.c_uint8 * 4, C.c_uint8 * 4,
                               C.c_int, C.c_int, P(SimResult)]
         L.sim_tile_matmul.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_int,
                                       C.c_uint32, C.c_uint32, C.c_uint32,
                                       P(C.c_uint64), P(C.c_uint64), P(C.c_uint64)]
         for name in ("orc_space_size", "orc_decode", "orc_eval", "orc_eval_mapping",
-                     "orc_eval_batch", "orc_search_range", "orc_search", "sim_run",
+                     "orc_eval_batch", "orc_search_range", "orc_search", "orc_search_all", "sim_run",
                      "sim_tile_matmul"):
             getattr(L, name).restype = C.c_int
         _lib = L
@@ -158,6 +160,15 @@ def search(w: Workload, h: Hw, objective: int, first_idx: int | None = None, n: 
         rc = lib().orc_search_range(C.byref(w), C.byref(h), objective, first_idx, n,
                                     C.byref(bi), C.byref(c), C.byref(nv), C.byref(th))
     return rc, bi.value, c, nv.value, th.value
+
+
+def search_all(w: Workload, h: Hw, first_idx: int | None = None, n: int | None = None):
+    """One exhaustive pass, all three objectives.  Returns (rc, [idx]*3, [Cost]*3, n_valid, threads)."""
+    if first_idx is None:
+        first_idx, n = 0, space_size(w, h)
+    bi, bc, nv, th = (C.c_uint64 * 3)(), (Cost * 3)(), C.c_uint64(), C.c_int()
+    rc = lib().orc_search_all(C.byref(w), C.byref(h), first_idx, n, bi, bc, C.byref(nv), C.byref(th))
+    return rc, list(bi), list(bc), nv.value, th.value
 
 
 def simulate(xG, xD, order, level, recompute: int, fused: int) -> SimResult:

@@ -506,6 +506,66 @@ int orc_search_range(const orc_workload *w, const orc_hw *hw, int objective,
     return 0;
 }
 
+/* One pass over [first_idx, first_idx + n) keeping the minimum for each of the
+ * three objectives at once (slot = objective code). */
+int orc_search_all(const orc_workload *w, const orc_hw *hw, uint64_t first_idx, uint64_t n,
+                   uint64_t best_idx[3], orc_cost best_cost[3], uint64_t *n_valid, int *threads_used)
+{
+    tiling_space ts;
+    if (check_args(w, hw) || !best_idx || !best_cost) return -1;
+    if (make_space(w, &ts)) return -1;
+    uint64_t S = ts.n_tilings * ROWS_PER_TILING;
+    if (first_idx > S || n > S - first_idx) return -2;
+    int have = 0, nthreads = 1;
+    uint64_t gidx[3] = {0, 0, 0}, gvalid = 0;
+    orc_cost gcost[3];
+    memset(gcost, 0, sizeof(gcost));
+    const uint64_t CH = 1u << 16;
+    int64_t nchunks = (int64_t)((n + CH - 1) / CH);
+#pragma omp parallel
+    {
+        int lhave = 0;
+        uint64_t lidx[3] = {0, 0, 0}, lvalid = 0;
+        orc_cost lcost[3];
+        memset(lcost, 0, sizeof(lcost));
+#ifdef _OPENMP
+#pragma omp single
+        nthreads = omp_get_num_threads();
+#endif
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t ch = 0; ch < nchunks; ++ch) {
+            uint64_t lo = first_idx + (uint64_t)ch * CH;
+            uint64_t hi = lo + CH;
+            if (hi > first_idx + n) hi = first_idx + n;
+            for (uint64_t idx = lo; idx < hi; ++idx) {
+                orc_mapping m;
+                orc_cost c;
+                decode_idx(&ts, idx, &m);
+                eval_mapping(w, hw, &ts, &m, &c, 0);
+                if (!c.valid) continue;
+                ++lvalid;
+                for (int o = 0; o < 3; ++o)
+                    if (!lhave || better(o, &c, idx, &lcost[o], lidx[o])) { lcost[o] = c; lidx[o] = idx; }
+                lhave = 1;
+            }
+        }
+#pragma omp critical
+        {
+            gvalid += lvalid;
+            if (lhave) {
+                for (int o = 0; o < 3; ++o)
+                    if (!have || better(o, &lcost[o], lidx[o], &gcost[o], gidx[o])) { gcost[o] = lcost[o]; gidx[o] = lidx[o]; }
+                have = 1;
+            }
+        }
+    }
+    if (threads_used) *threads_used = nthreads;
+    if (n_valid) *n_valid = gvalid;
+    if (!have) { for (int o = 0; o < 3; ++o) best_cost[o].valid = 0; return -3; }
+    for (int o = 0; o < 3; ++o) { best_idx[o] = gidx[o]; best_cost[o] = gcost[o]; }
+    return 0;
+}
+
 int orc_search(const orc_workload *w, const orc_hw *hw, int objective,
                uint64_t *best_idx, orc_cost *best_cost, uint64_t *n_valid, int *threads_used)
 {

@@ -1,0 +1,702 @@
+// HIP kernels of libmmee for gfx950 (wave64).  Included once by mmee.hip.
+//
+//   k_build_rows     offline:  row id -> selectors (the query-matrix side, Sec. V-E / VI-A)
+//   k_prune_rows     offline:  symbolic dominance test inside each group (Sec. VI-B)
+//   k_compact_rows   offline:  ballot + prefix compaction of surviving rows
+//   k_build_tilings  online:   tiling id -> boundaries -> per-tiling tables (the boundary-matrix side)
+//   k_search         online:   contraction, capacity mask, energy/latency, hierarchical argmin
+//   k_eval_batch     online:   the same model, one 64-byte record per candidate
+//   k_decode         online:   index -> mapping
+#pragma once
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include "../../include/mmee.h"
+#include "layout.h"
+
+namespace mmee {
+
+// ---------------------------------------------------------------------------
+// small helpers
+
+__device__ __forceinline__ double pos_inf() { return __longlong_as_double(0x7ff0000000000000ll); }
+
+__device__ __forceinline__ bool key_less(const Key &a, const Key &b)
+{
+    if (a.p != b.p) return a.p < b.p;
+    if (a.s != b.s) return a.s < b.s;
+    return a.idx < b.idx;
+}
+
+// ---- cross-lane moves for the wave-level argmin (DPP inside a row of 16 lanes,
+// ds_swizzle across rows of a half wave, ds_bpermute across the halves) --------
+template <int STEP>
+__device__ __forceinline__ uint32_t lane_exchange(uint32_t v)
+{
+    if constexpr (STEP == 0) return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+    if constexpr (STEP == 1) return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+    if constexpr (STEP == 2) return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xF, 0xF, false);  // row_half_mirror
+    if constexpr (STEP == 3) return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xF, 0xF, false);  // row_mirror
+    if constexpr (STEP == 4) return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x401F);                          // lane ^ 16
+    return (uint32_t)__builtin_amdgcn_ds_bpermute((int)(((threadIdx.x & 63) ^ 32) << 2), (int)v);                   // lane ^ 32
+}
+
+template <int STEP>
+__device__ __forceinline__ Key key_exchange(const Key &k)
+{
+    Key o;
+    unsigned long long p = (unsigned long long)__double_as_longlong(k.p);
+    unsigned long long s = (unsigned long long)__double_as_longlong(k.s);
+    uint32_t plo = lane_exchange<STEP>((uint32_t)p), phi = lane_exchange<STEP>((uint32_t)(p >> 32));
+    uint32_t slo = lane_exchange<STEP>((uint32_t)s), shi = lane_exchange<STEP>((uint32_t)(s >> 32));
+    uint32_t ilo = lane_exchange<STEP>((uint32_t)k.idx), ihi = lane_exchange<STEP>((uint32_t)(k.idx >> 32));
+    o.p = __longlong_as_double((long long)(((unsigned long long)phi << 32) | plo));
+    o.s = __longlong_as_double((long long)(((unsigned long long)shi << 32) | slo));
+    o.idx = ((uint64_t)ihi << 32) | ilo;
+    return o;
+}
+
+// after this every lane of the wave holds the wave's minimum
+__device__ __forceinline__ Key wave_min(Key k)
+{
+    Key o;
+    o = key_exchange<0>(k); if (key_less(o, k)) k = o;
+    o = key_exchange<1>(k); if (key_less(o, k)) k = o;
+    o = key_exchange<2>(k); if (key_less(o, k)) k = o;
+    o = key_exchange<3>(k); if (key_less(o, k)) k = o;
+    o = key_exchange<4>(k); if (key_less(o, k)) k = o;
+    o = key_exchange<5>(k); if (key_less(o, k)) k = o;
+    return k;
+}
+
+// ---------------------------------------------------------------------------
+// offline stage: the query side
+
+// the 24 inter-tile loop orders, outer -> inner, in lexicographic order over i<k<l<j;
+// 2 bits per slot, slot 0 = outermost
+__device__ __forceinline__ uint32_t order_of_rank(uint32_t rank)
+{
+    uint32_t avail = 0xE4;            // nibble list 3,2,1,0 packed 2 bits each: entry e at bits 2e
+    uint32_t packed = 0;
+    uint32_t f = 6, left = 4;
+    for (uint32_t slot = 0; slot < 4; ++slot) {
+        uint32_t pick = rank / f;
+        rank -= pick * f;
+        uint32_t sym = (avail >> (2 * pick)) & 3;
+        packed |= sym << (2 * slot);
+        // delete entry `pick` from the list
+        uint32_t low = avail & ((1u << (2 * pick)) - 1);
+        uint32_t high = (avail >> (2 * pick + 2)) << (2 * pick);
+        avail = low | high;
+        --left;
+        if (left) f /= left;
+    }
+    return packed;
+}
+
+// selector of a DRAM term: which of the two loops an operand does not own multiply its
+// matrix size.  nest_mask: loops of the operand's operator nest; own0/own1: its own dims;
+// n0/n1: the other two dims in table order.
+__device__ __forceinline__ uint32_t dram_selector(const int pos[4], uint32_t nest_mask, uint32_t prefix_mask,
+                                                  int own0, int own1, int n0, int n1, int level)
+{
+    // blocker: innermost own loop outside the buffering level (Sec. V-A)
+    int bpos = 99, bdim = -1;
+    if (pos[own0] >= level) { bpos = pos[own0]; bdim = own0; }
+    if (pos[own1] >= level && pos[own1] < bpos) { bpos = pos[own1]; bdim = own1; }
+    if (bdim < 0) return 0;                                   // whole matrix resident: fetched once
+    uint32_t counted;
+    if (level == 0 && ((prefix_mask >> bdim) & 1)) {
+        counted = prefix_mask;                                // evicted at every operator switch
+    } else {
+        counted = 0;                                          // Scenario 1: blocker and all loops above it
+        for (int q = 0; q < 4; ++q)
+            if (((nest_mask >> q) & 1) && pos[q] >= bpos) counted |= 1u << q;
+    }
+    return ((counted >> n0) & 1) | (((counted >> n1) & 1) << 1);
+}
+
+__global__ void k_build_rows(uint4 *enc, uint32_t *sig)
+{
+    uint32_t row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= N_DFROWS) return;
+    uint32_t x = row;
+    int lvl[5];
+    lvl[OA] = x % 5; x /= 5;
+    lvl[OB] = x % 5; x /= 5;
+    lvl[OD] = x % 5; x /= 5;
+    lvl[OE] = x % 5; x /= 5;
+    lvl[OC] = 0;
+    uint32_t rank = x % 24; x /= 24;
+    uint32_t r = x & 1, f = x >> 1;
+
+    uint32_t ord = order_of_rank(rank);
+    int pos[4];
+    for (int slot = 0; slot < 4; ++slot) pos[(ord >> (2 * slot)) & 3] = 3 - slot;
+
+    // loops iterated by both operators lead the nest (Sec. IV-B); the rest splits per operator
+    uint32_t shared_mask = (1u << DI) | (1u << DL) | (r ? (1u << DJ) : 0u);
+    uint32_t prefix_mask = 0;
+    for (int slot = 0; slot < 4; ++slot) {
+        uint32_t q = (ord >> (2 * slot)) & 3;
+        if (!((shared_mask >> q) & 1)) break;
+        prefix_mask |= 1u << q;
+    }
+    uint32_t nest1 = prefix_mask | (1u << DI) | (1u << DK) | (1u << DL);
+    uint32_t nest2 = prefix_mask | (1u << DI) | (1u << DL) | (1u << DJ);
+
+    const int own[5][2] = {{DI, DK}, {DK, DL}, {DI, DL}, {DL, DJ}, {DI, DJ}};
+    uint8_t sel[16];
+    uint32_t bs_sel[5];
+    for (int X = 0; X < 5; ++X) {
+        if (X == OC) continue;
+        bs_sel[X] = (uint32_t)(pos[own[X][0]] < lvl[X]) | ((uint32_t)(pos[own[X][1]] < lvl[X]) << 1);
+    }
+    // C holds every tile the producer finishes before the consumer starts (fused), else one tile
+    bs_sel[OC] = f ? ((uint32_t)!((prefix_mask >> DI) & 1) | ((uint32_t)!((prefix_mask >> DL) & 1) << 1)) : 0u;
+    for (int X = 0; X < 5; ++X) sel[X] = (uint8_t)(ENT_BS + 4 * X + bs_sel[X]);
+    const int ret[4] = {OA, OB, OD, OE};
+    uint32_t tau_bits = 0;
+    for (int y = 0; y < 4; ++y) {
+        bool tau = lvl[ret[y]] >= 1;
+        tau_bits |= (uint32_t)tau << y;
+        sel[5 + y] = tau ? sel[ret[y]] : (uint8_t)ENT_ZERO;
+    }
+    uint32_t da_sel[4];
+    da_sel[0] = dram_selector(pos, nest1, prefix_mask, DI, DK, DL, DJ, lvl[OA]);
+    da_sel[1] = dram_selector(pos, nest1, prefix_mask, DK, DL, DI, DJ, lvl[OB]);
+    da_sel[2] = dram_selector(pos, nest2, prefix_mask, DL, DJ, DI, DK, lvl[OD]);
+    da_sel[3] = dram_selector(pos, nest2, prefix_mask, DI, DJ, DK, DL, lvl[OE]);
+    for (int y = 0; y < 4; ++y) sel[9 + y] = (uint8_t)(ENT_DA + 4 * y + da_sel[y]);
+    uint32_t dac_sel = 0;
+    if (f) {
+        sel[13] = (uint8_t)ENT_ZERO;                          // DA_C = 0 (Sec. V-C)
+    } else {
+        uint32_t out_k = dram_selector(pos, nest1, prefix_mask, DI, DL, DK, DJ, 0) & 1;
+        uint32_t in_j = (dram_selector(pos, nest2, prefix_mask, DI, DL, DK, DJ, 0) >> 1) & 1;
+        dac_sel = out_k | (in_j << 1);
+        sel[13] = (uint8_t)(ENT_DAC + dac_sel);
+    }
+    // recomputation must revisit C tiles (j outside k) and needs an on-chip C
+    bool valid = !(r && (!f || pos[DK] > pos[DJ]));
+    sel[ROW_FLAGS] = (uint8_t)((valid ? 1u : 0u) | (r << 1) | (f << 2));
+    sel[15] = 0;
+
+    uint4 packed;
+    packed.x = sel[0] | (sel[1] << 8) | (sel[2] << 16) | ((uint32_t)sel[3] << 24);
+    packed.y = sel[4] | (sel[5] << 8) | (sel[6] << 16) | ((uint32_t)sel[7] << 24);
+    packed.z = sel[8] | (sel[9] << 8) | (sel[10] << 16) | ((uint32_t)sel[11] << 24);
+    packed.w = sel[12] | (sel[13] << 8) | (sel[14] << 16) | ((uint32_t)sel[15] << 24);
+    enc[row] = packed;
+
+    // symbolic signature: one bit per optional factor of every term; a row whose bits are a
+    // subset of another's is no larger in any term, for every tiling (all factors are >= 1)
+    uint32_t s = 0;
+    for (int X = 0; X < 5; ++X) s |= bs_sel[X] << (2 * X);
+    s |= tau_bits << 10;
+    for (int y = 0; y < 4; ++y) s |= da_sel[y] << (14 + 2 * y);
+    s |= dac_sel << 22;
+    sig[row] = valid ? s : 0xFFFFFFFFu;
+}
+
+// Eq. (12) in a form that also protects index ties: row v goes if some row u of its group with a
+// lower row id is term-wise no larger.  flags[v]: bit0 = denotes a dataflow, bit1 = survives.
+__global__ void k_prune_rows(const uint32_t *__restrict__ sig, uint8_t *flags)
+{
+    __shared__ uint32_t s_sig[ROWS_PER_GROUP];
+    const uint32_t g = blockIdx.y;
+    for (uint32_t a = threadIdx.x; a < ROWS_PER_GROUP; a += blockDim.x) s_sig[a] = sig[g * ROWS_PER_GROUP + a];
+    __syncthreads();
+    uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= ROWS_PER_GROUP) return;
+    uint32_t sv = s_sig[v];
+    bool valid = sv != 0xFFFFFFFFu;
+    bool dominated = false;
+    if (valid) {
+        uint32_t nv = ~sv;
+        for (uint32_t u = 0; u < v; ++u) {
+            if ((s_sig[u] & nv) == 0) { dominated = true; break; }
+        }
+    }
+    flags[g * ROWS_PER_GROUP + v] = (uint8_t)((valid ? 1u : 0u) | ((valid && !dominated) ? 2u : 0u));
+}
+
+// Stable compaction of the rows whose flag bit `which` is set: wave ballot for the position
+// inside the wave, LDS prefix over the waves of the block.  One block per (list, group).
+__global__ void k_compact_rows(const uint8_t *__restrict__ flags, uint32_t *rows_valid, uint32_t *rows_kept,
+                               uint32_t *counts)
+{
+    __shared__ uint32_t wave_cnt[16];
+    __shared__ uint32_t running;
+    const uint32_t g = blockIdx.x & 3, which = blockIdx.x >> 2;
+    uint32_t *out = (which ? rows_kept : rows_valid) + g * ROWS_PER_GROUP;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    if (threadIdx.x == 0) running = 0;
+    __syncthreads();
+    for (uint32_t start = 0; start < ROWS_PER_GROUP; start += blockDim.x) {
+        uint32_t row = start + threadIdx.x;
+        bool on = row < ROWS_PER_GROUP && ((flags[g * ROWS_PER_GROUP + row] >> which) & 1);
+        unsigned long long mask = __ballot(on);
+        uint32_t before = __popcll(mask & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_cnt[wave] = __popcll(mask);
+        __syncthreads();
+        uint32_t base = running;
+        for (uint32_t wv = 0; wv < wave; ++wv) base += wave_cnt[wv];
+        if (on) out[base + before] = g * ROWS_PER_GROUP + row;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t tot = 0;
+            for (uint32_t wv = 0; wv < nwaves; ++wv) tot += wave_cnt[wv];
+            running += tot;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) counts[blockIdx.x] = running;
+}
+
+// ---------------------------------------------------------------------------
+// online stage: the boundary side
+
+__device__ __forceinline__ uint64_t cdiv(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+
+// words crossing buffer<->RF and cycles of one tile matmul m x r x n; mode 0 WS, 1 IS, 2 OS
+__device__ __forceinline__ void tile_cost(uint64_t m, uint64_t r, uint64_t n, int mode, uint64_t R, uint64_t C,
+                                          uint64_t g, uint64_t &words, uint64_t &cycles)
+{
+    uint64_t rows_dim = mode == 0 ? r : m;                 // spread over PE rows
+    uint64_t cols_dim = mode == 1 ? r : n;                 // spread over PE columns
+    uint64_t time_dim = mode == 0 ? m : (mode == 1 ? n : r);
+    uint64_t row_folds = cdiv(rows_dim, R);
+    words = rows_dim * cols_dim + time_dim * rows_dim * cdiv(cols_dim, C * g) + time_dim * cols_dim * row_folds;
+    cycles = row_folds * cdiv(cols_dim, C) * time_dim;
+}
+
+// One thread per tiling: decode the four tiling digits, derive the boundary vector and
+// store every subset product a row may select (entry-major, coalesced in the tiling).
+__global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__ btab, double *__restrict__ ctab_s,
+                                uint64_t *__restrict__ ctab_e)
+{
+    uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= mc.T) return;
+    uint64_t G[4], D[4];
+    uint32_t x = t;
+    for (int q = 0; q < 4; ++q) {
+        uint32_t digit = x % dv.ndiv[q];
+        x /= dv.ndiv[q];
+        G[q] = dv.div[q][digit];
+        D[q] = dv.X[q] / (uint32_t)G[q];
+    }
+    const uint64_t tp = mc.tpad;
+    const int own[5][2] = {{DI, DK}, {DK, DL}, {DI, DL}, {DL, DJ}, {DI, DJ}};
+    for (int X = 0; X < 5; ++X) {
+        uint64_t tile = G[own[X][0]] * G[own[X][1]];
+        uint64_t d0 = D[own[X][0]], d1 = D[own[X][1]];
+        btab[(ENT_BS + 4 * X + 0) * tp + t] = (double)tile;
+        btab[(ENT_BS + 4 * X + 1) * tp + t] = (double)(tile * d0);
+        btab[(ENT_BS + 4 * X + 2) * tp + t] = (double)(tile * d1);
+        btab[(ENT_BS + 4 * X + 3) * tp + t] = (double)(tile * d0 * d1);
+    }
+    btab[ENT_ZERO * tp + t] = 0.0;
+    const int da_own[4][2] = {{DI, DK}, {DK, DL}, {DL, DJ}, {DI, DJ}};
+    const int da_other[4][2] = {{DL, DJ}, {DI, DJ}, {DI, DK}, {DK, DL}};
+    for (int y = 0; y < 4; ++y) {
+        uint64_t whole = (uint64_t)dv.X[da_own[y][0]] * dv.X[da_own[y][1]];
+        uint64_t n0 = D[da_other[y][0]], n1 = D[da_other[y][1]];
+        btab[(ENT_DA + 4 * y + 0) * tp + t] = (double)whole;
+        btab[(ENT_DA + 4 * y + 1) * tp + t] = (double)(whole * n0);
+        btab[(ENT_DA + 4 * y + 2) * tp + t] = (double)(whole * n1);
+        btab[(ENT_DA + 4 * y + 3) * tp + t] = (double)(whole * n0 * n1);
+    }
+    {
+        uint64_t whole = (uint64_t)dv.X[DI] * dv.X[DL];
+        for (uint32_t s = 0; s < 4; ++s) {
+            uint64_t spill = (s & 1) ? D[DK] : 1, fetch = (s & 2) ? D[DJ] : 1;
+            btab[(ENT_DAC + s) * tp + t] = (double)(whole * (spill + fetch + 2));
+        }
+    }
+
+    // stationary-mode dependent part: buffer<->RF words and cycles per tile stage
+    uint64_t br1[3], cy1[3], br2[3], cy2[3];
+    for (int s = 0; s < 3; ++s) {
+        tile_cost(G[DI], G[DK], G[DL], s, mc.pe_rows, mc.pe_cols, mc.g_words, br1[s], cy1[s]);
+        tile_cost(G[DI], G[DL], G[DJ], s, mc.pe_rows, mc.pe_cols, mc.g_words, br2[s], cy2[s]);
+    }
+    const uint64_t I = dv.X[DI], K = dv.X[DK], L = dv.X[DL], J = dv.X[DJ];
+    const uint64_t BH = (uint64_t)mc.BH;
+    for (uint32_t r = 0; r < 2; ++r) {
+        uint64_t rho = r ? D[DJ] : 1;                         // producer repeated per j tile (Sec. V-D)
+        uint64_t st1 = rho * D[DI] * D[DK] * D[DL], st2 = D[DI] * D[DL] * D[DJ];
+        uint64_t mac = rho * I * K * L + I * L * J;
+        uint64_t sm = rho * I * L;
+        double *cs = ctab_s + ((uint64_t)t * 2 + r) * NCS;
+        for (uint32_t c9 = 0; c9 < 9; ++c9) {
+            uint32_t s1 = c9 % 3, s2 = c9 / 3;
+            uint64_t br = st1 * br1[s1] + st2 * br2[s2];
+            uint64_t cyc = st1 * cy1[s1] + st2 * cy2[s2];
+            double t_gb = mc.gb_bw > 0.0 ? (double)(br * (uint64_t)mc.word) / mc.gb_bw : 0.0;
+            cs[c9] = (double)(BH * br);
+            cs[9 + c9] = mc.c_lat * fmax((double)cyc, t_gb);
+            ctab_e[((uint64_t)r * NCE + c9) * tp + t] = br;
+            ctab_e[((uint64_t)r * NCE + 9 + c9) * tp + t] = cyc;
+        }
+        cs[18] = mc.e_rf * (double)(BH * 3 * mac);
+        cs[19] = mc.e_mac * (double)(BH * (mac + (uint64_t)mc.c_softmax * sm));
+        ctab_e[((uint64_t)r * NCE + 18) * tp + t] = mac;
+        ctab_e[((uint64_t)r * NCE + 19) * tp + t] = sm;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// one candidate, complete (shared by k_eval_batch and by the search's final record)
+
+struct EvalArgs {
+    const uint4 *enc;
+    const double *btab;
+    const uint64_t *ctab_e;
+    ModelConst mc;
+};
+
+__device__ __forceinline__ uint32_t sel_of(const uint4 &e, int k)
+{
+    uint32_t w = k < 4 ? e.x : (k < 8 ? e.y : (k < 12 ? e.z : e.w));
+    return (w >> (8 * (k & 3))) & 0xFF;
+}
+
+__device__ __forceinline__ void eval_candidate(const EvalArgs &a, uint32_t row, uint32_t t, mmee_cost &c)
+{
+    // row = levels/order (15000) + 15000 r + 30000 s1 + 90000 s2 + 270000 f
+    uint32_t lo = row % 15000, hi = row / 15000;
+    uint32_t r = hi & 1; hi >>= 1;
+    uint32_t s1 = hi % 3; hi /= 3;
+    uint32_t s2 = hi % 3; uint32_t f = hi / 3;
+    uint4 e = a.enc[lo + ROWS_PER_GROUP * (r + 2 * f)];
+    uint32_t flags = sel_of(e, ROW_FLAGS);
+    if (!(flags & 1)) {
+        c.bs_words = c.da_words = c.br_words = c.mac_total = c.comp_cycles = 0;
+        c.energy_pj = pos_inf(); c.latency_cycles = pos_inf();
+        c.valid = 0; c.reason = 1;
+        return;
+    }
+    const uint64_t tp = a.mc.tpad;
+    double v[NSEL];
+#pragma unroll
+    for (int k = 0; k < NSEL; ++k) v[k] = a.btab[sel_of(e, k) * tp + t];
+    // Eq. (1), (2), (4)
+    double bs1 = v[0] + v[1] + v[2] + v[7] + v[8];
+    double bs2 = v[2] + v[3] + v[4] + v[5] + v[6];
+    double bs = fmax(bs1, bs2);
+    double da = v[9] + v[10] + v[11] + v[12] + v[13];        // Eq. (7)
+    uint32_t c9 = s1 + 3 * s2;
+    uint64_t br = a.ctab_e[((uint64_t)r * NCE + c9) * tp + t];
+    uint64_t cyc = a.ctab_e[((uint64_t)r * NCE + 9 + c9) * tp + t];
+    uint64_t mac = a.ctab_e[((uint64_t)r * NCE + 18) * tp + t];
+    uint64_t sm = a.ctab_e[((uint64_t)r * NCE + 19) * tp + t];
+    c.bs_words = (uint64_t)bs; c.da_words = (uint64_t)da; c.br_words = br;
+    c.mac_total = mac; c.comp_cycles = cyc;
+    if (bs > a.mc.cap_words) {
+        c.energy_pj = pos_inf(); c.latency_cycles = pos_inf();
+        c.valid = 0; c.reason = 2;
+        return;
+    }
+    const double BH = a.mc.BH;
+    double t_dram_words = BH * da;
+    double t_gb_words = BH * (da + (double)br);
+    double t_rf = BH * 3.0 * (double)mac;
+    double t_mac = BH * ((double)mac + (double)a.mc.c_softmax * (double)sm);
+    double en = a.mc.e_dram * t_dram_words;
+    en = en + a.mc.e_gb * t_gb_words;
+    en = en + a.mc.e_rf * t_rf;
+    en = en + a.mc.e_mac * t_mac;
+    double l_comp = (double)cyc;
+    double l_dram = a.mc.dram_bw > 0.0 ? (da * a.mc.word) / a.mc.dram_bw : 0.0;
+    double l_gb = a.mc.gb_bw > 0.0 ? ((double)br * a.mc.word) / a.mc.gb_bw : 0.0;
+    c.energy_pj = en;
+    c.latency_cycles = a.mc.c_lat * fmax(fmax(l_comp, l_dram), l_gb);
+    c.valid = 1; c.reason = 0;
+}
+
+__device__ __forceinline__ void decode_candidate(const DivTable &dv, uint32_t T, uint64_t idx, mmee_mapping &m)
+{
+    uint32_t t = (uint32_t)(idx % T);
+    uint32_t row = (uint32_t)(idx / T);
+    m.idx = idx;
+    for (int q = 0; q < 4; ++q) {
+        uint32_t digit = t % dv.ndiv[q];
+        t /= dv.ndiv[q];
+        m.xG[q] = dv.div[q][digit];
+        m.xD[q] = dv.X[q] / m.xG[q];
+    }
+    for (int y = 0; y < 4; ++y) { m.level[y] = (uint8_t)(row % 5); row /= 5; }
+    uint32_t ord = order_of_rank(row % 24); row /= 24;
+    for (int slot = 0; slot < 4; ++slot) m.order[slot] = (uint8_t)((ord >> (2 * slot)) & 3);
+    m.recompute = (uint8_t)(row & 1); row >>= 1;
+    m.stat1 = (uint8_t)(row % 3); row /= 3;
+    m.stat2 = (uint8_t)(row % 3); row /= 3;
+    m.fused = (uint8_t)row;
+}
+
+__global__ void k_decode(DivTable dv, uint32_t T, const uint64_t *__restrict__ idx, uint64_t n, mmee_mapping *out)
+{
+    uint64_t a = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (a >= n) return;
+    mmee_mapping m;
+    decode_candidate(dv, T, idx[a], m);
+    out[a] = m;
+}
+
+// One candidate per thread, a block = 256 consecutive tilings of one row.  Records leave through
+// LDS so that every store instruction of a wave writes one contiguous kilobyte.
+__global__ __launch_bounds__(256) void k_eval_batch(EvalArgs a, uint64_t first_idx, uint64_t n, uint32_t row_first,
+                                                    uint32_t blocks_per_row, uint4 *__restrict__ out)
+{
+    __shared__ uint4 stage[4][256];                           // [wave][64 records x 4 pieces]
+    const uint32_t row = row_first + blockIdx.x / blocks_per_row;
+    const uint32_t t = (blockIdx.x % blocks_per_row) * 256 + threadIdx.x;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t T = a.mc.T;
+    const uint64_t idx = (uint64_t)row * T + t;
+    const bool on = t < T && idx >= first_idx && idx - first_idx < n;
+    mmee_cost c;
+    if (on) {
+        eval_candidate(a, row, t, c);
+        const uint4 *src = reinterpret_cast<const uint4 *>(&c);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) stage[wave][lane * 4 + k] = src[k];
+    }
+    const unsigned long long mask = __ballot(on);
+    // the wave's 64 records are consecutive in the output; lane L moves piece (L & 3) of
+    // record 16 k + L / 4 on pass k
+    const uint64_t wave_first = (uint64_t)row * T + (t - lane);   // index of lane 0's candidate
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        uint32_t rec = 16 * k + (lane >> 2);
+        if ((mask >> rec) & 1ull) {
+            uint64_t o = wave_first + rec - first_idx;
+            out[o * 4 + (lane & 3)] = stage[wave][rec * 4 + (lane & 3)];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// the search kernel
+
+struct SearchArgs {
+    const uint4 *enc;            // encoded rows
+    const uint32_t *rows;        // compacted row ids, groups back to back
+    uint32_t group_off[4];       // start of each group's list inside rows[]
+    uint32_t group_cnt[4];
+    uint32_t rb_start[5];        // first row-block of each group, [4] = total
+    uint32_t n_chunks;           // tiling chunks
+    const double *btab;
+    const double *ctab_s;
+    ModelConst mc;
+    Key *partials;               // [gridDim.x][3]
+    uint32_t *ticket;
+    FinalRecord *final_out;      // [3]
+    const uint64_t *ctab_e;
+    DivTable const *dv;          // device copy, for the final record's mapping
+};
+
+constexpr int TC = 64;           // tilings per block
+constexpr int SEARCH_THREADS = 256;
+
+// MASK: bit0 energy, bit1 latency, bit2 latency-then-energy.
+// EXACT_K: the DRAM bandwidth is 0 or a power of two, so words*word/bw is one exact multiply.
+template <int MASK, bool EXACT_K>
+__global__ __launch_bounds__(SEARCH_THREADS) void k_search(SearchArgs a)
+{
+    __shared__ double tab[TC * NENT];
+    __shared__ Key wave_best[3][SEARCH_THREADS / 64];
+    __shared__ uint32_t is_last;
+
+    const uint32_t chunk = blockIdx.x % a.n_chunks;
+    const uint32_t rb = blockIdx.x / a.n_chunks;
+    uint32_t g = 0;
+    while (g < 3 && rb >= a.rb_start[g + 1]) ++g;
+    const uint32_t slot = (rb - a.rb_start[g]) * SEARCH_THREADS + threadIdx.x;
+    const bool live = slot < a.group_cnt[g];
+    const uint32_t dfrow = a.rows[a.group_off[g] + (live ? slot : 0)];
+    const uint4 e = a.enc[dfrow];
+    const uint32_t r = g & 1;
+
+    const uint32_t t0 = chunk * TC;
+    const uint32_t nt = min((uint32_t)TC, a.mc.T - t0);
+
+    // stage this chunk of the boundary-side tables: global entry-major -> LDS tiling-major
+    for (uint32_t i = threadIdx.x; i < NENT * TC; i += SEARCH_THREADS) {
+        uint32_t ent = i / TC, tl = i % TC;
+        if (tl < nt) tab[tl * NENT + ent] = a.btab[(uint64_t)ent * a.mc.tpad + t0 + tl];
+    }
+    __syncthreads();
+
+    uint32_t off[NSEL];
+#pragma unroll
+    for (int k = 0; k < NSEL; ++k) off[k] = sel_of(e, k);
+
+    const double inf = pos_inf();
+    double bestE[9], bestL[9], bestLE_l[9], bestLE_e[9];
+    uint32_t codeE[9], codeL[9], codeLE[9];
+#pragma unroll
+    for (int c9 = 0; c9 < 9; ++c9) {
+        bestE[c9] = bestL[c9] = bestLE_l[c9] = bestLE_e[c9] = inf;
+        codeE[c9] = codeL[c9] = codeLE[c9] = 0;
+    }
+
+    const double *cs_base = a.ctab_s + ((uint64_t)t0 * 2 + r) * NCS;
+    for (uint32_t tl = 0; tl < nt; ++tl) {
+        const double *row_tab = tab + tl * NENT;
+        double v[NSEL];
+#pragma unroll
+        for (int k = 0; k < NSEL; ++k) v[k] = row_tab[off[k]];
+        // Eq. (1), (2), (4) and the capacity mask
+        double bs1 = v[0] + v[1] + v[2] + v[7] + v[8];
+        double bs2 = v[2] + v[3] + v[4] + v[5] + v[6];
+        bool ok = live && fmax(bs1, bs2) <= a.mc.cap_words;
+        double da = v[9] + v[10] + v[11] + v[12] + v[13];    // Eq. (7)
+        double dram_words = a.mc.BH * da;
+        double e_dram_part = ok ? a.mc.e_dram * dram_words : inf;
+        double l_dram;
+        if constexpr (EXACT_K) l_dram = a.mc.c_lat * (da * a.mc.dram_k);
+        else l_dram = a.mc.c_lat * ((da * a.mc.word) / a.mc.dram_bw);
+        l_dram = ok ? l_dram : inf;
+        const double *cs = cs_base + (uint64_t)tl * 2 * NCS;  // wave-uniform: scalar loads
+        const double e_rf_part = cs[18], e_mac_part = cs[19];
+#pragma unroll
+        for (int c9 = 0; c9 < 9; ++c9) {
+            double gb_words = dram_words + cs[c9];
+            double en = e_dram_part + a.mc.e_gb * gb_words;
+            en = en + e_rf_part;
+            en = en + e_mac_part;
+            double lat = fmax(l_dram, cs[9 + c9]);
+            if constexpr (MASK & 1) {
+                bool lt = en < bestE[c9];
+                bestE[c9] = fmin(bestE[c9], en);
+                codeE[c9] = lt ? tl : codeE[c9];
+            }
+            if constexpr (MASK & 2) {
+                bool lt = lat < bestL[c9];
+                bestL[c9] = fmin(bestL[c9], lat);
+                codeL[c9] = lt ? tl : codeL[c9];
+            }
+            if constexpr (MASK & 4) {
+                bool lt = lat < bestLE_l[c9] || (lat == bestLE_l[c9] && en < bestLE_e[c9]);
+                bestLE_l[c9] = lt ? lat : bestLE_l[c9];
+                bestLE_e[c9] = lt ? en : bestLE_e[c9];
+                codeLE[c9] = lt ? tl : codeLE[c9];
+            }
+        }
+    }
+
+    // fold the nine per-combination minima of this lane; ascending combination = ascending index
+    const uint32_t f = g >> 1;
+    const uint64_t row_base = (uint64_t)(dfrow % ROWS_PER_GROUP) + 15000ull * r + 270000ull * f;
+    Key mine[3];
+#pragma unroll
+    for (int o = 0; o < 3; ++o) { mine[o].p = inf; mine[o].s = 0.0; mine[o].idx = ~0ull; }
+#pragma unroll
+    for (int c9 = 0; c9 < 9; ++c9) {
+        const uint64_t combo_rows = 30000ull * (c9 % 3) + 90000ull * (c9 / 3);
+        if constexpr (MASK & 1) {
+            if (bestE[c9] < mine[0].p) {
+                mine[0].p = bestE[c9];
+                mine[0].idx = (uint64_t)(t0 + codeE[c9]) + (uint64_t)a.mc.T * (row_base + combo_rows);
+            }
+        }
+        if constexpr (MASK & 2) {
+            if (bestL[c9] < mine[1].p) {
+                mine[1].p = bestL[c9];
+                mine[1].idx = (uint64_t)(t0 + codeL[c9]) + (uint64_t)a.mc.T * (row_base + combo_rows);
+            }
+        }
+        if constexpr (MASK & 4) {
+            if (bestLE_l[c9] < mine[2].p || (bestLE_l[c9] == mine[2].p && bestLE_e[c9] < mine[2].s)) {
+                mine[2].p = bestLE_l[c9];
+                mine[2].s = bestLE_e[c9];
+                mine[2].idx = (uint64_t)(t0 + codeLE[c9]) + (uint64_t)a.mc.T * (row_base + combo_rows);
+            }
+        }
+    }
+    // a lane that found nothing feasible must not win a tie between infinities
+#pragma unroll
+    for (int o = 0; o < 3; ++o)
+        if (!(mine[o].p < inf)) { mine[o].p = inf; mine[o].s = 0.0; mine[o].idx = ~0ull; }
+
+    // wave -> block -> grid
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int o = 0; o < 3; ++o) {
+        if (!((MASK >> o) & 1)) continue;
+        Key k = wave_min(mine[o]);
+        if (lane == 0) wave_best[o][wave] = k;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int o = 0; o < 3; ++o) {
+            if (!((MASK >> o) & 1)) continue;
+            Key k = wave_best[o][0];
+            for (int wv = 1; wv < SEARCH_THREADS / 64; ++wv)
+                if (key_less(wave_best[o][wv], k)) k = wave_best[o][wv];
+            Key *dst = a.partials + (uint64_t)blockIdx.x * 3 + o;
+            __hip_atomic_store(&dst->idx, k.idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(reinterpret_cast<uint64_t *>(&dst->p), (uint64_t)__double_as_longlong(k.p),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(reinterpret_cast<uint64_t *>(&dst->s), (uint64_t)__double_as_longlong(k.s),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __threadfence();
+        uint32_t ticket = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        is_last = ticket == gridDim.x - 1;
+    }
+    __syncthreads();
+    if (!is_last) return;
+
+    // the last block to finish reduces every block's record
+    __threadfence();
+#pragma unroll
+    for (int o = 0; o < 3; ++o) {
+        if (!((MASK >> o) & 1)) continue;
+        Key k; k.p = inf; k.s = 0.0; k.idx = ~0ull;
+        for (uint32_t b = threadIdx.x; b < gridDim.x; b += SEARCH_THREADS) {
+            Key *src = a.partials + (uint64_t)b * 3 + o;
+            Key c;
+            c.idx = __hip_atomic_load(&src->idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            c.p = __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<uint64_t *>(&src->p),
+                                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            c.s = __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<uint64_t *>(&src->s),
+                                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            if (key_less(c, k)) k = c;
+        }
+        k = wave_min(k);
+        if (lane == 0) wave_best[o][wave] = k;
+    }
+    __syncthreads();
+    if (threadIdx.x < 3 && ((MASK >> threadIdx.x) & 1)) {
+        const int o = threadIdx.x;
+        Key k = wave_best[o][0];
+        for (int wv = 1; wv < SEARCH_THREADS / 64; ++wv)
+            if (key_less(wave_best[o][wv], k)) k = wave_best[o][wv];
+        FinalRecord *fr = a.final_out + o;
+        fr->key = k;
+        mmee_cost c;
+        mmee_mapping m;
+        if (k.p < inf) {
+            EvalArgs ea;
+            ea.enc = a.enc; ea.btab = a.btab; ea.ctab_e = a.ctab_e; ea.mc = a.mc;
+            eval_candidate(ea, (uint32_t)(k.idx / a.mc.T), (uint32_t)(k.idx % a.mc.T), c);
+            decode_candidate(*a.dv, a.mc.T, k.idx, m);
+        } else {
+            c.bs_words = c.da_words = c.br_words = c.mac_total = c.comp_cycles = 0;
+            c.energy_pj = inf; c.latency_cycles = inf; c.valid = 0; c.reason = 0;
+            for (int q = 0; q < 4; ++q) { m.xG[q] = m.xD[q] = 0; m.order[q] = m.level[q] = 0; }
+            m.idx = ~0ull; m.recompute = m.stat1 = m.stat2 = m.fused = 0;
+        }
+        const uint64_t *cs = reinterpret_cast<const uint64_t *>(&c);
+        for (int q = 0; q < 8; ++q) fr->cost[q] = cs[q];
+        uint64_t mbuf[7] = {0, 0, 0, 0, 0, 0, 0};
+        __builtin_memcpy(mbuf, &m, sizeof(mmee_mapping));
+        for (int q = 0; q < 7; ++q) fr->map[q] = mbuf[q];
+    }
+    if (threadIdx.x == 0) *a.ticket = 0;          // ready for the next launch on this stream
+}
+
+}  // namespace mmee

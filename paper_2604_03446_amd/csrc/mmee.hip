@@ -1,0 +1,540 @@
+// libmmee: host side of the C ABI declared in include/mmee.h.
+// Argument checking, integer factorisation of the loop extents (the online
+// tiling enumeration of Sec. VI-A), launch plumbing and result unpacking.
+// Every number the calls return is produced by the kernels in kernels.h.
+#include <hip/hip_runtime.h>
+
+#include <chrono>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "kernels.h"
+
+namespace mmee {
+namespace {
+
+#define HIP_TRY(expr)                                                                        \
+    do {                                                                                     \
+        hipError_t err_ = (expr);                                                            \
+        if (err_ != hipSuccess) {                                                            \
+            std::snprintf(g_last_error, sizeof(g_last_error), "%s: %s (%s:%d)", #expr,       \
+                          hipGetErrorString(err_), __FILE__, __LINE__);                      \
+            return MMEE_EDEVICE;                                                             \
+        }                                                                                    \
+    } while (0)
+
+char g_last_error[512] = "";
+std::mutex g_lock;
+
+struct State {
+    bool ready = false;
+    hipStream_t stream = nullptr;
+    // offline stage
+    uint4 *enc = nullptr;
+    uint32_t *sig = nullptr;
+    uint8_t *flags = nullptr;
+    uint32_t *rows[2] = {nullptr, nullptr};     // [0] every row that denotes a dataflow, [1] survivors
+    uint32_t *counts_dev = nullptr;
+    uint32_t counts[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+    // online scratch, grown on demand
+    double *btab = nullptr, *ctab_s = nullptr;
+    uint64_t *ctab_e = nullptr;
+    size_t tiling_cap = 0;
+    Key *partials = nullptr;
+    size_t partials_cap = 0;
+    uint32_t *ticket = nullptr;
+    FinalRecord *final_dev = nullptr, *final_host = nullptr;
+    DivTable *dv_dev = nullptr, *dv_host = nullptr;
+    size_t slots = 0;
+    std::vector<hipEvent_t> events;
+    void *eval_dev = nullptr;
+    size_t eval_cap = 0;
+} S;
+
+// ---- argument checking and the per-call plan ---------------------------------
+
+struct Plan {
+    DivTable dv;
+    ModelConst mc;
+    uint64_t T;
+    uint64_t space;
+    bool exact_k;
+};
+
+bool finite_nonneg(double v) { return std::isfinite(v) && v >= 0.0; }
+
+int list_divisors(uint32_t X, uint32_t mode, uint32_t *out)
+{
+    // trial division up to sqrt(X); ascending order
+    std::vector<uint32_t> lo, hi;
+    for (uint64_t a = 1; a * a <= X; ++a) {
+        if (X % a) continue;
+        lo.push_back((uint32_t)a);
+        if (a * a != X) hi.push_back((uint32_t)(X / a));
+    }
+    int n = 0;
+    auto keep = [&](uint32_t v) {
+        if (mode == 0 && (v & (v - 1))) return;
+        if (n < MAXDIV) out[n] = v;
+        ++n;
+    };
+    for (uint32_t v : lo) keep(v);
+    for (auto it = hi.rbegin(); it != hi.rend(); ++it) keep(*it);
+    return n;
+}
+
+int make_plan(const mmee_workload *w, const mmee_hw *hw, Plan &p)
+{
+    if (!w || !hw) return MMEE_EINVAL;
+    if (!w->B || !w->H || !w->N || !w->d || !w->word_bytes || w->tiling_mode > 1 || w->reserved) return MMEE_EINVAL;
+    if (!hw->pe_rows || !hw->pe_cols || !hw->n_arrays) return MMEE_EINVAL;
+    if ((uint64_t)hw->rf_bytes < 3ull * w->word_bytes) return MMEE_EINVAL;
+    if (!finite_nonneg(hw->e_dram) || !finite_nonneg(hw->e_gb) || !finite_nonneg(hw->e_rf) ||
+        !finite_nonneg(hw->e_mac) || !finite_nonneg(hw->dram_bw) || !finite_nonneg(hw->gb_bw))
+        return MMEE_EINVAL;
+    std::memset(&p, 0, sizeof(p));
+    p.dv.X[DI] = w->N; p.dv.X[DK] = w->d; p.dv.X[DL] = w->N; p.dv.X[DJ] = w->d;
+    p.T = 1;
+    for (int q = 0; q < 4; ++q) {
+        int n = list_divisors(p.dv.X[q], w->tiling_mode, p.dv.div[q]);
+        if (n <= 0 || n > MAXDIV) return MMEE_EINVAL;
+        p.dv.ndiv[q] = (uint32_t)n;
+        p.T *= (uint64_t)n;
+    }
+    if (p.T > (1ull << 22)) return MMEE_EINVAL;
+    p.space = p.T * ROWS_PER_TILING;
+    // every count of the model must stay an exact integer in fp64
+    long double bound = (long double)w->B * w->H * (long double)w->N * w->d * (long double)w->N * w->d *
+                        (16.0L + (long double)w->c_softmax) * (long double)w->word_bytes;
+    if (bound >= 9007199254740992.0L) return MMEE_EINVAL;
+    ModelConst &mc = p.mc;
+    mc.BH = (double)((uint64_t)w->B * w->H);
+    mc.c_lat = mc.BH / (double)hw->n_arrays;
+    uint64_t cap = hw->gb_bytes / w->word_bytes;
+    mc.cap_words = cap >= (1ull << 53) ? 9007199254740992.0 : (double)cap;
+    mc.word = (double)w->word_bytes;
+    mc.e_dram = hw->e_dram; mc.e_gb = hw->e_gb; mc.e_rf = hw->e_rf; mc.e_mac = hw->e_mac;
+    mc.dram_bw = hw->dram_bw; mc.gb_bw = hw->gb_bw;
+    int ex = 0;
+    p.exact_k = hw->dram_bw == 0.0 || std::frexp(hw->dram_bw, &ex) == 0.5;
+    mc.dram_k = hw->dram_bw > 0.0 ? mc.word / hw->dram_bw : 0.0;
+    mc.pe_rows = hw->pe_rows; mc.pe_cols = hw->pe_cols;
+    mc.g_words = hw->rf_bytes / w->word_bytes / 2;
+    mc.c_softmax = w->c_softmax;
+    mc.T = (uint32_t)p.T;
+    mc.tpad = (uint32_t)((p.T + 63) & ~63ull);
+    return MMEE_OK;
+}
+
+// ---- device state ------------------------------------------------------------
+
+int ensure_ready()
+{
+    if (S.ready) return MMEE_OK;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) {
+        std::snprintf(g_last_error, sizeof(g_last_error), "no HIP device");
+        return MMEE_EDEVICE;
+    }
+    HIP_TRY(hipMalloc(&S.enc, sizeof(uint4) * N_DFROWS));
+    HIP_TRY(hipMalloc(&S.sig, sizeof(uint32_t) * N_DFROWS));
+    HIP_TRY(hipMalloc(&S.flags, N_DFROWS));
+    HIP_TRY(hipMalloc(&S.rows[0], sizeof(uint32_t) * N_DFROWS));
+    HIP_TRY(hipMalloc(&S.rows[1], sizeof(uint32_t) * N_DFROWS));
+    HIP_TRY(hipMalloc(&S.counts_dev, sizeof(uint32_t) * 8));
+    HIP_TRY(hipMalloc(&S.ticket, sizeof(uint32_t)));
+    HIP_TRY(hipMemset(S.ticket, 0, sizeof(uint32_t)));
+    HIP_TRY(hipMemset(S.rows[0], 0, sizeof(uint32_t) * N_DFROWS));
+    HIP_TRY(hipMemset(S.rows[1], 0, sizeof(uint32_t) * N_DFROWS));
+    // offline stage: encode every (order, levels, r, f) row, prune, compact
+    hipLaunchKernelGGL(k_build_rows, dim3((N_DFROWS + 255) / 256), dim3(256), 0, S.stream, S.enc, S.sig);
+    hipLaunchKernelGGL(k_prune_rows, dim3((ROWS_PER_GROUP + 255) / 256, N_GROUPS), dim3(256), 0, S.stream, S.sig,
+                       S.flags);
+    hipLaunchKernelGGL(k_compact_rows, dim3(8), dim3(1024), 0, S.stream, S.flags, S.rows[0], S.rows[1],
+                       S.counts_dev);
+    HIP_TRY(hipGetLastError());
+    uint32_t h[8];
+    HIP_TRY(hipMemcpyAsync(h, S.counts_dev, sizeof(h), hipMemcpyDeviceToHost, S.stream));
+    HIP_TRY(hipStreamSynchronize(S.stream));
+    for (int g = 0; g < 4; ++g) { S.counts[0][g] = h[g]; S.counts[1][g] = h[4 + g]; }
+    S.ready = true;
+    return MMEE_OK;
+}
+
+int ensure_tilings(uint64_t tpad)
+{
+    if (tpad <= S.tiling_cap) return MMEE_OK;
+    if (S.btab) { HIP_TRY(hipStreamSynchronize(S.stream)); (void)hipFree(S.btab); (void)hipFree(S.ctab_s); (void)hipFree(S.ctab_e); }
+    S.btab = nullptr; S.ctab_s = nullptr; S.ctab_e = nullptr; S.tiling_cap = 0;
+    HIP_TRY(hipMalloc(&S.btab, sizeof(double) * NENT * tpad));
+    HIP_TRY(hipMalloc(&S.ctab_s, sizeof(double) * 2 * NCS * tpad));
+    HIP_TRY(hipMalloc(&S.ctab_e, sizeof(uint64_t) * 2 * NCE * tpad));
+    S.tiling_cap = tpad;
+    return MMEE_OK;
+}
+
+int ensure_partials(size_t nblocks)
+{
+    if (nblocks <= S.partials_cap) return MMEE_OK;
+    if (S.partials) { HIP_TRY(hipStreamSynchronize(S.stream)); (void)hipFree(S.partials); }
+    S.partials = nullptr; S.partials_cap = 0;
+    HIP_TRY(hipMalloc(&S.partials, sizeof(Key) * 3 * nblocks));
+    S.partials_cap = nblocks;
+    return MMEE_OK;
+}
+
+int ensure_slots(size_t n)
+{
+    if (n <= S.slots) return MMEE_OK;
+    if (S.final_dev) {
+        HIP_TRY(hipStreamSynchronize(S.stream));
+        (void)hipFree(S.final_dev); (void)hipFree(S.dv_dev);
+        (void)hipHostFree(S.final_host); (void)hipHostFree(S.dv_host);
+    }
+    S.slots = 0;
+    HIP_TRY(hipMalloc(&S.final_dev, sizeof(FinalRecord) * 3 * n));
+    HIP_TRY(hipMalloc(&S.dv_dev, sizeof(DivTable) * n));
+    HIP_TRY(hipHostMalloc(&S.final_host, sizeof(FinalRecord) * 3 * n));
+    HIP_TRY(hipHostMalloc(&S.dv_host, sizeof(DivTable) * n));
+    while (S.events.size() < 2 * n) {
+        hipEvent_t e;
+        HIP_TRY(hipEventCreate(&e));
+        S.events.push_back(e);
+    }
+    S.slots = n;
+    return MMEE_OK;
+}
+
+int launch_tilings(const Plan &p)
+{
+    int rc = ensure_tilings(p.mc.tpad);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_build_tilings, dim3((p.mc.T + 255) / 256), dim3(256), 0, S.stream, p.dv, p.mc, S.btab,
+                       S.ctab_s, S.ctab_e);
+    HIP_TRY(hipGetLastError());
+    return MMEE_OK;
+}
+
+template <int MASK>
+void launch_search_mask(bool exact_k, dim3 grid, const SearchArgs &a)
+{
+    if (exact_k) hipLaunchKernelGGL((k_search<MASK, true>), grid, dim3(SEARCH_THREADS), 0, S.stream, a);
+    else hipLaunchKernelGGL((k_search<MASK, false>), grid, dim3(SEARCH_THREADS), 0, S.stream, a);
+}
+
+// enqueue one pass (tables + search + readback of the final records) into slot `slot`
+int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_t *evaluated)
+{
+    int rc = launch_tilings(p);
+    if (rc) return rc;
+    const int which = (flags & MMEE_SEARCH_EXHAUSTIVE) ? 0 : 1;
+    SearchArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.enc = S.enc; a.rows = S.rows[which];
+    uint32_t rb = 0;
+    uint64_t nrows = 0;
+    for (uint32_t g = 0; g < 4; ++g) {
+        a.group_off[g] = g * ROWS_PER_GROUP;
+        a.group_cnt[g] = S.counts[which][g];
+        a.rb_start[g] = rb;
+        rb += (S.counts[which][g] + SEARCH_THREADS - 1) / SEARCH_THREADS;
+        nrows += S.counts[which][g];
+    }
+    a.rb_start[4] = rb;
+    a.n_chunks = (uint32_t)((p.T + TC - 1) / TC);
+    a.btab = S.btab; a.ctab_s = S.ctab_s; a.ctab_e = S.ctab_e;
+    a.mc = p.mc;
+    const uint64_t nblocks = (uint64_t)rb * a.n_chunks;
+    if (nblocks == 0 || nblocks > 0x7fffffffull) return MMEE_EINVAL;
+    rc = ensure_partials(nblocks);
+    if (rc) return rc;
+    a.partials = S.partials; a.ticket = S.ticket;
+    a.final_out = S.final_dev + 3 * slot;
+    a.dv = S.dv_dev + slot;
+    S.dv_host[slot] = p.dv;
+    HIP_TRY(hipMemcpyAsync(S.dv_dev + slot, S.dv_host + slot, sizeof(DivTable), hipMemcpyHostToDevice, S.stream));
+    HIP_TRY(hipEventRecord(S.events[2 * slot], S.stream));
+    dim3 grid((uint32_t)nblocks);
+    switch (mask) {
+    case 1: launch_search_mask<1>(p.exact_k, grid, a); break;
+    case 2: launch_search_mask<2>(p.exact_k, grid, a); break;
+    case 3: launch_search_mask<3>(p.exact_k, grid, a); break;
+    case 4: launch_search_mask<4>(p.exact_k, grid, a); break;
+    case 5: launch_search_mask<5>(p.exact_k, grid, a); break;
+    case 6: launch_search_mask<6>(p.exact_k, grid, a); break;
+    case 7: launch_search_mask<7>(p.exact_k, grid, a); break;
+    default: return MMEE_EINVAL;
+    }
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(S.events[2 * slot + 1], S.stream));
+    HIP_TRY(hipMemcpyAsync(S.final_host + 3 * slot, S.final_dev + 3 * slot, sizeof(FinalRecord) * 3,
+                           hipMemcpyDeviceToHost, S.stream));
+    *evaluated = nrows * p.T * 9ull;
+    return MMEE_OK;
+}
+
+int unpack_result(const Plan &p, size_t slot, int objective, uint64_t evaluated, double seconds, double ksec,
+                  mmee_result *out)
+{
+    const FinalRecord &fr = S.final_host[3 * slot + objective];
+    std::memset(out, 0, sizeof(*out));
+    std::memcpy(&out->cost, fr.cost, sizeof(mmee_cost));
+    std::memcpy(&out->best, fr.map, sizeof(mmee_mapping));
+    out->space = p.space;
+    out->evaluated = evaluated;
+    out->seconds = seconds;
+    out->kernel_seconds = ksec;
+    if (!(fr.key.p < INFINITY)) { out->cost.valid = 0; return MMEE_ENOFEASIBLE; }
+    return MMEE_OK;
+}
+
+bool same_problem(const mmee_workload &a, const mmee_hw &b, const mmee_workload &c, const mmee_hw &d)
+{
+    return std::memcmp(&a, &c, sizeof(a)) == 0 && b.pe_rows == d.pe_rows && b.pe_cols == d.pe_cols &&
+           b.n_arrays == d.n_arrays && b.rf_bytes == d.rf_bytes && b.gb_bytes == d.gb_bytes &&
+           b.e_dram == d.e_dram && b.e_gb == d.e_gb && b.e_rf == d.e_rf && b.e_mac == d.e_mac &&
+           b.dram_bw == d.dram_bw && b.gb_bw == d.gb_bw;
+}
+
+double now_seconds()
+{
+    return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+}  // namespace
+}  // namespace mmee
+
+using namespace mmee;
+
+extern "C" {
+
+int mmee_space_size(const mmee_workload *w, const mmee_hw *hw, uint64_t *out)
+{
+    if (!out) return MMEE_EINVAL;
+    Plan p;
+    int rc = make_plan(w, hw, p);
+    if (rc) return rc;
+    *out = p.space;
+    return MMEE_OK;
+}
+
+int mmee_set_stream(void *hip_stream)
+{
+    std::lock_guard<std::mutex> guard(g_lock);
+    if (S.ready) { HIP_TRY(hipStreamSynchronize(S.stream)); }
+    S.stream = (hipStream_t)hip_stream;
+    return MMEE_OK;
+}
+
+int mmee_offline_stats(mmee_row_stats *out)
+{
+    if (!out) return MMEE_EINVAL;
+    std::lock_guard<std::mutex> guard(g_lock);
+    int rc = ensure_ready();
+    if (rc) return rc;
+    for (int g = 0; g < 4; ++g) {
+        out->rows_total[g] = ROWS_PER_GROUP;
+        out->rows_valid[g] = S.counts[0][g];
+        out->rows_kept[g] = S.counts[1][g];
+    }
+    return MMEE_OK;
+}
+
+int mmee_decode(const mmee_workload *w, const mmee_hw *hw, const uint64_t *idx, uint64_t n, mmee_mapping *out)
+{
+    if (n && (!idx || !out)) return MMEE_EINVAL;
+    Plan p;
+    int rc = make_plan(w, hw, p);
+    if (rc) return rc;
+    for (uint64_t a = 0; a < n; ++a)
+        if (idx[a] >= p.space) return MMEE_ERANGE;
+    if (!n) return MMEE_OK;
+    std::lock_guard<std::mutex> guard(g_lock);
+    rc = ensure_ready();
+    if (rc) return rc;
+    uint64_t *d_idx = nullptr;
+    mmee_mapping *d_out = nullptr;
+    HIP_TRY(hipMalloc(&d_idx, sizeof(uint64_t) * n));
+    if (hipMalloc(&d_out, sizeof(mmee_mapping) * n) != hipSuccess) { (void)hipFree(d_idx); return MMEE_EDEVICE; }
+    hipError_t e = hipMemcpyAsync(d_idx, idx, sizeof(uint64_t) * n, hipMemcpyHostToDevice, S.stream);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(k_decode, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0, S.stream, p.dv, p.mc.T, d_idx, n,
+                           d_out);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(out, d_out, sizeof(mmee_mapping) * n, hipMemcpyDeviceToHost, S.stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(S.stream);
+    (void)hipFree(d_idx); (void)hipFree(d_out);
+    if (e != hipSuccess) {
+        std::snprintf(g_last_error, sizeof(g_last_error), "mmee_decode: %s", hipGetErrorString(e));
+        return MMEE_EDEVICE;
+    }
+    return MMEE_OK;
+}
+
+int mmee_eval_batch(const mmee_workload *w, const mmee_hw *hw, uint64_t first_idx, uint64_t n, mmee_cost *out_costs)
+{
+    Plan p;
+    int rc = make_plan(w, hw, p);
+    if (rc) return rc;
+    if (first_idx > p.space || n > p.space - first_idx) return MMEE_ERANGE;
+    if (!n) return MMEE_OK;
+    if (!out_costs) return MMEE_EINVAL;
+    std::lock_guard<std::mutex> guard(g_lock);
+    rc = ensure_ready();
+    if (rc) return rc;
+    rc = launch_tilings(p);
+    if (rc) return rc;
+
+    hipPointerAttribute_t attr;
+    bool on_device = false;
+    if (hipPointerGetAttributes(&attr, out_costs) == hipSuccess) on_device = attr.type == hipMemoryTypeDevice;
+    else (void)hipGetLastError();
+
+    EvalArgs ea;
+    ea.enc = S.enc; ea.btab = S.btab; ea.ctab_e = S.ctab_e; ea.mc = p.mc;
+    const uint32_t bpr = (uint32_t)((p.T + 255) / 256);
+    const uint64_t CHUNK = 1ull << 24;          // records per launch: 1 GiB of output
+    if (!on_device) {
+        size_t need = (size_t)std::min<uint64_t>(n, CHUNK) * sizeof(mmee_cost);
+        if (need > S.eval_cap) {
+            if (S.eval_dev) { HIP_TRY(hipStreamSynchronize(S.stream)); (void)hipFree(S.eval_dev); }
+            S.eval_dev = nullptr; S.eval_cap = 0;
+            HIP_TRY(hipMalloc(&S.eval_dev, need));
+            S.eval_cap = need;
+        }
+    }
+    for (uint64_t done = 0; done < n; done += CHUNK) {
+        const uint64_t cnt = std::min<uint64_t>(CHUNK, n - done);
+        const uint64_t first = first_idx + done;
+        const uint64_t row_first = first / p.T, row_last = (first + cnt - 1) / p.T;
+        const uint64_t nblocks = (row_last - row_first + 1) * bpr;
+        if (nblocks > 0x7fffffffull) return MMEE_EINVAL;
+        uint4 *dst = on_device ? reinterpret_cast<uint4 *>(out_costs + done) : reinterpret_cast<uint4 *>(S.eval_dev);
+        hipLaunchKernelGGL(k_eval_batch, dim3((uint32_t)nblocks), dim3(256), 0, S.stream, ea, first, cnt,
+                           (uint32_t)row_first, bpr, dst);
+        HIP_TRY(hipGetLastError());
+        if (!on_device) {
+            HIP_TRY(hipMemcpyAsync(out_costs + done, S.eval_dev, cnt * sizeof(mmee_cost), hipMemcpyDeviceToHost,
+                                   S.stream));
+            HIP_TRY(hipStreamSynchronize(S.stream));
+        }
+    }
+    HIP_TRY(hipStreamSynchronize(S.stream));
+    return MMEE_OK;
+}
+
+int mmee_search_many(const mmee_workload *w, const mmee_hw *hw, const int *objectives, uint32_t count,
+                     uint32_t flags, mmee_result *out, int *rc_out)
+{
+    if (!count) return MMEE_OK;
+    if (!w || !hw || !objectives || !out) return MMEE_EINVAL;
+    if (flags & ~(uint32_t)MMEE_SEARCH_EXHAUSTIVE) return MMEE_EINVAL;
+    std::lock_guard<std::mutex> guard(g_lock);
+    const double t_start = now_seconds();
+    int rc = ensure_ready();
+    if (rc) return rc;
+
+    // group neighbouring entries that describe the same problem into one pass
+    struct Pass { uint32_t first, n; int mask; Plan plan; int rc; uint64_t evaluated; };
+    std::vector<Pass> passes;
+    std::vector<int> codes(count, MMEE_OK);
+    for (uint32_t a = 0; a < count;) {
+        Pass ps;
+        ps.first = a; ps.n = 0; ps.mask = 0; ps.evaluated = 0;
+        ps.rc = make_plan(w + a, hw + a, ps.plan);
+        uint32_t b = a;
+        while (b < count && same_problem(w[a], hw[a], w[b], hw[b])) {
+            int o = objectives[b];
+            if (o < 0 || o > 2) { if (!ps.rc) ps.rc = MMEE_EINVAL; }
+            else if (ps.mask & (1 << o)) break;      // same objective twice: start a new pass
+            else ps.mask |= 1 << o;
+            ++b; ++ps.n;
+        }
+        if (ps.n == 0) { ps.n = 1; b = a + 1; }
+        passes.push_back(ps);
+        a = b;
+    }
+    rc = ensure_slots(passes.size());
+    if (rc) return rc;
+    for (size_t s = 0; s < passes.size(); ++s) {
+        Pass &ps = passes[s];
+        if (ps.rc == MMEE_OK) ps.rc = enqueue_search(ps.plan, ps.mask, flags, s, &ps.evaluated);
+    }
+    HIP_TRY(hipStreamSynchronize(S.stream));
+    const double seconds = now_seconds() - t_start;
+    int first_bad = MMEE_OK;
+    for (size_t s = 0; s < passes.size(); ++s) {
+        Pass &ps = passes[s];
+        float ms = 0.f;
+        if (ps.rc == MMEE_OK) (void)hipEventElapsedTime(&ms, S.events[2 * s], S.events[2 * s + 1]);
+        for (uint32_t a = ps.first; a < ps.first + ps.n; ++a) {
+            int code = ps.rc;
+            if (code == MMEE_OK)
+                code = unpack_result(ps.plan, s, objectives[a], ps.evaluated, seconds, ms * 1e-3, out + a);
+            else
+                std::memset(out + a, 0, sizeof(mmee_result));
+            if (rc_out) rc_out[a] = code;
+            if (code && !first_bad) first_bad = code;
+        }
+    }
+    return first_bad;
+}
+
+int mmee_search_multi(const mmee_workload *w, const mmee_hw *hw, const int *objectives, uint32_t n_obj,
+                      uint32_t flags, mmee_result *out)
+{
+    if (!w || !hw || !objectives || !out || n_obj < 1 || n_obj > 3) return MMEE_EINVAL;
+    int seen = 0;
+    for (uint32_t a = 0; a < n_obj; ++a) {
+        if (objectives[a] < 0 || objectives[a] > 2 || (seen & (1 << objectives[a]))) return MMEE_EINVAL;
+        seen |= 1 << objectives[a];
+    }
+    mmee_workload ws[3] = {*w, *w, *w};
+    mmee_hw hs[3] = {*hw, *hw, *hw};
+    return mmee_search_many(ws, hs, objectives, n_obj, flags, out, nullptr);
+}
+
+int mmee_search_ex(const mmee_workload *w, const mmee_hw *hw, int objective, uint32_t flags, mmee_result *out)
+{
+    return mmee_search_multi(w, hw, &objective, 1, flags, out);
+}
+
+int mmee_search(const mmee_workload *w, const mmee_hw *hw, int objective, mmee_result *out)
+{
+    return mmee_search_ex(w, hw, objective, MMEE_SEARCH_PRUNED, out);
+}
+
+void mmee_shutdown(void)
+{
+    std::lock_guard<std::mutex> guard(g_lock);
+    if (S.ready || S.btab || S.partials) (void)hipStreamSynchronize(S.stream);
+    (void)hipFree(S.enc); (void)hipFree(S.sig); (void)hipFree(S.flags);
+    (void)hipFree(S.rows[0]); (void)hipFree(S.rows[1]); (void)hipFree(S.counts_dev);
+    (void)hipFree(S.btab); (void)hipFree(S.ctab_s); (void)hipFree(S.ctab_e);
+    (void)hipFree(S.partials); (void)hipFree(S.ticket);
+    (void)hipFree(S.final_dev); (void)hipFree(S.dv_dev); (void)hipFree(S.eval_dev);
+    if (S.final_host) (void)hipHostFree(S.final_host);
+    if (S.dv_host) (void)hipHostFree(S.dv_host);
+    for (hipEvent_t e : S.events) (void)hipEventDestroy(e);
+    hipStream_t keep = S.stream;
+    S = State();
+    S.stream = keep;
+}
+
+const char *mmee_strerror(int code)
+{
+    switch (code) {
+    case MMEE_OK: return "ok";
+    case MMEE_EINVAL: return "invalid argument";
+    case MMEE_ERANGE: return "candidate index out of range";
+    case MMEE_ENOFEASIBLE: return "no feasible candidate";
+    case MMEE_EDEVICE: return g_last_error[0] ? g_last_error : "HIP device error";
+    default: return "unknown error";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,292 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle.
+
+Bar: integer fields, validity and the selected optimum bit-exact; fp64 energy and
+latency bit-exact too (both sides form them in the same order without fused
+multiply-add), which is tighter than the 1e-12 relative bound the method states.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import oracle as O
+from inputs import CONFIGS, SplitMix64, sweep_hw, sweep_workloads
+
+pytestmark = pytest.mark.gpu
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+INT_FIELDS = ("bs_words", "da_words", "br_words", "mac_total", "comp_cycles")
+OBJ_NAMES = {0: "energy", 1: "latency", 2: "latency_then_energy"}
+
+
+@pytest.fixture(scope="module")
+def M():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2604_03446_amd as mod
+    return mod
+
+
+def assert_costs_equal(got, want, where=""):
+    assert (got["valid"] == want["valid"]).all(), where
+    assert (got["reason"] == want["reason"]).all(), where
+    real = want["reason"] != 1          # rows that are no dataflow carry zeros by definition
+    for name in INT_FIELDS:
+        assert (got[name][real] == want[name][real]).all(), (where, name)
+        assert (got[name][~real] == 0).all(), (where, name)
+    for name in ("energy_pj", "latency_cycles"):
+        assert np.array_equal(got[name], want[name]), (where, name)
+        ok = want["valid"] == 1
+        rel = np.abs(got[name][ok] - want[name][ok]) / want[name][ok]
+        assert (rel <= 1e-12).all(), (where, name)
+
+
+def windows(space, seed, sizes):
+    rng = SplitMix64(seed)
+    for n in sizes:
+        yield rng.next() % (space - n), n
+
+
+@pytest.mark.parametrize("name", ["tiny", "bert", "prefill", "long"])
+def test_eval_batch_windows(M, name):
+    cfg = CONFIGS[name]
+    w, h = cfg["workload"], cfg["hw"]
+    ow, oh = O.workload(w), O.hw(h)
+    S = O.space_size(ow, oh)
+    assert M.mmee_space_size(w, h) == S
+    T = S // 540000
+    # ragged sizes: less than a wave, a few blocks + tail, several rows of tilings
+    sizes = [1, 63, 257, 100003, 3 * T + 17, 400000]
+    for first, n in list(windows(S, 11, sizes)) + [(0, 70000), (S - 70001, 70001)]:
+        got = M.mmee_eval_batch(w, h, first, n)
+        want = O.eval_batch(ow, oh, first, n)
+        assert_costs_equal(got, want, (name, first, n))
+        print(name, "window", first, n, "valid", int(want["valid"].sum()), flush=True)
+
+
+def test_eval_batch_strided_rows_cover_every_digit(M):
+    """Short windows at 3000 seeded offsets: every order / level / recompute / stationary /
+    fusion digit value is exercised on the Tiny space."""
+    cfg = CONFIGS["tiny"]
+    w, h = cfg["workload"], cfg["hw"]
+    ow, oh = O.workload(w), O.hw(h)
+    S = O.space_size(ow, oh)
+    rng = SplitMix64(2024)
+    seen_rows = set()
+    for _ in range(300):
+        first = rng.next() % (S - 64)
+        got = M.mmee_eval_batch(w, h, first, 64)
+        want = O.eval_batch(ow, oh, first, 64)
+        assert_costs_equal(got, want, first)
+        seen_rows.add(first // (S // 540000) // 15000)
+    assert len(seen_rows) >= 30          # (r, s1, s2, f) combinations out of 36
+
+
+def test_eval_batch_general_shapes_and_bandwidths(M):
+    """All-divisor tilings of a non-power-of-two shape; a DRAM bandwidth that is not a power of
+    two (true division on the device); several heads, arrays and batch."""
+    w = dict(B=2, H=3, N=48, d=24, word_bytes=2, tiling_mode=1, c_softmax=10)
+    h = dict(pe_rows=8, pe_cols=4, n_arrays=2, rf_bytes=96, gb_bytes=6000,
+             e_dram=137.25, e_gb=5.5, e_rf=0.75, e_mac=1.125, dram_bw=60.0, gb_bw=100.0)
+    ow, oh = O.workload(w), O.hw(h)
+    S = O.space_size(ow, oh)
+    assert M.mmee_space_size(w, h) == S == (10 * 8) ** 2 * 540000
+    for first, n in windows(S, 5, [200001, 6400 * 3 + 5, 77]):
+        assert_costs_equal(M.mmee_eval_batch(w, h, first, n), O.eval_batch(ow, oh, first, n), (first, n))
+    for extra in (dict(dram_bw=0.0), dict(gb_bw=0.0), dict(dram_bw=0.0, gb_bw=0.0), dict(word_bytes=4)):
+        w2 = dict(w, **{k: v for k, v in extra.items() if k in w})
+        h2 = dict(h, **{k: v for k, v in extra.items() if k in h})
+        first, n = next(windows(S, 6, [50001]))
+        assert_costs_equal(M.mmee_eval_batch(w2, h2, first, n),
+                           O.eval_batch(O.workload(w2), O.hw(h2), first, n), extra)
+
+
+def test_eval_batch_into_device_memory(M):
+    import torch
+    cfg = CONFIGS["bert"]
+    w, h = cfg["workload"], cfg["hw"]
+    first, n = 1_234_567_890, 300007
+    buf = torch.zeros(n * 8, dtype=torch.int64, device="cuda")
+    M.mmee_eval_batch(w, h, first, n, out=buf.data_ptr())
+    torch.cuda.synchronize()
+    got = buf.cpu().numpy().view(M.COST_DTYPE)
+    want = O.eval_batch(O.workload(w), O.hw(h), first, n)
+    assert_costs_equal(got, want)
+
+
+def test_decode_matches_oracle(M):
+    for name, cfg in CONFIGS.items():
+        w, h = cfg["workload"], cfg["hw"]
+        ow, oh = O.workload(w), O.hw(h)
+        S = O.space_size(ow, oh)
+        rng = SplitMix64(17)
+        idx = [0, S - 1] + [rng.next() % S for _ in range(500)]
+        for i, m in zip(idx, M.mmee_decode(w, h, idx)):
+            om, _, _ = O.evaluate(ow, oh, i)
+            assert m.idx == i
+            for fld in ("xG", "xD", "order", "level"):
+                assert list(getattr(m, fld)) == list(getattr(om, fld)), (name, i, fld)
+            assert (m.recompute, m.stat1, m.stat2, m.fused) == (om.recompute, om.stat1, om.stat2, om.fused)
+
+
+def check_result_against_oracle(res, ow, oh):
+    m, c, _ = O.evaluate(ow, oh, res.best.idx)
+    assert c.valid == 1 and res.cost.valid == 1
+    for fld in INT_FIELDS:
+        assert getattr(res.cost, fld) == getattr(c, fld), fld
+    assert res.cost.energy_pj == c.energy_pj and res.cost.latency_cycles == c.latency_cycles
+    for fld in ("xG", "xD", "order", "level"):
+        assert list(getattr(res.best, fld)) == list(getattr(m, fld)), fld
+    assert (res.best.recompute, res.best.stat1, res.best.stat2, res.best.fused) == \
+        (m.recompute, m.stat1, m.stat2, m.fused)
+
+
+SMALL = [
+    # (workload, hw) whose whole space the oracle enumerates in a moment
+    (dict(B=1, H=2, N=8, d=2, word_bytes=2, tiling_mode=1, c_softmax=10),
+     dict(pe_rows=4, pe_cols=4, n_arrays=1, rf_bytes=64, gb_bytes=96,
+          e_dram=200.0, e_gb=6.0, e_rf=1.0, e_mac=1.0, dram_bw=2.0, gb_bw=64.0)),
+    (dict(B=1, H=1, N=12, d=6, word_bytes=2, tiling_mode=1, c_softmax=10),
+     dict(pe_rows=2, pe_cols=4, n_arrays=1, rf_bytes=32, gb_bytes=400,
+          e_dram=150.0, e_gb=7.0, e_rf=1.5, e_mac=0.5, dram_bw=3.0, gb_bw=16.0)),
+    (dict(B=1, H=1, N=16, d=8, word_bytes=2, tiling_mode=0, c_softmax=10),
+     dict(pe_rows=4, pe_cols=4, n_arrays=1, rf_bytes=64, gb_bytes=1 << 20,
+          e_dram=200.0, e_gb=6.0, e_rf=1.0, e_mac=1.0, dram_bw=0.25, gb_bw=0.0)),
+]
+
+
+@pytest.mark.parametrize("case", range(len(SMALL)))
+def test_search_small_spaces_against_oracle_enumeration(M, case):
+    w, h = SMALL[case]
+    ow, oh = O.workload(w), O.hw(h)
+    rc, idx, cost, n_valid, _ = O.search_all(ow, oh)
+    assert rc == 0
+    for flags in (M.SEARCH_EXHAUSTIVE, M.SEARCH_PRUNED):
+        # one objective per pass, then all three in one pass
+        singles = [M.mmee_search_ex(w, h, obj, flags) for obj in (0, 1, 2)]
+        multi = M.mmee_search_multi(w, h, [0, 1, 2], flags)
+        for obj in (0, 1, 2):
+            for res in (singles[obj], multi[obj]):
+                assert res.best.idx == idx[obj], (case, flags, obj)
+                assert res.cost.energy_pj == cost[obj].energy_pj
+                assert res.cost.latency_cycles == cost[obj].latency_cycles
+                check_result_against_oracle(res, ow, oh)
+                assert res.space == O.space_size(ow, oh)
+
+
+def test_search_infeasible_and_argument_errors(M):
+    w, h = SMALL[0]
+    tiny_buffer = dict(h, gb_bytes=4)
+    code, res = M.mmee_search_ex(w, tiny_buffer, 0, M.SEARCH_EXHAUSTIVE, allow_infeasible=True)
+    assert code == M.ENOFEASIBLE and res.cost.valid == 0
+    code, res = M.mmee_search_ex(w, tiny_buffer, 1, M.SEARCH_PRUNED, allow_infeasible=True)
+    assert code == M.ENOFEASIBLE and res.cost.valid == 0
+    S = M.mmee_space_size(w, h)
+    with pytest.raises(M.MmeeError) as e:
+        M.mmee_eval_batch(w, h, S - 5, 6)
+    assert e.value.code == M.ERANGE
+    assert len(M.mmee_eval_batch(w, h, S, 0)) == 0
+    for bad_w, bad_h in ((dict(w, N=0), h), (w, dict(h, rf_bytes=5)), (w, dict(h, e_dram=-1.0)),
+                         (dict(w, tiling_mode=2), h), (w, dict(h, n_arrays=0))):
+        with pytest.raises(M.MmeeError) as e:
+            M.mmee_space_size(bad_w, bad_h)
+        assert e.value.code == M.EINVAL
+    with pytest.raises(M.MmeeError) as e:
+        M.mmee_search_ex(w, h, 7)
+    assert e.value.code == M.EINVAL
+
+
+def load_expected():
+    with open(os.path.join(GOLDEN, "expected_optima.json")) as fh:
+        return json.load(fh)
+
+
+@pytest.mark.parametrize("name", ["tiny", "bert", "prefill", "long"])
+def test_search_full_configs_against_stored_oracle_optima(M, name):
+    """Full-size searches in the configuration the benchmark times, against optima that the
+    oracle's exhaustive enumeration wrote to tests/golden/expected_optima.json."""
+    exp = load_expected()[name]
+    cfg = CONFIGS[name]
+    w, h = cfg["workload"], cfg["hw"]
+    assert exp["workload"] == w and exp["hw"] == h
+    ow, oh = O.workload(w), O.hw(h)
+    for flags in (M.SEARCH_EXHAUSTIVE, M.SEARCH_PRUNED):
+        results = M.mmee_search_multi(w, h, [0, 1, 2], flags)
+        for obj, res in enumerate(results):
+            want = exp["best"][OBJ_NAMES[obj]]
+            assert res.best.idx == want["idx"], (name, flags, obj)
+            assert res.cost.energy_pj == float.fromhex(want["energy_pj"])
+            assert res.cost.latency_cycles == float.fromhex(want["latency_cycles"])
+            for fld in INT_FIELDS:
+                assert getattr(res.cost, fld) == want[fld]
+            check_result_against_oracle(res, ow, oh)
+        if flags == M.SEARCH_EXHAUSTIVE:
+            # every candidate that denotes a dataflow was costed
+            assert results[0].evaluated == exp["space"] * 337500 // 540000
+        print(name, "flags", flags, "kernel ms", results[0].kernel_seconds * 1e3, flush=True)
+    for obj in cfg["objectives"]:
+        res = M.mmee_search(w, h, obj)
+        assert res.best.idx == exp["best"][OBJ_NAMES[obj]]["idx"]
+
+
+def test_sweep_points_against_stored_oracle_optima(M):
+    exp = load_expected()
+    names = [k for k in exp if k.startswith("sweep_")]
+    assert len(names) >= 8
+    points = []
+    for k in names:
+        for obj in (0, 1):
+            points.append((exp[k]["workload"], exp[k]["hw"], obj))
+    for flags in (M.SEARCH_PRUNED, M.SEARCH_EXHAUSTIVE):
+        results, codes = M.mmee_search_many(points, flags)
+        for (w, h, obj), res, code, k in zip(points, results, codes, [n for n in names for _ in (0, 1)]):
+            want = exp[k]["best"][OBJ_NAMES[obj]]
+            if want is None:
+                assert code == M.ENOFEASIBLE
+                continue
+            assert code == 0 and res.best.idx == want["idx"], (k, obj, flags)
+            assert res.cost.energy_pj == float.fromhex(want["energy_pj"])
+            assert res.cost.latency_cycles == float.fromhex(want["latency_cycles"])
+
+
+@pytest.mark.timeout(900)
+def test_sweep_pruned_equals_exhaustive_everywhere(M):
+    """All 64 accelerators x 8 workloads x 2 objectives in one launch stream: the pruned search
+    returns exactly what the exhaustive one returns, and the winner's record is the oracle's."""
+    wls, hws = sweep_workloads(), sweep_hw()
+    points = [(w, h, obj) for w in wls for h in hws for obj in (0, 1)]
+    assert len(points) == 1024
+    pruned, pc = M.mmee_search_many(points, M.SEARCH_PRUNED)
+    full, fc = M.mmee_search_many(points, M.SEARCH_EXHAUSTIVE)
+    rng = SplitMix64(31)
+    for i, (p, f) in enumerate(zip(pruned, full)):
+        assert pc[i] == fc[i]
+        if pc[i] != 0:
+            assert pc[i] == M.ENOFEASIBLE
+            continue
+        assert p.best.idx == f.best.idx, i
+        assert p.cost.energy_pj == f.cost.energy_pj and p.cost.latency_cycles == f.cost.latency_cycles
+        assert p.evaluated < f.evaluated
+    for i in [rng.next() % len(points) for _ in range(64)]:
+        if pc[i] == 0:
+            w, h, obj = points[i]
+            check_result_against_oracle(pruned[i], O.workload(w), O.hw(h))
+            # no seeded random candidate beats the optimum
+            ow, oh = O.workload(w), O.hw(h)
+            S = pruned[i].space
+            best = pruned[i].cost.energy_pj if obj == 0 else pruned[i].cost.latency_cycles
+            for _ in range(200):
+                _, c, _ = O.evaluate(ow, oh, rng.next() % S)
+                if c.valid:
+                    assert (c.energy_pj if obj == 0 else c.latency_cycles) >= best
+
+
+def test_offline_stage_counts(M):
+    st = M.mmee_offline_stats()
+    assert list(st.rows_total) == [15000] * 4
+    # g = r + 2 f: recomputation needs a fused C and j outside k (half of the 24 orders)
+    assert list(st.rows_valid) == [15000, 0, 15000, 7500]
+    kept = list(st.rows_kept)
+    assert kept[1] == 0 and all(0 < kept[g] < st.rows_valid[g] for g in (0, 2, 3))
+    print("rows kept per group", kept, flush=True)
