@@ -145,7 +145,6 @@ __global__ void k_build_rows(uint4 *enc, uint32_t *sig)
     uint32_t nest2 = prefix_mask | (1u << DI) | (1u << DL) | (1u << DJ);
 
     const int own[5][2] = {{DI, DK}, {DK, DL}, {DI, DL}, {DL, DJ}, {DI, DJ}};
-    uint8_t sel[16];
     uint32_t bs_sel[5];
     for (int X = 0; X < 5; ++X) {
         if (X == OC) continue;
@@ -153,33 +152,38 @@ __global__ void k_build_rows(uint4 *enc, uint32_t *sig)
     }
     // C holds every tile the producer finishes before the consumer starts (fused), else one tile
     bs_sel[OC] = f ? ((uint32_t)!((prefix_mask >> DI) & 1) | ((uint32_t)!((prefix_mask >> DL) & 1) << 1)) : 0u;
-    for (int X = 0; X < 5; ++X) sel[X] = (uint8_t)(ENT_BS + 4 * X + bs_sel[X]);
+    // retained operands (buffered at an inter-tile loop) also occupy the other operator's buffer
     const int ret[4] = {OA, OB, OD, OE};
-    uint32_t tau_bits = 0;
+    uint32_t tau_bits = 0, ret_sel[4];
     for (int y = 0; y < 4; ++y) {
         bool tau = lvl[ret[y]] >= 1;
         tau_bits |= (uint32_t)tau << y;
-        sel[5 + y] = tau ? sel[ret[y]] : (uint8_t)ENT_ZERO;
+        ret_sel[y] = tau ? bs_sel[ret[y]] : 4u;
     }
     uint32_t da_sel[4];
     da_sel[0] = dram_selector(pos, nest1, prefix_mask, DI, DK, DL, DJ, lvl[OA]);
     da_sel[1] = dram_selector(pos, nest1, prefix_mask, DK, DL, DI, DJ, lvl[OB]);
     da_sel[2] = dram_selector(pos, nest2, prefix_mask, DL, DJ, DI, DK, lvl[OD]);
     da_sel[3] = dram_selector(pos, nest2, prefix_mask, DI, DJ, DK, DL, lvl[OE]);
-    for (int y = 0; y < 4; ++y) sel[9 + y] = (uint8_t)(ENT_DA + 4 * y + da_sel[y]);
-    uint32_t dac_sel = 0;
-    if (f) {
-        sel[13] = (uint8_t)ENT_ZERO;                          // DA_C = 0 (Sec. V-C)
-    } else {
+    uint32_t dac_sel = 0, dac_opt = 4;                        // fused: DA_C = 0 (Sec. V-C)
+    if (!f) {
         uint32_t out_k = dram_selector(pos, nest1, prefix_mask, DI, DL, DK, DJ, 0) & 1;
         uint32_t in_j = (dram_selector(pos, nest2, prefix_mask, DI, DL, DK, DJ, 0) >> 1) & 1;
-        dac_sel = out_k | (in_j << 1);
-        sel[13] = (uint8_t)(ENT_DAC + dac_sel);
+        dac_sel = dac_opt = out_k | (in_j << 1);
     }
     // recomputation must revisit C tiles (j outside k) and needs an on-chip C
     bool valid = !(r && (!f || pos[DK] > pos[DJ]));
+    uint8_t sel[16];
+    sel[0] = (uint8_t)(ENT_BS_AB + bs_sel[OA] + 4 * bs_sel[OB]);
+    sel[1] = (uint8_t)(ENT_RET_DE + ret_sel[2] + 5 * ret_sel[3]);
+    sel[2] = (uint8_t)(ENT_BS_C + bs_sel[OC]);
+    sel[3] = (uint8_t)(ENT_BS_DE + bs_sel[OD] + 4 * bs_sel[OE]);
+    sel[4] = (uint8_t)(ENT_RET_AB + ret_sel[0] + 5 * ret_sel[1]);
+    sel[5] = (uint8_t)(ENT_DA_AB + da_sel[0] + 4 * da_sel[1]);
+    sel[6] = (uint8_t)(ENT_DA_DE + da_sel[2] + 4 * da_sel[3]);
+    sel[7] = (uint8_t)(ENT_DA_C + dac_opt);
     sel[ROW_FLAGS] = (uint8_t)((valid ? 1u : 0u) | (r << 1) | (f << 2));
-    sel[15] = 0;
+    for (int k = ROW_FLAGS + 1; k < 16; ++k) sel[k] = 0;
 
     uint4 packed;
     packed.x = sel[0] | (sel[1] << 8) | (sel[2] << 16) | ((uint32_t)sel[3] << 24);
@@ -286,32 +290,44 @@ __global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__
         D[q] = dv.X[q] / (uint32_t)G[q];
     }
     const uint64_t tp = mc.tpad;
+    const uint64_t BH = (uint64_t)mc.BH;
     const int own[5][2] = {{DI, DK}, {DK, DL}, {DI, DL}, {DL, DJ}, {DI, DJ}};
+    uint64_t bs[5][5];                                       // option 4 = absent
     for (int X = 0; X < 5; ++X) {
         uint64_t tile = G[own[X][0]] * G[own[X][1]];
         uint64_t d0 = D[own[X][0]], d1 = D[own[X][1]];
-        btab[(ENT_BS + 4 * X + 0) * tp + t] = (double)tile;
-        btab[(ENT_BS + 4 * X + 1) * tp + t] = (double)(tile * d0);
-        btab[(ENT_BS + 4 * X + 2) * tp + t] = (double)(tile * d1);
-        btab[(ENT_BS + 4 * X + 3) * tp + t] = (double)(tile * d0 * d1);
+        bs[X][0] = tile; bs[X][1] = tile * d0; bs[X][2] = tile * d1; bs[X][3] = tile * d0 * d1;
+        bs[X][4] = 0;
     }
-    btab[ENT_ZERO * tp + t] = 0.0;
     const int da_own[4][2] = {{DI, DK}, {DK, DL}, {DL, DJ}, {DI, DJ}};
     const int da_other[4][2] = {{DL, DJ}, {DI, DJ}, {DI, DK}, {DK, DL}};
+    uint64_t da[4][4];
     for (int y = 0; y < 4; ++y) {
         uint64_t whole = (uint64_t)dv.X[da_own[y][0]] * dv.X[da_own[y][1]];
         uint64_t n0 = D[da_other[y][0]], n1 = D[da_other[y][1]];
-        btab[(ENT_DA + 4 * y + 0) * tp + t] = (double)whole;
-        btab[(ENT_DA + 4 * y + 1) * tp + t] = (double)(whole * n0);
-        btab[(ENT_DA + 4 * y + 2) * tp + t] = (double)(whole * n1);
-        btab[(ENT_DA + 4 * y + 3) * tp + t] = (double)(whole * n0 * n1);
+        da[y][0] = whole; da[y][1] = whole * n0; da[y][2] = whole * n1; da[y][3] = whole * n0 * n1;
     }
-    {
-        uint64_t whole = (uint64_t)dv.X[DI] * dv.X[DL];
-        for (uint32_t s = 0; s < 4; ++s) {
-            uint64_t spill = (s & 1) ? D[DK] : 1, fetch = (s & 2) ? D[DJ] : 1;
-            btab[(ENT_DAC + s) * tp + t] = (double)(whole * (spill + fetch + 2));
+    for (int b = 0; b < 4; ++b)
+        for (int a = 0; a < 4; ++a) {
+            btab[(ENT_BS_AB + a + 4 * b) * tp + t] = (double)(bs[OA][a] + bs[OB][b]);
+            btab[(ENT_BS_DE + a + 4 * b) * tp + t] = (double)(bs[OD][a] + bs[OE][b]);
+            btab[(ENT_DA_AB + a + 4 * b) * tp + t] = (double)(BH * (da[0][a] + da[1][b]));
+            btab[(ENT_DA_DE + a + 4 * b) * tp + t] = (double)(BH * (da[2][a] + da[3][b]));
         }
+    for (int b = 0; b < 5; ++b)
+        for (int a = 0; a < 5; ++a) {
+            btab[(ENT_RET_DE + a + 5 * b) * tp + t] = (double)(bs[OD][a] + bs[OE][b]);
+            btab[(ENT_RET_AB + a + 5 * b) * tp + t] = (double)(bs[OA][a] + bs[OB][b]);
+        }
+    for (int c = 0; c < 4; ++c) btab[(ENT_BS_C + c) * tp + t] = (double)bs[OC][c];
+    {
+        // unfused C: spilled by Op1, fetched by Op2, plus one softmax pass over S and P
+        uint64_t whole = (uint64_t)dv.X[DI] * dv.X[DL];
+        for (uint32_t c = 0; c < 4; ++c) {
+            uint64_t spill = (c & 1) ? D[DK] : 1, fetch = (c & 2) ? D[DJ] : 1;
+            btab[(ENT_DA_C + c) * tp + t] = (double)(BH * whole * (spill + fetch + 2));
+        }
+        btab[(ENT_DA_C + 4) * tp + t] = 0.0;
     }
 
     // stationary-mode dependent part: buffer<->RF words and cycles per tile stage
@@ -321,7 +337,6 @@ __global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__
         tile_cost(G[DI], G[DL], G[DJ], s, mc.pe_rows, mc.pe_cols, mc.g_words, br2[s], cy2[s]);
     }
     const uint64_t I = dv.X[DI], K = dv.X[DK], L = dv.X[DL], J = dv.X[DJ];
-    const uint64_t BH = (uint64_t)mc.BH;
     for (uint32_t r = 0; r < 2; ++r) {
         uint64_t rho = r ? D[DJ] : 1;                         // producer repeated per j tile (Sec. V-D)
         uint64_t st1 = rho * D[DI] * D[DK] * D[DL], st2 = D[DI] * D[DL] * D[DJ];
@@ -381,10 +396,12 @@ __device__ __forceinline__ void eval_candidate(const EvalArgs &a, uint32_t row, 
 #pragma unroll
     for (int k = 0; k < NSEL; ++k) v[k] = a.btab[sel_of(e, k) * tp + t];
     // Eq. (1), (2), (4)
-    double bs1 = v[0] + v[1] + v[2] + v[7] + v[8];
-    double bs2 = v[2] + v[3] + v[4] + v[5] + v[6];
+    double bs1 = v[0] + v[2] + v[1];
+    double bs2 = v[3] + v[2] + v[4];
     double bs = fmax(bs1, bs2);
-    double da = v[9] + v[10] + v[11] + v[12] + v[13];        // Eq. (7)
+    const double BH = a.mc.BH;
+    double t_dram_words = v[5] + v[6] + v[7];                // B*H * Eq. (7)
+    double da = t_dram_words / BH;                           // exact: the tables hold multiples of B*H
     uint32_t c9 = s1 + 3 * s2;
     uint64_t br = a.ctab_e[((uint64_t)r * NCE + c9) * tp + t];
     uint64_t cyc = a.ctab_e[((uint64_t)r * NCE + 9 + c9) * tp + t];
@@ -397,8 +414,6 @@ __device__ __forceinline__ void eval_candidate(const EvalArgs &a, uint32_t row, 
         c.valid = 0; c.reason = 2;
         return;
     }
-    const double BH = a.mc.BH;
-    double t_dram_words = BH * da;
     double t_gb_words = BH * (da + (double)br);
     double t_rf = BH * 3.0 * (double)mac;
     double t_mac = BH * ((double)mac + (double)a.mc.c_softmax * (double)sm);
@@ -497,11 +512,15 @@ struct SearchArgs {
 };
 
 constexpr int TC = 64;           // tilings per block
-constexpr int SEARCH_THREADS = 256;
+constexpr int SEARCH_THREADS = 512;
+
+// keeps the optimiser from sinking a select below the operations that consume its result
+__device__ __forceinline__ void pin(double &x) { asm("" : "+v"(x)); }
 
 // MASK: bit0 energy, bit1 latency, bit2 latency-then-energy.
-// EXACT_K: the DRAM bandwidth is 0 or a power of two, so words*word/bw is one exact multiply.
-template <int MASK, bool EXACT_K>
+// FAST: DRAM bandwidth is 0 or a power of two and the array count is a power of two, so the
+// DRAM latency term is one exact multiply of the table value; otherwise it is divided out.
+template <int MASK, bool FAST>
 __global__ __launch_bounds__(SEARCH_THREADS) void k_search(SearchArgs a)
 {
     __shared__ double tab[TC * NENT];
@@ -533,6 +552,8 @@ __global__ __launch_bounds__(SEARCH_THREADS) void k_search(SearchArgs a)
     for (int k = 0; k < NSEL; ++k) off[k] = sel_of(e, k);
 
     const double inf = pos_inf();
+    // a lane without a row never passes the capacity test
+    const double cap = live ? a.mc.cap_words : -1.0;
     double bestE[9], bestL[9], bestLE_l[9], bestLE_e[9];
     uint32_t codeE[9], codeL[9], codeLE[9];
 #pragma unroll
@@ -548,16 +569,17 @@ __global__ __launch_bounds__(SEARCH_THREADS) void k_search(SearchArgs a)
 #pragma unroll
         for (int k = 0; k < NSEL; ++k) v[k] = row_tab[off[k]];
         // Eq. (1), (2), (4) and the capacity mask
-        double bs1 = v[0] + v[1] + v[2] + v[7] + v[8];
-        double bs2 = v[2] + v[3] + v[4] + v[5] + v[6];
-        bool ok = live && fmax(bs1, bs2) <= a.mc.cap_words;
-        double da = v[9] + v[10] + v[11] + v[12] + v[13];    // Eq. (7)
-        double dram_words = a.mc.BH * da;
+        double bs1 = v[0] + v[2] + v[1];
+        double bs2 = v[3] + v[2] + v[4];
+        bool ok = fmax(bs1, bs2) <= cap;
+        double dram_words = v[5] + v[6] + v[7];               // B*H * Eq. (7)
         double e_dram_part = ok ? a.mc.e_dram * dram_words : inf;
         double l_dram;
-        if constexpr (EXACT_K) l_dram = a.mc.c_lat * (da * a.mc.dram_k);
-        else l_dram = a.mc.c_lat * ((da * a.mc.word) / a.mc.dram_bw);
+        if constexpr (FAST) l_dram = dram_words * a.mc.dram_k;
+        else l_dram = a.mc.dram_bw > 0.0 ? a.mc.c_lat * (((dram_words / a.mc.BH) * a.mc.word) / a.mc.dram_bw) : 0.0;
         l_dram = ok ? l_dram : inf;
+        pin(e_dram_part);
+        pin(l_dram);
         const double *cs = cs_base + (uint64_t)tl * 2 * NCS;  // wave-uniform: scalar loads
         const double e_rf_part = cs[18], e_mac_part = cs[19];
 #pragma unroll

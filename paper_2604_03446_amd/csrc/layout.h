@@ -19,23 +19,27 @@ enum { DI = 0, DK = 1, DL = 2, DJ = 3 };          // loop dimensions
 enum { OA = 0, OB = 1, OC = 2, OD = 3, OE = 4 };  // operands
 
 // ---- entries of the per-tiling table ("B side") ------------------------------
-// BS_X options: tile_X * {1, d0, d1, d0*d1}, d0/d1 = inter-tile counts of X's two own dims
-constexpr int ENT_BS = 0;        // + 4*X + sel, X = A,B,C,D,E
-constexpr int ENT_ZERO = 20;     // 0 (operand not retained, or fused C in DRAM terms)
-// DA_X options: |X| * {1, n0, n1, n0*n1}, n0/n1 = inter-tile counts of the two dims X does not own
-constexpr int ENT_DA = 21;       // + 4*Y + sel, Y = A,B,D,E
-// unfused C: |C| * ((k_D or 1) + (j_D or 1) + 2)
-constexpr int ENT_DAC = 37;      // + sel
-constexpr int NENT = 41;
+// An operand's buffer size is tile_X * {1, d0, d1, d0*d1} (d0/d1 = inter-tile counts of its two
+// own dims, option index = bit0 | bit1 << 1); its DRAM traffic is B*H*|X| * {1, n0, n1, n0*n1}
+// (n0/n1 = inter-tile counts of the two dims it does not own).  Option 4 stands for "absent"
+// (operand not retained / fused C).  Terms that are only ever added are stored as pair sums so
+// that one lookup serves two operands:
+constexpr int ENT_BS_AB = 0;      // BS_A[a] + BS_B[b]              index a + 4 b        (Eq. (1))
+constexpr int ENT_BS_DE = 16;     // BS_D[a] + BS_E[b]                                   (Eq. (2))
+constexpr int ENT_RET_DE = 32;    // tau_D BS_D[a] + tau_E BS_E[b]  index a + 5 b, a,b in 0..4
+constexpr int ENT_RET_AB = 57;    // tau_A BS_A[a] + tau_B BS_B[b]
+constexpr int ENT_BS_C = 82;      // BS_C[c]
+constexpr int ENT_DA_AB = 86;     // B*H*(DA_A[a] + DA_B[b])        index a + 4 b        (Eq. (7))
+constexpr int ENT_DA_DE = 102;    // B*H*(DA_D[a] + DA_E[b])
+constexpr int ENT_DA_C = 118;     // B*H*DA_C[c], c in 0..4: |C| * ((k_D or 1) + (j_D or 1) + 2), or 0
+constexpr int NENT = 123;
 
-// ---- one encoded row ("Q side"): 14 selectors + flags, 16 bytes ---------------
-// sel[0..4]   BS_A BS_B BS_C BS_D BS_E
-// sel[5..8]   tau_X * BS_X for X = A,B,D,E   (ENT_ZERO when the operand is not retained)
-// sel[9..12]  DA_A DA_B DA_D DA_E
-// sel[13]     DA_C
-// sel[14]     flags: bit0 row denotes a dataflow, bit1 r, bit2 f
-constexpr int NSEL = 14;
-constexpr int ROW_FLAGS = 14;
+// ---- one encoded row ("Q side"): 8 selectors + flags in 16 bytes ----------------
+// sel[0] BS_AB  sel[1] RET_DE  sel[2] BS_C  sel[3] BS_DE  sel[4] RET_AB
+// sel[5] DA_AB  sel[6] DA_DE   sel[7] DA_C  (absolute entry numbers)
+// sel[8] flags: bit0 row denotes a dataflow, bit1 r, bit2 f
+constexpr int NSEL = 8;
+constexpr int ROW_FLAGS = 8;
 
 constexpr uint32_t ROWS_PER_GROUP = 15000;   // 5^4 levels * 24 orders
 constexpr uint32_t N_GROUPS = 4;             // g = r + 2 f
@@ -65,7 +69,7 @@ struct ModelConst {
     double word;        // word_bytes
     double e_dram, e_gb, e_rf, e_mac;
     double dram_bw, gb_bw;
-    double dram_k;      // word / dram_bw when that is exact (power-of-two bandwidth), else unused
+    double dram_k;      // word / dram_bw / n_arrays when that is exact (powers of two), else unused
     uint32_t pe_rows, pe_cols, g_words, c_softmax;
     uint32_t T, tpad;
 };

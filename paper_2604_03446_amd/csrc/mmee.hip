@@ -118,9 +118,13 @@ int make_plan(const mmee_workload *w, const mmee_hw *hw, Plan &p)
     mc.word = (double)w->word_bytes;
     mc.e_dram = hw->e_dram; mc.e_gb = hw->e_gb; mc.e_rf = hw->e_rf; mc.e_mac = hw->e_mac;
     mc.dram_bw = hw->dram_bw; mc.gb_bw = hw->gb_bw;
+    // with a power-of-two bandwidth and array count, (B*H/n) * (words*word/bw) is the B*H-scaled
+    // table value times one exactly representable constant
     int ex = 0;
-    p.exact_k = hw->dram_bw == 0.0 || std::frexp(hw->dram_bw, &ex) == 0.5;
-    mc.dram_k = hw->dram_bw > 0.0 ? mc.word / hw->dram_bw : 0.0;
+    const bool bw_pow2 = hw->dram_bw == 0.0 || std::frexp(hw->dram_bw, &ex) == 0.5;
+    const bool n_pow2 = (hw->n_arrays & (hw->n_arrays - 1)) == 0;
+    p.exact_k = bw_pow2 && n_pow2;
+    mc.dram_k = hw->dram_bw > 0.0 ? mc.word / hw->dram_bw / (double)hw->n_arrays : 0.0;
     mc.pe_rows = hw->pe_rows; mc.pe_cols = hw->pe_cols;
     mc.g_words = hw->rf_bytes / w->word_bytes / 2;
     mc.c_softmax = w->c_softmax;
