@@ -12,7 +12,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmmee.so")
+LIB_PATH = os.environ.get("MMEE_LIB") or os.path.join(_HERE, "libmmee.so")
 
 OBJ_ENERGY, OBJ_LATENCY, OBJ_LATENCY_THEN_ENERGY = 0, 1, 2
 SEARCH_PRUNED, SEARCH_EXHAUSTIVE = 0, 1

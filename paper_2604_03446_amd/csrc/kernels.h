@@ -501,18 +501,45 @@ struct SearchArgs {
     uint32_t group_cnt[4];
     uint32_t rb_start[5];        // first row-block of each group, [4] = total
     uint32_t n_chunks;           // tiling chunks
+    uint32_t n_items;            // row-blocks x tiling chunks
     const double *btab;
     const double *ctab_s;
     ModelConst mc;
     Key *partials;               // [gridDim.x][3]
     uint32_t *ticket;
+    uint32_t *work_counter;
     FinalRecord *final_out;      // [3]
     const uint64_t *ctab_e;
     DivTable const *dv;          // device copy, for the final record's mapping
 };
 
-constexpr int TC = 64;           // tilings per block
-constexpr int SEARCH_THREADS = 512;
+#ifndef MMEE_TC
+#define MMEE_TC 64
+#endif
+#ifndef MMEE_THREADS
+#define MMEE_THREADS 512
+#endif
+#ifndef MMEE_PIPE
+#define MMEE_PIPE 1
+#endif
+#define MMEE_STR_(x) #x
+#define MMEE_PRAGMA_(x) _Pragma(MMEE_STR_(x))
+#ifdef MMEE_UNROLL
+#define MMEE_LOOP_UNROLL MMEE_PRAGMA_(unroll MMEE_UNROLL)
+#else
+#define MMEE_LOOP_UNROLL
+#endif
+#ifndef MMEE_BLOCKS_PER_CU
+#define MMEE_BLOCKS_PER_CU 2
+#endif
+constexpr int BLOCKS_PER_CU = MMEE_BLOCKS_PER_CU;   // what LDS (63 KB per block) lets a CU hold
+constexpr int TC = MMEE_TC;      // tilings per block
+constexpr int SEARCH_THREADS = MMEE_THREADS;
+
+// Read-only tables that the kernel never writes are read through the constant address space, so
+// that wave-uniform reads become scalar loads even next to atomics and inline assembly.
+typedef const double __attribute__((address_space(4))) *ConstF64;
+__device__ __forceinline__ ConstF64 as_constant(const double *p) { return (ConstF64)p; }
 
 // keeps the optimiser from sinking a select below the operations that consume its result
 __device__ __forceinline__ void pin(double &x) { asm("" : "+v"(x)); }
@@ -520,136 +547,190 @@ __device__ __forceinline__ void pin(double &x) { asm("" : "+v"(x)); }
 // MASK: bit0 energy, bit1 latency, bit2 latency-then-energy.
 // FAST: DRAM bandwidth is 0 or a power of two and the array count is a power of two, so the
 // DRAM latency term is one exact multiply of the table value; otherwise it is divided out.
+//
+// Persistent blocks (as many as the chip holds) pull work items from a global counter.  One item =
+// SEARCH_THREADS rows of one (r, f) group (lane = row) x TC consecutive tilings (loop).
 template <int MASK, bool FAST>
-__global__ __launch_bounds__(SEARCH_THREADS) void k_search(SearchArgs a)
+__global__ __launch_bounds__(SEARCH_THREADS, (MASK == 5 || MASK == 6 || MASK == 7) ? 2 : 4) void k_search(SearchArgs a)
 {
-    __shared__ double tab[TC * NENT];
+    __shared__ double tab[(TC + 1) * NENT];      // one spare row: the loop reads one tiling ahead
     __shared__ Key wave_best[3][SEARCH_THREADS / 64];
     __shared__ uint32_t is_last;
 
-    const uint32_t chunk = blockIdx.x % a.n_chunks;
-    const uint32_t rb = blockIdx.x / a.n_chunks;
-    uint32_t g = 0;
-    while (g < 3 && rb >= a.rb_start[g + 1]) ++g;
-    const uint32_t slot = (rb - a.rb_start[g]) * SEARCH_THREADS + threadIdx.x;
-    const bool live = slot < a.group_cnt[g];
-    const uint32_t dfrow = a.rows[a.group_off[g] + (live ? slot : 0)];
-    const uint4 e = a.enc[dfrow];
-    const uint32_t r = g & 1;
-
-    const uint32_t t0 = chunk * TC;
-    const uint32_t nt = min((uint32_t)TC, a.mc.T - t0);
-
-    // stage this chunk of the boundary-side tables: global entry-major -> LDS tiling-major
-    for (uint32_t i = threadIdx.x; i < NENT * TC; i += SEARCH_THREADS) {
-        uint32_t ent = i / TC, tl = i % TC;
-        if (tl < nt) tab[tl * NENT + ent] = a.btab[(uint64_t)ent * a.mc.tpad + t0 + tl];
-    }
-    __syncthreads();
-
-    uint32_t off[NSEL];
-#pragma unroll
-    for (int k = 0; k < NSEL; ++k) off[k] = sel_of(e, k);
-
     const double inf = pos_inf();
-    // a lane without a row never passes the capacity test
-    const double cap = live ? a.mc.cap_words : -1.0;
-    double bestE[9], bestL[9], bestLE_l[9], bestLE_e[9];
-    uint32_t codeE[9], codeL[9], codeLE[9];
-#pragma unroll
-    for (int c9 = 0; c9 < 9; ++c9) {
-        bestE[c9] = bestL[c9] = bestLE_l[c9] = bestLE_e[c9] = inf;
-        codeE[c9] = codeL[c9] = codeLE[c9] = 0;
-    }
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // wave_best[o][w]: best key of wave w over all items so far; only wave w touches its slot
+    if (lane < 3) { wave_best[lane][wave].p = inf; wave_best[lane][wave].s = 0.0; wave_best[lane][wave].idx = ~0ull; }
 
-    const double *cs_base = a.ctab_s + ((uint64_t)t0 * 2 + r) * NCS;
-    for (uint32_t tl = 0; tl < nt; ++tl) {
-        const double *row_tab = tab + tl * NENT;
-        double v[NSEL];
+    // work items are handed out through a global counter; the first one is the block's own number.
+    // Thread 0 asks for the next item while the current one is being processed.
+    __shared__ uint32_t s_item;
+    uint32_t upcoming = blockIdx.x;
+    while (true) {
+        if (threadIdx.x == 0) s_item = upcoming;
+        __syncthreads();                          // also: the previous item's LDS readers are done
+        const uint32_t item = s_item;
+        if (item >= a.n_items) break;
+        if (threadIdx.x == 0)
+            upcoming = gridDim.x + __hip_atomic_fetch_add(a.work_counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t chunk = item % a.n_chunks;
+        const uint32_t rb = item / a.n_chunks;
+        uint32_t g = 0;
+        while (g < 3 && rb >= a.rb_start[g + 1]) ++g;
+        const uint32_t slot = (rb - a.rb_start[g]) * SEARCH_THREADS + threadIdx.x;
+        const bool live = slot < a.group_cnt[g];
+        const uint32_t dfrow = a.rows[a.group_off[g] + (live ? slot : 0)];
+        const uint4 e = a.enc[dfrow];
+        const uint32_t r = g & 1;
+        const uint32_t t0 = chunk * TC;
+        const uint32_t nt = min((uint32_t)TC, a.mc.T - t0);
+
+        // stage this chunk of the boundary-side tables: global entry-major -> LDS tiling-major
+        for (uint32_t i = threadIdx.x; i < NENT * TC; i += SEARCH_THREADS) {
+            uint32_t ent = i / TC, tl = i % TC;
+            if (tl < nt) tab[tl * NENT + ent] = a.btab[(uint64_t)ent * a.mc.tpad + t0 + tl];
+        }
+        __syncthreads();
+
+        uint32_t off[NSEL];
 #pragma unroll
-        for (int k = 0; k < NSEL; ++k) v[k] = row_tab[off[k]];
-        // Eq. (1), (2), (4) and the capacity mask
-        double bs1 = v[0] + v[2] + v[1];
-        double bs2 = v[3] + v[2] + v[4];
-        bool ok = fmax(bs1, bs2) <= cap;
-        double dram_words = v[5] + v[6] + v[7];               // B*H * Eq. (7)
-        double e_dram_part = ok ? a.mc.e_dram * dram_words : inf;
-        double l_dram;
-        if constexpr (FAST) l_dram = dram_words * a.mc.dram_k;
-        else l_dram = a.mc.dram_bw > 0.0 ? a.mc.c_lat * (((dram_words / a.mc.BH) * a.mc.word) / a.mc.dram_bw) : 0.0;
-        l_dram = ok ? l_dram : inf;
-        pin(e_dram_part);
-        pin(l_dram);
-        const double *cs = cs_base + (uint64_t)tl * 2 * NCS;  // wave-uniform: scalar loads
-        const double e_rf_part = cs[18], e_mac_part = cs[19];
+        for (int k = 0; k < NSEL; ++k) off[k] = sel_of(e, k);
+
+        // a lane without a row never passes the capacity test
+        const double cap = live ? a.mc.cap_words : -1.0;
+        double bestE[9], bestL[9], bestLE_l[9], bestLE_e[9];
+        uint32_t codeE[9], codeL[9], codeLE[9];
 #pragma unroll
         for (int c9 = 0; c9 < 9; ++c9) {
-            double gb_words = dram_words + cs[c9];
-            double en = e_dram_part + a.mc.e_gb * gb_words;
-            en = en + e_rf_part;
-            en = en + e_mac_part;
-            double lat = fmax(l_dram, cs[9 + c9]);
+            bestE[c9] = bestL[c9] = bestLE_l[c9] = bestLE_e[c9] = inf;
+            codeE[c9] = codeL[c9] = codeLE[c9] = 0;
+        }
+
+        // Software pipeline: table values (LDS) and the per-tiling constants (scalar loads) of the
+        // next tiling are requested while the current one is costed.  The constants come in two
+        // halves (combinations 0..4 / 5..8) so that each half is reloaded as soon as it is spent.
+        ConstF64 cs_base = as_constant(a.ctab_s + ((uint64_t)t0 * 2 + r) * NCS);
+        double v[NSEL];
+#if MMEE_PIPE
+#pragma unroll
+        for (int k = 0; k < NSEL; ++k) v[k] = tab[off[k]];
+#endif
+        double gbA[5], latA[5], gbB[4], latB[4], e_rf_part, e_mac_part;
+#pragma unroll
+        for (int c = 0; c < 5; ++c) { gbA[c] = cs_base[c]; latA[c] = cs_base[9 + c]; }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { gbB[c] = cs_base[5 + c]; latB[c] = cs_base[14 + c]; }
+        e_rf_part = cs_base[18]; e_mac_part = cs_base[19];
+        ConstF64 cs_cur = cs_base;
+        ConstF64 const cs_end = cs_base + (uint64_t)nt * 2 * NCS;
+
+        for (uint32_t tl = 0; tl < nt; ++tl) {
+#if !MMEE_PIPE
+            {
+                const double *row_tab = tab + tl * NENT;
+#pragma unroll
+                for (int k = 0; k < NSEL; ++k) v[k] = row_tab[off[k]];
+            }
+#endif
+            // Eq. (1), (2), (4) and the capacity mask
+            double bs1 = v[0] + v[2] + v[1];
+            double bs2 = v[3] + v[2] + v[4];
+            bool ok = fmax(bs1, bs2) <= cap;
+            double dram_words = v[5] + v[6] + v[7];           // B*H * Eq. (7)
+            double e_dram_part = ok ? a.mc.e_dram * dram_words : inf;
+            double l_dram;
+            if constexpr (FAST) l_dram = dram_words * a.mc.dram_k;
+            else l_dram = a.mc.dram_bw > 0.0 ? a.mc.c_lat * (((dram_words / a.mc.BH) * a.mc.word) / a.mc.dram_bw) : 0.0;
+            l_dram = ok ? l_dram : inf;
+            pin(e_dram_part);
+            pin(l_dram);
+#if MMEE_PIPE
+            {
+                const double *next_tab = tab + (tl + 1) * NENT;
+#pragma unroll
+                for (int k = 0; k < NSEL; ++k) v[k] = next_tab[off[k]];
+            }
+#endif
+            ConstF64 cs_next = cs_cur + 2 * NCS;              // stay inside the table on the last turn
+            cs_next = cs_next < cs_end ? cs_next : cs_cur;
+            cs_cur = cs_next;
+            const double e_rf_now = e_rf_part, e_mac_now = e_mac_part;
+
+            auto cost_one = [&](int c9, double gb_part, double lat_part) {
+                double gb_words = dram_words + gb_part;
+                double en = e_dram_part + a.mc.e_gb * gb_words;
+                en = en + e_rf_now;
+                en = en + e_mac_now;
+                double lat = fmax(l_dram, lat_part);
+                if constexpr (MASK & 1) {
+                    bool lt = en < bestE[c9];
+                    bestE[c9] = fmin(bestE[c9], en);
+                    codeE[c9] = lt ? tl : codeE[c9];
+                }
+                if constexpr (MASK & 2) {
+                    bool lt = lat < bestL[c9];
+                    bestL[c9] = fmin(bestL[c9], lat);
+                    codeL[c9] = lt ? tl : codeL[c9];
+                }
+                if constexpr (MASK & 4) {
+                    bool lt = lat < bestLE_l[c9] || (lat == bestLE_l[c9] && en < bestLE_e[c9]);
+                    bestLE_l[c9] = lt ? lat : bestLE_l[c9];
+                    bestLE_e[c9] = lt ? en : bestLE_e[c9];
+                    codeLE[c9] = lt ? tl : codeLE[c9];
+                }
+            };
+#pragma unroll
+            for (int c = 0; c < 5; ++c) cost_one(c, gbA[c], latA[c]);
+#pragma unroll
+            for (int c = 0; c < 5; ++c) { gbA[c] = cs_next[c]; latA[c] = cs_next[9 + c]; }
+            e_rf_part = cs_next[18]; e_mac_part = cs_next[19];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) cost_one(5 + c, gbB[c], latB[c]);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) { gbB[c] = cs_next[5 + c]; latB[c] = cs_next[14 + c]; }
+        }
+
+        // fold the nine per-combination minima of this lane (ascending combination = ascending
+        // index, so a strict < keeps the lowest index), reduce over the wave, keep the wave's best
+        const uint32_t f = g >> 1;
+        const uint64_t row_base = (uint64_t)(dfrow % ROWS_PER_GROUP) + 15000ull * r + 270000ull * f;
+        Key mine[3];
+#pragma unroll
+        for (int o = 0; o < 3; ++o) { mine[o].p = inf; mine[o].s = 0.0; mine[o].idx = ~0ull; }
+#pragma unroll
+        for (int c9 = 0; c9 < 9; ++c9) {
+            const uint64_t combo_rows = row_base + 30000ull * (c9 % 3) + 90000ull * (c9 / 3);
             if constexpr (MASK & 1) {
-                bool lt = en < bestE[c9];
-                bestE[c9] = fmin(bestE[c9], en);
-                codeE[c9] = lt ? tl : codeE[c9];
+                if (bestE[c9] < mine[0].p) {
+                    mine[0].p = bestE[c9];
+                    mine[0].idx = (uint64_t)(t0 + codeE[c9]) + (uint64_t)a.mc.T * combo_rows;
+                }
             }
             if constexpr (MASK & 2) {
-                bool lt = lat < bestL[c9];
-                bestL[c9] = fmin(bestL[c9], lat);
-                codeL[c9] = lt ? tl : codeL[c9];
+                if (bestL[c9] < mine[1].p) {
+                    mine[1].p = bestL[c9];
+                    mine[1].idx = (uint64_t)(t0 + codeL[c9]) + (uint64_t)a.mc.T * combo_rows;
+                }
             }
             if constexpr (MASK & 4) {
-                bool lt = lat < bestLE_l[c9] || (lat == bestLE_l[c9] && en < bestLE_e[c9]);
-                bestLE_l[c9] = lt ? lat : bestLE_l[c9];
-                bestLE_e[c9] = lt ? en : bestLE_e[c9];
-                codeLE[c9] = lt ? tl : codeLE[c9];
+                if (bestLE_l[c9] < mine[2].p || (bestLE_l[c9] == mine[2].p && bestLE_e[c9] < mine[2].s)) {
+                    mine[2].p = bestLE_l[c9];
+                    mine[2].s = bestLE_e[c9];
+                    mine[2].idx = (uint64_t)(t0 + codeLE[c9]) + (uint64_t)a.mc.T * combo_rows;
+                }
             }
+        }
+#pragma unroll
+        for (int o = 0; o < 3; ++o) {
+            if (!((MASK >> o) & 1)) continue;
+            // a lane that found nothing feasible must not win a tie between infinities
+            if (!(mine[o].p < inf)) { mine[o].s = 0.0; mine[o].idx = ~0ull; }
+            Key k = wave_min(mine[o]);
+            if (lane == 0 && key_less(k, wave_best[o][wave])) wave_best[o][wave] = k;
         }
     }
-
-    // fold the nine per-combination minima of this lane; ascending combination = ascending index
-    const uint32_t f = g >> 1;
-    const uint64_t row_base = (uint64_t)(dfrow % ROWS_PER_GROUP) + 15000ull * r + 270000ull * f;
-    Key mine[3];
-#pragma unroll
-    for (int o = 0; o < 3; ++o) { mine[o].p = inf; mine[o].s = 0.0; mine[o].idx = ~0ull; }
-#pragma unroll
-    for (int c9 = 0; c9 < 9; ++c9) {
-        const uint64_t combo_rows = 30000ull * (c9 % 3) + 90000ull * (c9 / 3);
-        if constexpr (MASK & 1) {
-            if (bestE[c9] < mine[0].p) {
-                mine[0].p = bestE[c9];
-                mine[0].idx = (uint64_t)(t0 + codeE[c9]) + (uint64_t)a.mc.T * (row_base + combo_rows);
-            }
-        }
-        if constexpr (MASK & 2) {
-            if (bestL[c9] < mine[1].p) {
-                mine[1].p = bestL[c9];
-                mine[1].idx = (uint64_t)(t0 + codeL[c9]) + (uint64_t)a.mc.T * (row_base + combo_rows);
-            }
-        }
-        if constexpr (MASK & 4) {
-            if (bestLE_l[c9] < mine[2].p || (bestLE_l[c9] == mine[2].p && bestLE_e[c9] < mine[2].s)) {
-                mine[2].p = bestLE_l[c9];
-                mine[2].s = bestLE_e[c9];
-                mine[2].idx = (uint64_t)(t0 + codeLE[c9]) + (uint64_t)a.mc.T * (row_base + combo_rows);
-            }
-        }
-    }
-    // a lane that found nothing feasible must not win a tie between infinities
-#pragma unroll
-    for (int o = 0; o < 3; ++o)
-        if (!(mine[o].p < inf)) { mine[o].p = inf; mine[o].s = 0.0; mine[o].idx = ~0ull; }
 
     // wave -> block -> grid
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int o = 0; o < 3; ++o) {
-        if (!((MASK >> o) & 1)) continue;
-        Key k = wave_min(mine[o]);
-        if (lane == 0) wave_best[o][wave] = k;
-    }
     __syncthreads();
     if (threadIdx.x == 0) {
 #pragma unroll
@@ -718,7 +799,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void k_search(SearchArgs a)
         __builtin_memcpy(mbuf, &m, sizeof(mmee_mapping));
         for (int q = 0; q < 7; ++q) fr->map[q] = mbuf[q];
     }
-    if (threadIdx.x == 0) *a.ticket = 0;          // ready for the next launch on this stream
+    if (threadIdx.x == 0) { *a.ticket = 0; *a.work_counter = 0; }   // ready for the next launch on this stream
 }
 
 }  // namespace mmee

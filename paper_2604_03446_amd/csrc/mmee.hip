@@ -52,6 +52,7 @@ struct State {
     std::vector<hipEvent_t> events;
     void *eval_dev = nullptr;
     size_t eval_cap = 0;
+    uint32_t resident_blocks = 512;
 } S;
 
 // ---- argument checking and the per-call plan ---------------------------------
@@ -143,14 +144,20 @@ int ensure_ready()
         std::snprintf(g_last_error, sizeof(g_last_error), "no HIP device");
         return MMEE_EDEVICE;
     }
+    {
+        int dev = 0, cus = 0;
+        HIP_TRY(hipGetDevice(&dev));
+        HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        S.resident_blocks = (uint32_t)std::max(cus, 1) * BLOCKS_PER_CU;
+    }
     HIP_TRY(hipMalloc(&S.enc, sizeof(uint4) * N_DFROWS));
     HIP_TRY(hipMalloc(&S.sig, sizeof(uint32_t) * N_DFROWS));
     HIP_TRY(hipMalloc(&S.flags, N_DFROWS));
     HIP_TRY(hipMalloc(&S.rows[0], sizeof(uint32_t) * N_DFROWS));
     HIP_TRY(hipMalloc(&S.rows[1], sizeof(uint32_t) * N_DFROWS));
     HIP_TRY(hipMalloc(&S.counts_dev, sizeof(uint32_t) * 8));
-    HIP_TRY(hipMalloc(&S.ticket, sizeof(uint32_t)));
-    HIP_TRY(hipMemset(S.ticket, 0, sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&S.ticket, 2 * sizeof(uint32_t)));        // [0] finish ticket, [1] work counter
+    HIP_TRY(hipMemset(S.ticket, 0, 2 * sizeof(uint32_t)));
     HIP_TRY(hipMemset(S.rows[0], 0, sizeof(uint32_t) * N_DFROWS));
     HIP_TRY(hipMemset(S.rows[1], 0, sizeof(uint32_t) * N_DFROWS));
     // offline stage: encode every (order, levels, r, f) row, prune, compact
@@ -251,11 +258,14 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     a.n_chunks = (uint32_t)((p.T + TC - 1) / TC);
     a.btab = S.btab; a.ctab_s = S.ctab_s; a.ctab_e = S.ctab_e;
     a.mc = p.mc;
-    const uint64_t nblocks = (uint64_t)rb * a.n_chunks;
-    if (nblocks == 0 || nblocks > 0x7fffffffull) return MMEE_EINVAL;
+    const uint64_t n_items = (uint64_t)rb * a.n_chunks;
+    if (n_items == 0 || n_items > 0x7fffffffull) return MMEE_EINVAL;
+    a.n_items = (uint32_t)n_items;
+    // persistent blocks: as many as the chip holds at once (LDS allows two per CU)
+    const uint64_t nblocks = std::min<uint64_t>(n_items, (uint64_t)S.resident_blocks);
     rc = ensure_partials(nblocks);
     if (rc) return rc;
-    a.partials = S.partials; a.ticket = S.ticket;
+    a.partials = S.partials; a.ticket = S.ticket; a.work_counter = S.ticket + 1;
     a.final_out = S.final_dev + 3 * slot;
     a.dv = S.dv_dev + slot;
     S.dv_host[slot] = p.dv;
