@@ -68,6 +68,12 @@ __device__ __forceinline__ Key wave_min(Key k)
     return k;
 }
 
+// Read-only tables that the kernel never writes are read through the constant address space, so
+// that wave-uniform reads become scalar loads even next to atomics and inline assembly.
+template <class T> using ConstPtr = const T __attribute__((address_space(4))) *;
+typedef ConstPtr<double> ConstF64;
+template <class T> __device__ __forceinline__ ConstPtr<T> as_constant(const T *p) { return (ConstPtr<T>)p; }
+
 // ---------------------------------------------------------------------------
 // offline stage: the query side
 
@@ -313,6 +319,8 @@ __global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__
             btab[(ENT_BS_DE + a + 4 * b) * tp + t] = (double)(bs[OD][a] + bs[OE][b]);
             btab[(ENT_DA_AB + a + 4 * b) * tp + t] = (double)(BH * (da[0][a] + da[1][b]));
             btab[(ENT_DA_DE + a + 4 * b) * tp + t] = (double)(BH * (da[2][a] + da[3][b]));
+            btab[(ENT_DA_AB + ENT_RAW_DA + a + 4 * b) * tp + t] = (double)(da[0][a] + da[1][b]);
+            btab[(ENT_DA_DE + ENT_RAW_DA + a + 4 * b) * tp + t] = (double)(da[2][a] + da[3][b]);
         }
     for (int b = 0; b < 5; ++b)
         for (int a = 0; a < 5; ++a) {
@@ -326,8 +334,10 @@ __global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__
         for (uint32_t c = 0; c < 4; ++c) {
             uint64_t spill = (c & 1) ? D[DK] : 1, fetch = (c & 2) ? D[DJ] : 1;
             btab[(ENT_DA_C + c) * tp + t] = (double)(BH * whole * (spill + fetch + 2));
+            btab[(ENT_DA_C + ENT_RAW_DA + c) * tp + t] = (double)(whole * (spill + fetch + 2));
         }
         btab[(ENT_DA_C + 4) * tp + t] = 0.0;
+        btab[(ENT_DA_C + ENT_RAW_DA + 4) * tp + t] = 0.0;
     }
 
     // stationary-mode dependent part: buffer<->RF words and cycles per tile stage
@@ -352,11 +362,14 @@ __global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__
             cs[9 + c9] = mc.c_lat * fmax((double)cyc, t_gb);
             ctab_e[((uint64_t)r * NCE + c9) * tp + t] = br;
             ctab_e[((uint64_t)r * NCE + 9 + c9) * tp + t] = cyc;
+            ctab_e[((uint64_t)r * NCE + 20 + c9) * tp + t] = (uint64_t)__double_as_longlong(cs[9 + c9]);
         }
         cs[18] = mc.e_rf * (double)(BH * 3 * mac);
         cs[19] = mc.e_mac * (double)(BH * (mac + (uint64_t)mc.c_softmax * sm));
         ctab_e[((uint64_t)r * NCE + 18) * tp + t] = mac;
         ctab_e[((uint64_t)r * NCE + 19) * tp + t] = sm;
+        ctab_e[((uint64_t)r * NCE + 29) * tp + t] = (uint64_t)__double_as_longlong(cs[18]);
+        ctab_e[((uint64_t)r * NCE + 30) * tp + t] = (uint64_t)__double_as_longlong(cs[19]);
     }
 }
 
@@ -376,6 +389,9 @@ __device__ __forceinline__ uint32_t sel_of(const uint4 &e, int k)
     return (w >> (8 * (k & 3))) & 0xFF;
 }
 
+// One candidate from the global tables.  The tables are read-only while this runs, so they are
+// read through the constant address space: with a wave-uniform row the selectors land in scalar
+// registers and each table read is one load at (uniform base + lane's tiling).
 __device__ __forceinline__ void eval_candidate(const EvalArgs &a, uint32_t row, uint32_t t, mmee_cost &c)
 {
     // row = levels/order (15000) + 15000 r + 30000 s1 + 90000 s2 + 270000 f
@@ -383,7 +399,9 @@ __device__ __forceinline__ void eval_candidate(const EvalArgs &a, uint32_t row, 
     uint32_t r = hi & 1; hi >>= 1;
     uint32_t s1 = hi % 3; hi /= 3;
     uint32_t s2 = hi % 3; uint32_t f = hi / 3;
-    uint4 e = a.enc[lo + ROWS_PER_GROUP * (r + 2 * f)];
+    ConstPtr<uint32_t> ew = as_constant(reinterpret_cast<const uint32_t *>(a.enc + lo + ROWS_PER_GROUP * (r + 2 * f)));
+    uint4 e;
+    e.x = ew[0]; e.y = ew[1]; e.z = ew[2]; e.w = ew[3];
     uint32_t flags = sel_of(e, ROW_FLAGS);
     if (!(flags & 1)) {
         c.bs_words = c.da_words = c.br_words = c.mac_total = c.comp_cycles = 0;
@@ -392,21 +410,23 @@ __device__ __forceinline__ void eval_candidate(const EvalArgs &a, uint32_t row, 
         return;
     }
     const uint64_t tp = a.mc.tpad;
+    ConstPtr<double> bt = as_constant(a.btab);
+    ConstPtr<uint64_t> ce = as_constant(a.ctab_e) + (uint64_t)r * NCE * tp;
     double v[NSEL];
 #pragma unroll
-    for (int k = 0; k < NSEL; ++k) v[k] = a.btab[sel_of(e, k) * tp + t];
-    // Eq. (1), (2), (4)
-    double bs1 = v[0] + v[2] + v[1];
-    double bs2 = v[3] + v[2] + v[4];
-    double bs = fmax(bs1, bs2);
-    const double BH = a.mc.BH;
-    double t_dram_words = v[5] + v[6] + v[7];                // B*H * Eq. (7)
-    double da = t_dram_words / BH;                           // exact: the tables hold multiples of B*H
+    for (int k = 0; k < 5; ++k) v[k] = bt[sel_of(e, k) * tp + t];
+#pragma unroll
+    for (int k = 5; k < NSEL; ++k) v[k] = bt[(sel_of(e, k) + ENT_RAW_DA) * tp + t];
     uint32_t c9 = s1 + 3 * s2;
-    uint64_t br = a.ctab_e[((uint64_t)r * NCE + c9) * tp + t];
-    uint64_t cyc = a.ctab_e[((uint64_t)r * NCE + 9 + c9) * tp + t];
-    uint64_t mac = a.ctab_e[((uint64_t)r * NCE + 18) * tp + t];
-    uint64_t sm = a.ctab_e[((uint64_t)r * NCE + 19) * tp + t];
+    uint64_t br = ce[(uint64_t)c9 * tp + t];
+    uint64_t cyc = ce[(uint64_t)(9 + c9) * tp + t];
+    uint64_t mac = ce[18ull * tp + t];
+    double lat_part = __longlong_as_double((long long)ce[(uint64_t)(20 + c9) * tp + t]);
+    double e_rf_part = __longlong_as_double((long long)ce[29ull * tp + t]);
+    double e_mac_part = __longlong_as_double((long long)ce[30ull * tp + t]);
+    // Eq. (1), (2), (4), (7)
+    double bs = fmax(v[0] + v[2] + v[1], v[3] + v[2] + v[4]);
+    double da = v[5] + v[6] + v[7];
     c.bs_words = (uint64_t)bs; c.da_words = (uint64_t)da; c.br_words = br;
     c.mac_total = mac; c.comp_cycles = cyc;
     if (bs > a.mc.cap_words) {
@@ -414,18 +434,17 @@ __device__ __forceinline__ void eval_candidate(const EvalArgs &a, uint32_t row, 
         c.valid = 0; c.reason = 2;
         return;
     }
-    double t_gb_words = BH * (da + (double)br);
-    double t_rf = BH * 3.0 * (double)mac;
-    double t_mac = BH * ((double)mac + (double)a.mc.c_softmax * (double)sm);
-    double en = a.mc.e_dram * t_dram_words;
-    en = en + a.mc.e_gb * t_gb_words;
-    en = en + a.mc.e_rf * t_rf;
-    en = en + a.mc.e_mac * t_mac;
-    double l_comp = (double)cyc;
-    double l_dram = a.mc.dram_bw > 0.0 ? (da * a.mc.word) / a.mc.dram_bw : 0.0;
-    double l_gb = a.mc.gb_bw > 0.0 ? ((double)br * a.mc.word) / a.mc.gb_bw : 0.0;
+    const double BH = a.mc.BH;
+    double en = a.mc.e_dram * (BH * da);
+    en = en + a.mc.e_gb * (BH * (da + (double)br));
+    en = en + e_rf_part;
+    en = en + e_mac_part;
+    // c * max(max(comp, dram), gb) = max(c * dram, c * max(comp, gb)): scaling by c >= 0 and max commute exactly
+    double l_dram;
+    if (a.mc.bw_pow2) l_dram = da * a.mc.eval_k;
+    else l_dram = (da * a.mc.word) / a.mc.dram_bw;
     c.energy_pj = en;
-    c.latency_cycles = a.mc.c_lat * fmax(fmax(l_comp, l_dram), l_gb);
+    c.latency_cycles = fmax(a.mc.c_lat * l_dram, lat_part);
     c.valid = 1; c.reason = 0;
 }
 
@@ -459,24 +478,39 @@ __global__ void k_decode(DivTable dv, uint32_t T, const uint64_t *__restrict__ i
 }
 
 // One candidate per thread, a block = 256 consecutive tilings of one row.  Records leave through
-// LDS so that every store instruction of a wave writes one contiguous kilobyte.
+// LDS so that every store instruction of a wave writes one contiguous kilobyte; the stores are
+// streaming (nothing reads the records back on the device).
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+#ifndef MMEE_EVAL_NT
+#define MMEE_EVAL_NT 1
+#endif
+
+// Work unit = 64 consecutive tilings of one index row, one wave each (4 units per block).
 __global__ __launch_bounds__(256) void k_eval_batch(EvalArgs a, uint64_t first_idx, uint64_t n, uint32_t row_first,
-                                                    uint32_t blocks_per_row, uint4 *__restrict__ out)
+                                                    uint32_t units_per_row, uint32_t n_units, v4u *__restrict__ out)
 {
-    __shared__ uint4 stage[4][256];                           // [wave][64 records x 4 pieces]
-    const uint32_t row = row_first + blockIdx.x / blocks_per_row;
-    const uint32_t t = (blockIdx.x % blocks_per_row) * 256 + threadIdx.x;
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ v4u stage[4][256];                             // [wave][64 records x 4 pieces]
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform on purpose
+    const uint32_t unit = blockIdx.x * 4 + wave;
+    if (unit >= n_units) return;
+    const uint32_t row = row_first + unit / units_per_row;
+    const uint32_t t = (unit % units_per_row) * 64 + lane;
     const uint64_t T = a.mc.T;
     const uint64_t idx = (uint64_t)row * T + t;
     const bool on = t < T && idx >= first_idx && idx - first_idx < n;
-    mmee_cost c;
     if (on) {
+        mmee_cost c;
         eval_candidate(a, row, t, c);
-        const uint4 *src = reinterpret_cast<const uint4 *>(&c);
+        const v4u *src = reinterpret_cast<const v4u *>(&c);
 #pragma unroll
         for (int k = 0; k < 4; ++k) stage[wave][lane * 4 + k] = src[k];
     }
+    // only this wave touches stage[wave]: order its LDS writes before its LDS reads
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const unsigned long long mask = __ballot(on);
     // the wave's 64 records are consecutive in the output; lane L moves piece (L & 3) of
     // record 16 k + L / 4 on pass k
@@ -486,7 +520,11 @@ __global__ __launch_bounds__(256) void k_eval_batch(EvalArgs a, uint64_t first_i
         uint32_t rec = 16 * k + (lane >> 2);
         if ((mask >> rec) & 1ull) {
             uint64_t o = wave_first + rec - first_idx;
+#if MMEE_EVAL_NT
+            __builtin_nontemporal_store(stage[wave][rec * 4 + (lane & 3)], &out[o * 4 + (lane & 3)]);
+#else
             out[o * 4 + (lane & 3)] = stage[wave][rec * 4 + (lane & 3)];
+#endif
         }
     }
 }
@@ -535,11 +573,6 @@ struct SearchArgs {
 constexpr int BLOCKS_PER_CU = MMEE_BLOCKS_PER_CU;   // what LDS (63 KB per block) lets a CU hold
 constexpr int TC = MMEE_TC;      // tilings per block
 constexpr int SEARCH_THREADS = MMEE_THREADS;
-
-// Read-only tables that the kernel never writes are read through the constant address space, so
-// that wave-uniform reads become scalar loads even next to atomics and inline assembly.
-typedef const double __attribute__((address_space(4))) *ConstF64;
-__device__ __forceinline__ ConstF64 as_constant(const double *p) { return (ConstF64)p; }
 
 // keeps the optimiser from sinking a select below the operations that consume its result
 __device__ __forceinline__ void pin(double &x) { asm("" : "+v"(x)); }

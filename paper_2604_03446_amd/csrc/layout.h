@@ -32,7 +32,10 @@ constexpr int ENT_BS_C = 82;      // BS_C[c]
 constexpr int ENT_DA_AB = 86;     // B*H*(DA_A[a] + DA_B[b])        index a + 4 b        (Eq. (7))
 constexpr int ENT_DA_DE = 102;    // B*H*(DA_D[a] + DA_E[b])
 constexpr int ENT_DA_C = 118;     // B*H*DA_C[c], c in 0..4: |C| * ((k_D or 1) + (j_D or 1) + 2), or 0
-constexpr int NENT = 123;
+constexpr int NENT = 123;          // entries the search kernel stages into LDS
+// the same DRAM terms without the B*H factor, read by the per-candidate kernel only
+constexpr int ENT_RAW_DA = 37;     // raw entry = scaled entry + 37
+constexpr int NENT_ALL = 160;
 
 // ---- one encoded row ("Q side"): 8 selectors + flags in 16 bytes ----------------
 // sel[0] BS_AB  sel[1] RET_DE  sel[2] BS_C  sel[3] BS_DE  sel[4] RET_AB
@@ -51,8 +54,10 @@ constexpr uint64_t ROWS_PER_TILING = 540000; // * 9 stationary combinations
 //   [9..17] c_lat * max(comp(combo), BR*w/gb_bw)
 //   [18]    e_rf * T_rf      [19] e_mac * T_mac
 constexpr int NCS = 20;
-// per (r, field, tiling) raw integers read by the eval kernel: br[9], comp[9], mac, softmax elems
-constexpr int NCE = 20;
+// per (r, field, tiling) values read by the per-candidate kernel, 64 bits each:
+//   [0..8] BR (u64)   [9..17] cycles (u64)   [18] MAC (u64)   [19] softmax elements (u64)
+//   [20..28] c_lat * max(cycles, BR*w/gb_bw) (fp64)   [29] e_rf * T_rf (fp64)   [30] e_mac * T_mac (fp64)
+constexpr int NCE = 31;
 
 constexpr int MAXDIV = 240;      // divisors per dimension (720720 has 240)
 
@@ -70,6 +75,8 @@ struct ModelConst {
     double e_dram, e_gb, e_rf, e_mac;
     double dram_bw, gb_bw;
     double dram_k;      // word / dram_bw / n_arrays when that is exact (powers of two), else unused
+    double eval_k;      // word / dram_bw when the bandwidth is a power of two (or 0), else unused
+    uint32_t bw_pow2;   // the DRAM bandwidth is 0 or a power of two
     uint32_t pe_rows, pe_cols, g_words, c_softmax;
     uint32_t T, tpad;
 };

@@ -126,6 +126,8 @@ int make_plan(const mmee_workload *w, const mmee_hw *hw, Plan &p)
     const bool n_pow2 = (hw->n_arrays & (hw->n_arrays - 1)) == 0;
     p.exact_k = bw_pow2 && n_pow2;
     mc.dram_k = hw->dram_bw > 0.0 ? mc.word / hw->dram_bw / (double)hw->n_arrays : 0.0;
+    mc.eval_k = hw->dram_bw > 0.0 ? mc.word / hw->dram_bw : 0.0;
+    mc.bw_pow2 = bw_pow2 ? 1u : 0u;
     mc.pe_rows = hw->pe_rows; mc.pe_cols = hw->pe_cols;
     mc.g_words = hw->rf_bytes / w->word_bytes / 2;
     mc.c_softmax = w->c_softmax;
@@ -180,7 +182,7 @@ int ensure_tilings(uint64_t tpad)
     if (tpad <= S.tiling_cap) return MMEE_OK;
     if (S.btab) { HIP_TRY(hipStreamSynchronize(S.stream)); (void)hipFree(S.btab); (void)hipFree(S.ctab_s); (void)hipFree(S.ctab_e); }
     S.btab = nullptr; S.ctab_s = nullptr; S.ctab_e = nullptr; S.tiling_cap = 0;
-    HIP_TRY(hipMalloc(&S.btab, sizeof(double) * NENT * tpad));
+    HIP_TRY(hipMalloc(&S.btab, sizeof(double) * NENT_ALL * tpad));
     HIP_TRY(hipMalloc(&S.ctab_s, sizeof(double) * 2 * NCS * tpad));
     HIP_TRY(hipMalloc(&S.ctab_e, sizeof(uint64_t) * 2 * NCE * tpad));
     S.tiling_cap = tpad;
@@ -410,8 +412,10 @@ int mmee_eval_batch(const mmee_workload *w, const mmee_hw *hw, uint64_t first_id
 
     EvalArgs ea;
     ea.enc = S.enc; ea.btab = S.btab; ea.ctab_e = S.ctab_e; ea.mc = p.mc;
-    const uint32_t bpr = (uint32_t)((p.T + 255) / 256);
-    const uint64_t CHUNK = 1ull << 24;          // records per launch: 1 GiB of output
+    const uint32_t upr = (uint32_t)((p.T + 63) / 64);      // 64-tiling units per index row
+    // records per launch: 1 GiB of staging for host output, one launch (grid limit) for device output
+    uint64_t CHUNK = on_device ? (1ull << 30) : (1ull << 24);
+    CHUNK = std::min<uint64_t>(CHUNK, std::max<uint64_t>(1, (1ull << 29) / upr) * p.T);   // grid size limit
     if (!on_device) {
         size_t need = (size_t)std::min<uint64_t>(n, CHUNK) * sizeof(mmee_cost);
         if (need > S.eval_cap) {
@@ -425,11 +429,12 @@ int mmee_eval_batch(const mmee_workload *w, const mmee_hw *hw, uint64_t first_id
         const uint64_t cnt = std::min<uint64_t>(CHUNK, n - done);
         const uint64_t first = first_idx + done;
         const uint64_t row_first = first / p.T, row_last = (first + cnt - 1) / p.T;
-        const uint64_t nblocks = (row_last - row_first + 1) * bpr;
-        if (nblocks > 0x7fffffffull) return MMEE_EINVAL;
-        uint4 *dst = on_device ? reinterpret_cast<uint4 *>(out_costs + done) : reinterpret_cast<uint4 *>(S.eval_dev);
+        const uint64_t n_units = (row_last - row_first + 1) * upr;
+        if (n_units > 0x7fffffffull) return MMEE_EINVAL;
+        const uint64_t nblocks = (n_units + 3) / 4;
+        v4u *dst = on_device ? reinterpret_cast<v4u *>(out_costs + done) : reinterpret_cast<v4u *>(S.eval_dev);
         hipLaunchKernelGGL(k_eval_batch, dim3((uint32_t)nblocks), dim3(256), 0, S.stream, ea, first, cnt,
-                           (uint32_t)row_first, bpr, dst);
+                           (uint32_t)row_first, upr, (uint32_t)n_units, dst);
         HIP_TRY(hipGetLastError());
         if (!on_device) {
             HIP_TRY(hipMemcpyAsync(out_costs + done, S.eval_dev, cnt * sizeof(mmee_cost), hipMemcpyDeviceToHost,
