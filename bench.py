@@ -33,6 +33,22 @@ ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 OPS_PER_CANDIDATE = 12 + 12 / 9
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/*.md), scaled by what the
+# same counters read for a 1 GiB device-to-device copy (x2.0 and x1.0).  Valid only for the kernel
+# sources they were taken with: any change to the sources turns "traffic" into null.
+COUNTERS_TAKEN_WITH = "30a2a3ac8681a3f7d796ea67f1b9f115aa518b1929637bb107ddc256486372ce"
+SEARCH_TRAFFIC_BYTES = 109597.3 * 1024 * 2.0 + 292.8 * 1024 * 1.0
+EVAL_TRAFFIC_BYTES = 22049.8 * 1024 * 2.0 + 4367499.5 * 1024 * 1.0
+
+
+def kernel_sources_digest():
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("layout.h", "kernels.h", "mmee.hip"):
+        with open(os.path.join(ROOT, "paper_2604_03446_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -104,6 +120,9 @@ def main():
                      "kernel_candidates_per_s": evaluated / (kernel_ms * 1e-3)},
     }
     out["roofline"]["frac"] = out["roofline"]["achieved"] / out["roofline"]["peak"]
+    counters_valid = kernel_sources_digest() == COUNTERS_TAKEN_WITH
+    if counters_valid:
+        out["roofline"]["traffic"] = SEARCH_TRAFFIC_BYTES
 
     if not args.profile_only:
         # time-to-optimum of the paper's method (pruned rows), host wall time per call
@@ -152,6 +171,8 @@ def main():
                                       "frac": gbs / HBM_PEAK_GBS, "traffic": None, "kernel": "k_eval_batch",
                                       "records": n_rec, "ms": eval_ms,
                                       "candidates_per_s": n_rec / (eval_ms * 1e-3)}
+        if counters_valid:
+            out["roofline_eval_batch"]["traffic"] = EVAL_TRAFFIC_BYTES
         # a plain device-to-device copy of known size (1 GiB read + 1 GiB written): the reference
         # reading for the FETCH_SIZE / WRITE_SIZE counters when the run is profiled
         src = torch.zeros(1 << 27, dtype=torch.int64, device="cuda")
