@@ -43,6 +43,30 @@ CONFIGS = {
                  objectives=[OBJ_ENERGY]),
 }
 
+def _chain(I, K, L, J, batch=1, tiling_mode=1):
+    # GEMM chains carry no softmax between the operators
+    return dict(batch=batch, I=I, K=K, L=L, J=J, word_bytes=2, tiling_mode=tiling_mode, c_softmax=0)
+
+
+def conv_chain_as_gemms(hw_pixels, c_in, c_mid, c_out, k1, k2=1):
+    """im2col of two back-to-back convolutions (the second one 1x1): rows = output pixels,
+    reduction of the first = input channels x kernel window."""
+    assert k2 == 1, "a second kernel larger than 1x1 is not a plain chain of two GEMMs"
+    return hw_pixels, c_in * k1 * k1, c_mid, c_out
+
+
+# an accelerator in the style of the paper's Accel. 1: 4 arrays of 32x32 PEs, 1 MiB buffer, 60 B/cycle
+_ACCEL1 = dict(pe_rows=32, pe_cols=32, n_arrays=4, rf_bytes=512, gb_bytes=1 * MiB,
+               e_dram=200.0, e_gb=6.0, e_rf=1.0, e_mac=1.0, dram_bw=60.0, gb_bw=256.0)
+
+# the shapes of the paper's Table V (two GEMMs and convolution chains)
+CHAINS = {
+    "mlp": dict(workload=_chain(768, 64, 384, 64), hw=_ACCEL1),
+    "ffn": dict(workload=_chain(2048, 768, 3072, 768, tiling_mode=0), hw=_ACCEL1),
+    "cc1": dict(workload=_chain(*conv_chain_as_gemms(112 * 112, 64, 192, 128, 3), tiling_mode=0), hw=_ACCEL1),
+    "cc2": dict(workload=_chain(*conv_chain_as_gemms(56 * 56, 64, 64, 64, 1)), hw=_ACCEL1),
+}
+
 SWEEP_SEED = 0x260403446
 _M64 = (1 << 64) - 1
 

@@ -32,6 +32,12 @@ class Workload(C.Structure):
                 ("c_softmax", C.c_uint32), ("reserved", C.c_uint32)]
 
 
+class Chain(C.Structure):
+    _fields_ = [("batch", C.c_uint32), ("I", C.c_uint32), ("K", C.c_uint32), ("L", C.c_uint32),
+                ("J", C.c_uint32), ("word_bytes", C.c_uint32), ("tiling_mode", C.c_uint32),
+                ("c_softmax", C.c_uint32)]
+
+
 class Hw(C.Structure):
     _fields_ = [("pe_rows", C.c_uint32), ("pe_cols", C.c_uint32), ("n_arrays", C.c_uint32),
                 ("rf_bytes", C.c_uint32), ("gb_bytes", C.c_uint64),
@@ -82,23 +88,24 @@ def lib() -> C.CDLL:
         build()
         L = C.CDLL(LIB_PATH)
         P = C.POINTER
-        L.orc_space_size.argtypes = [P(Workload), P(Hw), P(C.c_uint64)]
-        L.orc_decode.argtypes = [P(Workload), P(Hw), C.c_uint64, P(Mapping)]
-        L.orc_eval.argtypes = [P(Workload), P(Hw), C.c_uint64, P(Mapping), P(Cost), P(Detail)]
-        L.orc_eval_mapping.argtypes = [P(Workload), P(Hw), P(Mapping), P(Cost), P(Detail)]
-        L.orc_eval_batch.argtypes = [P(Workload), P(Hw), C.c_uint64, C.c_uint64, C.c_void_p]
-        L.orc_search_range.argtypes = [P(Workload), P(Hw), C.c_int, C.c_uint64, C.c_uint64,
+        L.orc_from_attention.argtypes = [P(Workload), P(Chain)]
+        L.orc_space_size.argtypes = [P(Chain), P(Hw), P(C.c_uint64)]
+        L.orc_decode.argtypes = [P(Chain), P(Hw), C.c_uint64, P(Mapping)]
+        L.orc_eval.argtypes = [P(Chain), P(Hw), C.c_uint64, P(Mapping), P(Cost), P(Detail)]
+        L.orc_eval_mapping.argtypes = [P(Chain), P(Hw), P(Mapping), P(Cost), P(Detail)]
+        L.orc_eval_batch.argtypes = [P(Chain), P(Hw), C.c_uint64, C.c_uint64, C.c_void_p]
+        L.orc_search_range.argtypes = [P(Chain), P(Hw), C.c_int, C.c_uint64, C.c_uint64,
                                        P(C.c_uint64), P(Cost), P(C.c_uint64), P(C.c_int)]
-        L.orc_search.argtypes = [P(Workload), P(Hw), C.c_int,
+        L.orc_search.argtypes = [P(Chain), P(Hw), C.c_int,
                                  P(C.c_uint64), P(Cost), P(C.c_uint64), P(C.c_int)]
-        L.orc_search_all.argtypes = [P(Workload), P(Hw), C.c_uint64, C.c_uint64,
+        L.orc_search_all.argtypes = [P(Chain), P(Hw), C.c_uint64, C.c_uint64,
                                      C.c_uint64 * 3, Cost * 3, P(C.c_uint64), P(C.c_int)]
         L.sim_run.argtypes = [C.c_uint32 * 4, C.c_uint32 * 4, C.c_uint8 * 4, C.c_uint8 * 4,
                               C.c_int, C.c_int, P(SimResult)]
         L.sim_tile_matmul.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_int,
                                       C.c_uint32, C.c_uint32, C.c_uint32,
                                       P(C.c_uint64), P(C.c_uint64), P(C.c_uint64)]
-        for name in ("orc_space_size", "orc_decode", "orc_eval", "orc_eval_mapping",
+        for name in ("orc_from_attention", "orc_space_size", "orc_decode", "orc_eval", "orc_eval_mapping",
                      "orc_eval_batch", "orc_search_range", "orc_search", "orc_search_all", "sim_run",
                      "sim_tile_matmul"):
             getattr(L, name).restype = C.c_int
@@ -106,9 +113,17 @@ def lib() -> C.CDLL:
     return _lib
 
 
-def workload(cfg: dict) -> Workload:
-    return Workload(cfg["B"], cfg["H"], cfg["N"], cfg["d"], cfg["word_bytes"],
-                    cfg["tiling_mode"], cfg["c_softmax"], 0)
+def workload(cfg: dict) -> Chain:
+    """Attention shape (B, H, N, d) or free chain shape (batch, I, K, L, J) -> the oracle's chain."""
+    if "I" in cfg:
+        return Chain(cfg["batch"], cfg["I"], cfg["K"], cfg["L"], cfg["J"], cfg["word_bytes"],
+                     cfg["tiling_mode"], cfg["c_softmax"])
+    a = Workload(cfg["B"], cfg["H"], cfg["N"], cfg["d"], cfg["word_bytes"],
+                 cfg["tiling_mode"], cfg["c_softmax"], 0)
+    c = Chain()
+    if lib().orc_from_attention(C.byref(a), C.byref(c)):
+        raise ValueError("orc_from_attention failed")
+    return c
 
 
 def hw(cfg: dict) -> Hw:
@@ -116,7 +131,7 @@ def hw(cfg: dict) -> Hw:
               cfg["e_dram"], cfg["e_gb"], cfg["e_rf"], cfg["e_mac"], cfg["dram_bw"], cfg["gb_bw"])
 
 
-def space_size(w: Workload, h: Hw) -> int:
+def space_size(w: Chain, h: Hw) -> int:
     out = C.c_uint64()
     rc = lib().orc_space_size(C.byref(w), C.byref(h), C.byref(out))
     if rc:
@@ -124,7 +139,7 @@ def space_size(w: Workload, h: Hw) -> int:
     return out.value
 
 
-def evaluate(w: Workload, h: Hw, idx: int):
+def evaluate(w: Chain, h: Hw, idx: int):
     m, c, d = Mapping(), Cost(), Detail()
     rc = lib().orc_eval(C.byref(w), C.byref(h), idx, C.byref(m), C.byref(c), C.byref(d))
     if rc:
@@ -132,7 +147,7 @@ def evaluate(w: Workload, h: Hw, idx: int):
     return m, c, d
 
 
-def evaluate_mapping(w: Workload, h: Hw, m: Mapping):
+def evaluate_mapping(w: Chain, h: Hw, m: Mapping):
     c, d = Cost(), Detail()
     rc = lib().orc_eval_mapping(C.byref(w), C.byref(h), C.byref(m), C.byref(c), C.byref(d))
     if rc:
@@ -140,7 +155,7 @@ def evaluate_mapping(w: Workload, h: Hw, m: Mapping):
     return c, d
 
 
-def eval_batch(w: Workload, h: Hw, first_idx: int, n: int):
+def eval_batch(w: Chain, h: Hw, first_idx: int, n: int):
     """Returns a numpy structured array of n cost records."""
     import numpy as np
     out = np.zeros(n, dtype=COST_DTYPE)
@@ -150,7 +165,7 @@ def eval_batch(w: Workload, h: Hw, first_idx: int, n: int):
     return out
 
 
-def search(w: Workload, h: Hw, objective: int, first_idx: int | None = None, n: int | None = None):
+def search(w: Chain, h: Hw, objective: int, first_idx: int | None = None, n: int | None = None):
     """Exhaustive search.  Returns (rc, best_idx, Cost, n_valid, threads)."""
     bi, c, nv, th = C.c_uint64(), Cost(), C.c_uint64(), C.c_int()
     if first_idx is None:
@@ -162,7 +177,7 @@ def search(w: Workload, h: Hw, objective: int, first_idx: int | None = None, n: 
     return rc, bi.value, c, nv.value, th.value
 
 
-def search_all(w: Workload, h: Hw, first_idx: int | None = None, n: int | None = None):
+def search_all(w: Chain, h: Hw, first_idx: int | None = None, n: int | None = None):
     """One exhaustive pass, all three objectives.  Returns (rc, [idx]*3, [Cost]*3, n_valid, threads)."""
     if first_idx is None:
         first_idx, n = 0, space_size(w, h)

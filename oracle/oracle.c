@@ -38,6 +38,14 @@ typedef struct {
     uint32_t reserved;
 } orc_workload;
 
+/* Two chained matrix multiplications of free shape (Sec. VII-H: two GEMMs, or a
+ * convolution chain after im2col): Op1 is I x K x L, Op2 is I x L x J, `batch`
+ * independent instances.  Attention is the case I = L = N, K = J = d, batch = B*H. */
+typedef struct {
+    uint32_t batch, I, K, L, J;
+    uint32_t word_bytes, tiling_mode, c_softmax;
+} orc_chain;
+
 typedef struct {
     uint32_t pe_rows, pe_cols, n_arrays, rf_bytes;
     uint64_t gb_bytes;
@@ -104,9 +112,9 @@ typedef struct {
     uint64_t n_tilings;
 } tiling_space;
 
-static int make_space(const orc_workload *w, tiling_space *ts)
+static int make_space(const orc_chain *w, tiling_space *ts)
 {
-    ts->X[DIM_I] = w->N; ts->X[DIM_K] = w->d; ts->X[DIM_L] = w->N; ts->X[DIM_J] = w->d;
+    ts->X[DIM_I] = w->I; ts->X[DIM_K] = w->K; ts->X[DIM_L] = w->L; ts->X[DIM_J] = w->J;
     ts->n_tilings = 1;
     for (int q = 0; q < 4; ++q) {
         int n = list_divisors(ts->X[q], w->tiling_mode, ts->div[q], MAXDIV);
@@ -119,10 +127,10 @@ static int make_space(const orc_workload *w, tiling_space *ts)
 
 #define ROWS_PER_TILING 540000ull   /* 5^4 levels * 24 orders * 2 * 3 * 3 * 2 */
 
-static int check_args(const orc_workload *w, const orc_hw *hw)
+static int check_args(const orc_chain *w, const orc_hw *hw)
 {
     if (!w || !hw) return -1;
-    if (!w->B || !w->H || !w->N || !w->d || !w->word_bytes) return -1;
+    if (!w->batch || !w->I || !w->K || !w->L || !w->J || !w->word_bytes) return -1;
     if (w->tiling_mode > 1) return -1;
     if (!hw->pe_rows || !hw->pe_cols || !hw->n_arrays) return -1;
     if (hw->rf_bytes < 3 * w->word_bytes) return -1;
@@ -131,7 +139,18 @@ static int check_args(const orc_workload *w, const orc_hw *hw)
     return 0;
 }
 
-int orc_space_size(const orc_workload *w, const orc_hw *hw, uint64_t *out)
+/* Attention as a chain (Sec. III-A): A = Q, B = K^T, D = V, E = O per head. */
+int orc_from_attention(const orc_workload *a, orc_chain *c)
+{
+    if (!a || !c) return -1;
+    if ((uint64_t)a->B * a->H > 0xffffffffull) return -1;
+    c->batch = a->B * a->H;
+    c->I = a->N; c->K = a->d; c->L = a->N; c->J = a->d;
+    c->word_bytes = a->word_bytes; c->tiling_mode = a->tiling_mode; c->c_softmax = a->c_softmax;
+    return 0;
+}
+
+int orc_space_size(const orc_chain *w, const orc_hw *hw, uint64_t *out)
 {
     tiling_space ts;
     if (check_args(w, hw) || !out) return -1;
@@ -178,7 +197,7 @@ static int decode_idx(const tiling_space *ts, uint64_t idx, orc_mapping *m)
     return 0;
 }
 
-int orc_decode(const orc_workload *w, const orc_hw *hw, uint64_t idx, orc_mapping *out)
+int orc_decode(const orc_chain *w, const orc_hw *hw, uint64_t idx, orc_mapping *out)
 {
     tiling_space ts;
     if (check_args(w, hw) || !out) return -1;
@@ -237,7 +256,7 @@ static void tile_matmul(uint64_t m, uint64_t r, uint64_t n, int mode,
     *cycles = ceil_div(u, R) * ceil_div(v, C) * t;
 }
 
-static void eval_mapping(const orc_workload *w, const orc_hw *hw, const tiling_space *ts,
+static void eval_mapping(const orc_chain *w, const orc_hw *hw, const tiling_space *ts,
                          const orc_mapping *m, orc_cost *c, orc_detail *dt)
 {
     orc_detail local;
@@ -365,7 +384,7 @@ static void eval_mapping(const orc_workload *w, const orc_hw *hw, const tiling_s
 
     /* Energy: DRAM<->buffer, buffer<->RF, RF<->MAC and compute (Sec. V-D);
      * softmax costs c_softmax per element of C produced.  All heads. */
-    uint64_t BH = (uint64_t)w->B * w->H;
+    uint64_t BH = w->batch;
     uint64_t T_dram = BH * DA;
     uint64_t T_gb = BH * (DA + BR);
     uint64_t T_rf = BH * 3 * MAC;
@@ -387,7 +406,7 @@ static void eval_mapping(const orc_workload *w, const orc_hw *hw, const tiling_s
     c->valid = 1; c->reason = 0;
 }
 
-int orc_eval(const orc_workload *w, const orc_hw *hw, uint64_t idx,
+int orc_eval(const orc_chain *w, const orc_hw *hw, uint64_t idx,
              orc_mapping *map_out, orc_cost *cost_out, orc_detail *detail_out)
 {
     tiling_space ts;
@@ -405,7 +424,7 @@ int orc_eval(const orc_workload *w, const orc_hw *hw, uint64_t idx,
 
 /* Evaluate an explicit tuple (used by tests that build the Fig. 11 example
  * directly from its description instead of from an index). */
-int orc_eval_mapping(const orc_workload *w, const orc_hw *hw, const orc_mapping *m,
+int orc_eval_mapping(const orc_chain *w, const orc_hw *hw, const orc_mapping *m,
                      orc_cost *cost_out, orc_detail *detail_out)
 {
     tiling_space ts;
@@ -419,7 +438,7 @@ int orc_eval_mapping(const orc_workload *w, const orc_hw *hw, const orc_mapping 
     return 0;
 }
 
-int orc_eval_batch(const orc_workload *w, const orc_hw *hw, uint64_t first_idx,
+int orc_eval_batch(const orc_chain *w, const orc_hw *hw, uint64_t first_idx,
                    uint64_t n, orc_cost *out)
 {
     tiling_space ts;
@@ -450,7 +469,7 @@ static int better(int objective, const orc_cost *a, uint64_t ia, const orc_cost 
 
 /* Exhaustive search over [first_idx, first_idx + n): evaluate every candidate,
  * keep the minimum.  Returns 0, -3 when no candidate in the range is feasible. */
-int orc_search_range(const orc_workload *w, const orc_hw *hw, int objective,
+int orc_search_range(const orc_chain *w, const orc_hw *hw, int objective,
                      uint64_t first_idx, uint64_t n,
                      uint64_t *best_idx, orc_cost *best_cost, uint64_t *n_valid, int *threads_used)
 {
@@ -508,7 +527,7 @@ int orc_search_range(const orc_workload *w, const orc_hw *hw, int objective,
 
 /* One pass over [first_idx, first_idx + n) keeping the minimum for each of the
  * three objectives at once (slot = objective code). */
-int orc_search_all(const orc_workload *w, const orc_hw *hw, uint64_t first_idx, uint64_t n,
+int orc_search_all(const orc_chain *w, const orc_hw *hw, uint64_t first_idx, uint64_t n,
                    uint64_t best_idx[3], orc_cost best_cost[3], uint64_t *n_valid, int *threads_used)
 {
     tiling_space ts;
@@ -566,7 +585,7 @@ int orc_search_all(const orc_workload *w, const orc_hw *hw, uint64_t first_idx, 
     return 0;
 }
 
-int orc_search(const orc_workload *w, const orc_hw *hw, int objective,
+int orc_search(const orc_chain *w, const orc_hw *hw, int objective,
                uint64_t *best_idx, orc_cost *best_cost, uint64_t *n_valid, int *threads_used)
 {
     uint64_t S;

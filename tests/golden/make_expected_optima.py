@@ -1,6 +1,6 @@
 """Writes tests/golden/expected_optima.json: the optimal mapping of every
-benchmark configuration and of a few hardware-sweep points, for all three
-objectives, found by the CPU oracle's exhaustive search.
+benchmark configuration, of a few hardware-sweep points and of the two-GEMM /
+convolution-chain shapes, for all three objectives, found by the CPU oracle's exhaustive search.
 
 Calls only oracle/ and the shared input module.  Full enumeration: about
 3e10 candidate evaluations, tens of minutes on a few cores.
@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__)
 sys.path.insert(0, ROOT)
 
 import oracle as O                                   # noqa: E402
-from inputs import CONFIGS, SplitMix64, sweep_hw, sweep_workloads   # noqa: E402
+from inputs import CHAINS, CONFIGS, SplitMix64, sweep_hw, sweep_workloads   # noqa: E402
 
 OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "expected_optima.json")
 
@@ -58,6 +58,7 @@ def main():
     args = ap.parse_args()
     todo = [(name, cfg["workload"], cfg["hw"]) for name, cfg in CONFIGS.items()]
     todo += sweep_choice(args.sweep_points)
+    todo += [("chain_" + name, cfg["workload"], cfg["hw"]) for name, cfg in CHAINS.items()]
     if args.only:
         keep = set(args.only.split(","))
         todo = [t for t in todo if t[0] in keep]

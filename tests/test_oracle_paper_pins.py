@@ -118,18 +118,20 @@ def test_fig10_unrolled_example_stage_sequence():
     assert list(s.occ_trace[:3]) == [int(v) for v in fx["occupancy_stage_1_2_3"]]
     assert s.psum_violation == 0 and s.coverage_error == 0
     assert s.max_occupancy == 6          # a1 a2 c d e1 e2
-    # the oracle's reservation for the same mapping equals the simulated peak; attention has
-    # I = L, so the oracle side uses i_G = 2 (one tile row of two elements) for the same structure
-    xG = [2, 1, 1, 1]
-    s2 = O.simulate(xG, xD, order, level, 0, 1)
-    w, h = O.workload(wl(2, 2)), O.hw(HW)
-    m = O.Mapping()
-    for q in range(4):
-        m.xG[q], m.xD[q], m.order[q], m.level[q] = xG[q], xD[q], order[q], level[q]
-    m.fused = 1
-    c, d = O.evaluate_mapping(w, h, m)
-    assert c.bs_words == s2.max_occupancy == 4 + 1 + 2 + 4
-    assert list(d.da) == list(s2.da)
+    # the oracle's reservation for the same mapping equals the simulated peak, both for the
+    # example itself (a chain with I = 1, K = L = J = 2) and for an attention shape (I = L)
+    # with the same structure (i_G = 2: one tile row of two elements)
+    for xG_, shape in (([1, 1, 1, 1], dict(batch=1, I=1, K=2, L=2, J=2, word_bytes=2, tiling_mode=1, c_softmax=10)),
+                       ([2, 1, 1, 1], wl(2, 2))):
+        s2 = O.simulate(xG_, xD, order, level, 0, 1)
+        w, h = O.workload(shape), O.hw(HW)
+        m = O.Mapping()
+        for q in range(4):
+            m.xG[q], m.xD[q], m.order[q], m.level[q] = xG_[q], xD[q], order[q], level[q]
+        m.fused = 1
+        c, d = O.evaluate_mapping(w, h, m)
+        assert c.bs_words == s2.max_occupancy == (6 if xG_[0] == 1 else 4 + 1 + 2 + 4)
+        assert list(d.da) == list(s2.da)
 
 
 @pytest.mark.parametrize("N,d", [(8, 4), (12, 6)])
@@ -275,6 +277,33 @@ def test_invariants_on_all_configs():
             assert (c.valid == 0 and c.reason == 2) if over else (c.valid == 1 and c.reason == 0)
             nvalid += c.valid
         assert nvalid > 0
+
+
+def test_two_gemm_and_conv_chain_shapes():
+    """Sec. VII-H, Table V: two GEMMs [I,K,L,J] and convolution chains turned into GEMMs by im2col.
+    The model is the same; only the four loop extents are free."""
+    from inputs import CHAINS
+    assert [CHAINS["mlp"]["workload"][k] for k in "IKLJ"] == [768, 64, 384, 64]
+    assert [CHAINS["ffn"]["workload"][k] for k in "IKLJ"] == [2048, 768, 3072, 768]
+    assert [CHAINS["cc1"]["workload"][k] for k in "IKLJ"] == [112 * 112, 64 * 9, 192, 128]
+    assert [CHAINS["cc2"]["workload"][k] for k in "IKLJ"] == [56 * 56, 64, 64, 64]
+    for name, cfg in CHAINS.items():
+        w, h = O.workload(cfg["workload"]), O.hw(cfg["hw"])
+        I, K, L, J = (cfg["workload"][k] for k in "IKLJ")
+        S = O.space_size(w, h)
+        rng = SplitMix64(len(name))
+        seen = 0
+        for _ in range(3000):
+            m, c, dt = O.evaluate(w, h, rng.next() % S)
+            assert [m.xG[q] * m.xD[q] for q in range(4)] == [I, K, L, J]
+            if c.reason == 1:
+                continue
+            seen += 1
+            rho = m.xD[3] if m.recompute else 1
+            assert c.mac_total == rho * I * K * L + I * L * J
+            assert c.da_words >= I * K + K * L + L * J + I * J      # every matrix moves at least once
+            assert dt.softmax_elems == rho * I * L
+        assert seen > 1000
 
 
 def test_space_sizes():

@@ -21,20 +21,26 @@ def wl(N, d):
     return dict(B=1, H=1, N=N, d=d, word_bytes=2, tiling_mode=1, c_softmax=10)
 
 
+def chain(I, K, L, J, batch=1):
+    return dict(batch=batch, I=I, K=K, L=L, J=J, word_bytes=2, tiling_mode=1, c_softmax=10)
+
+
 CASES = [
-    # (N, d, inter-tile counts i,k,l,j)
-    (4, 4, [2, 2, 2, 2]), (4, 4, [4, 2, 2, 4]), (4, 4, [2, 4, 4, 2]),
-    (8, 2, [4, 2, 2, 2]), (8, 2, [2, 2, 8, 2]),
-    (6, 3, [2, 3, 3, 3]), (6, 3, [3, 3, 2, 3]),            # not powers of two
-    (4, 4, [1, 2, 2, 2]), (4, 4, [2, 1, 4, 2]), (4, 4, [2, 2, 1, 2]), (4, 4, [4, 2, 2, 1]),
-    (4, 4, [1, 1, 1, 1]), (4, 4, [1, 4, 1, 4]), (6, 3, [6, 1, 2, 3]), (6, 3, [1, 3, 6, 1]),
+    # (extents I,K,L,J; inter-tile counts i,k,l,j); attention shapes have I = L and K = J
+    ([4, 4, 4, 4], [2, 2, 2, 2]), ([4, 4, 4, 4], [4, 2, 2, 4]), ([4, 4, 4, 4], [2, 4, 4, 2]),
+    ([8, 2, 8, 2], [4, 2, 2, 2]), ([8, 2, 8, 2], [2, 2, 8, 2]),
+    ([6, 3, 6, 3], [2, 3, 3, 3]), ([6, 3, 6, 3], [3, 3, 2, 3]),            # not powers of two
+    ([4, 4, 4, 4], [1, 2, 2, 2]), ([4, 4, 4, 4], [2, 1, 4, 2]), ([4, 4, 4, 4], [2, 2, 1, 2]),
+    ([4, 4, 4, 4], [4, 2, 2, 1]), ([4, 4, 4, 4], [1, 1, 1, 1]), ([4, 4, 4, 4], [1, 4, 1, 4]),
+    ([6, 3, 6, 3], [6, 1, 2, 3]), ([6, 3, 6, 3], [1, 3, 6, 1]),
+    # free two-GEMM chains: all four extents differ
+    ([4, 6, 8, 10], [2, 3, 4, 5]), ([12, 2, 3, 8], [3, 2, 3, 2]), ([2, 9, 10, 3], [2, 3, 5, 1]),
 ]
 
 
-@pytest.mark.parametrize("N,d,xD", CASES)
-def test_every_order_level_recompute_fusion(N, d, xD):
-    w, h = O.workload(wl(N, d)), O.hw(HW)
-    X = [N, d, N, d]
+@pytest.mark.parametrize("X,xD", CASES)
+def test_every_order_level_recompute_fusion(X, xD):
+    w, h = O.workload(chain(*X)), O.hw(HW)
     xG = [X[q] // xD[q] for q in range(4)]
     all_ge2 = all(v >= 2 for v in xD)
     n = n_tight = 0
