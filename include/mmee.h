@@ -50,6 +50,18 @@ typedef struct mmee_workload {
     uint32_t reserved;      /* must be 0                                                   */
 } mmee_workload;
 
+/* Two chained matrix multiplications of free shape (Sec. VII-H, Table V: two GEMMs, or a
+ * convolution chain turned into GEMMs by im2col): Op1 is I x K x L, Op2 is I x L x J, `batch`
+ * independent instances.  An attention workload is the chain I = L = N, K = J = d, batch = B*H;
+ * every mmee_* call on a workload is the mmee_chain_* call on that chain. */
+typedef struct mmee_chain {
+    uint32_t batch;
+    uint32_t I, K, L, J;
+    uint32_t word_bytes;
+    uint32_t tiling_mode;   /* as in mmee_workload                                         */
+    uint32_t c_softmax;     /* 0 when nothing sits between the two operators               */
+} mmee_chain;
+
 /* Spatial accelerator (Sec. II-B): PE arrays with register files, one global buffer, DRAM. */
 typedef struct mmee_hw {
     uint32_t pe_rows, pe_cols;  /* one PE array                                            */
@@ -151,6 +163,18 @@ int mmee_search_multi(const mmee_workload *w, const mmee_hw *hw, const int *obje
  * (per-entry codes are stored in rc[i] when rc is not null). */
 int mmee_search_many(const mmee_workload *w, const mmee_hw *hw, const int *objectives,
                      uint32_t count, uint32_t flags, mmee_result *out, int *rc);
+
+/* The same calls for a free chain shape (Sec. VII-H).  Semantics, layouts and error codes are
+ * those of the workload calls above. */
+int mmee_chain_space_size(const mmee_chain *c, const mmee_hw *hw, uint64_t *out);
+int mmee_chain_decode(const mmee_chain *c, const mmee_hw *hw, const uint64_t *idx, uint64_t n,
+                      mmee_mapping *out);
+int mmee_chain_eval_batch(const mmee_chain *c, const mmee_hw *hw, uint64_t first_idx, uint64_t n,
+                          mmee_cost *out_costs);
+int mmee_chain_search_multi(const mmee_chain *c, const mmee_hw *hw, const int *objectives,
+                            uint32_t n_obj, uint32_t flags, mmee_result *out);
+int mmee_chain_search_many(const mmee_chain *c, const mmee_hw *hw, const int *objectives,
+                           uint32_t count, uint32_t flags, mmee_result *out, int *rc);
 
 /* Runs the offline stage if needed (row encoding + symbolic pruning, once per process) and
  * reports its counts. */

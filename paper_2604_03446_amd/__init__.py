@@ -31,6 +31,12 @@ class Workload(C.Structure):
                 ("c_softmax", C.c_uint32), ("reserved", C.c_uint32)]
 
 
+class Chain(C.Structure):
+    _fields_ = [("batch", C.c_uint32), ("I", C.c_uint32), ("K", C.c_uint32), ("L", C.c_uint32),
+                ("J", C.c_uint32), ("word_bytes", C.c_uint32), ("tiling_mode", C.c_uint32),
+                ("c_softmax", C.c_uint32)]
+
+
 class Hw(C.Structure):
     _fields_ = [("pe_rows", C.c_uint32), ("pe_cols", C.c_uint32), ("n_arrays", C.c_uint32),
                 ("rf_bytes", C.c_uint32), ("gb_bytes", C.c_uint64),
@@ -84,6 +90,12 @@ def _load() -> C.CDLL:
     L.mmee_search_multi.argtypes = [P(Workload), P(Hw), P(C.c_int), C.c_uint32, C.c_uint32, P(Result)]
     L.mmee_search_many.argtypes = [P(Workload), P(Hw), P(C.c_int), C.c_uint32, C.c_uint32, P(Result),
                                    P(C.c_int)]
+    L.mmee_chain_space_size.argtypes = [P(Chain), P(Hw), P(C.c_uint64)]
+    L.mmee_chain_decode.argtypes = [P(Chain), P(Hw), P(C.c_uint64), C.c_uint64, P(Mapping)]
+    L.mmee_chain_eval_batch.argtypes = [P(Chain), P(Hw), C.c_uint64, C.c_uint64, C.c_void_p]
+    L.mmee_chain_search_multi.argtypes = [P(Chain), P(Hw), P(C.c_int), C.c_uint32, C.c_uint32, P(Result)]
+    L.mmee_chain_search_many.argtypes = [P(Chain), P(Hw), P(C.c_int), C.c_uint32, C.c_uint32, P(Result),
+                                         P(C.c_int)]
     L.mmee_offline_stats.argtypes = [P(RowStats)]
     L.mmee_set_stream.argtypes = [C.c_void_p]
     L.mmee_shutdown.argtypes = []
@@ -91,7 +103,9 @@ def _load() -> C.CDLL:
     L.mmee_strerror.argtypes = [C.c_int]
     L.mmee_strerror.restype = C.c_char_p
     for name in ("mmee_space_size", "mmee_decode", "mmee_eval_batch", "mmee_search", "mmee_search_ex",
-                 "mmee_search_multi", "mmee_search_many", "mmee_offline_stats", "mmee_set_stream"):
+                 "mmee_search_multi", "mmee_search_many", "mmee_offline_stats", "mmee_set_stream",
+                 "mmee_chain_space_size", "mmee_chain_decode", "mmee_chain_eval_batch",
+                 "mmee_chain_search_multi", "mmee_chain_search_many"):
         getattr(L, name).restype = C.c_int
     return L
 
@@ -114,6 +128,13 @@ def workload(cfg) -> Workload:
         return cfg
     return Workload(cfg["B"], cfg["H"], cfg["N"], cfg["d"], cfg["word_bytes"],
                     cfg["tiling_mode"], cfg["c_softmax"], 0)
+
+
+def chain(cfg) -> Chain:
+    if isinstance(cfg, Chain):
+        return cfg
+    return Chain(cfg["batch"], cfg["I"], cfg["K"], cfg["L"], cfg["J"], cfg["word_bytes"],
+                 cfg["tiling_mode"], cfg["c_softmax"])
 
 
 def hw(cfg) -> Hw:
@@ -180,6 +201,53 @@ def mmee_search_many(points, flags: int = SEARCH_PRUNED):
     out = (Result * n)()
     codes = (C.c_int * n)()
     _check(_lib.mmee_search_many(ws, hs, objs, n, flags, out, codes), "mmee_search_many", allow=(ENOFEASIBLE,))
+    return list(out), list(codes)
+
+
+def mmee_chain_space_size(c, h) -> int:
+    out = C.c_uint64()
+    _check(_lib.mmee_chain_space_size(C.byref(chain(c)), C.byref(hw(h)), C.byref(out)), "mmee_chain_space_size")
+    return out.value
+
+
+def mmee_chain_decode(c, h, indices):
+    idx = np.ascontiguousarray(indices, dtype=np.uint64)
+    out = (Mapping * len(idx))()
+    _check(_lib.mmee_chain_decode(C.byref(chain(c)), C.byref(hw(h)),
+                                  idx.ctypes.data_as(C.POINTER(C.c_uint64)), len(idx), out), "mmee_chain_decode")
+    return list(out)
+
+
+def mmee_chain_eval_batch(c, h, first_idx: int, n: int, out=None):
+    if out is None:
+        host = np.zeros(n, dtype=COST_DTYPE)
+        _check(_lib.mmee_chain_eval_batch(C.byref(chain(c)), C.byref(hw(h)), first_idx, n,
+                                          host.ctypes.data), "mmee_chain_eval_batch")
+        return host
+    _check(_lib.mmee_chain_eval_batch(C.byref(chain(c)), C.byref(hw(h)), first_idx, n, C.c_void_p(int(out))),
+           "mmee_chain_eval_batch")
+    return None
+
+
+def mmee_chain_search_multi(c, h, objectives, flags: int = SEARCH_PRUNED):
+    n = len(objectives)
+    objs = (C.c_int * n)(*objectives)
+    out = (Result * n)()
+    _check(_lib.mmee_chain_search_multi(C.byref(chain(c)), C.byref(hw(h)), objs, n, flags, out),
+           "mmee_chain_search_multi")
+    return list(out)
+
+
+def mmee_chain_search_many(points, flags: int = SEARCH_PRUNED):
+    """points: sequence of (chain, hw, objective).  Returns (results, codes)."""
+    n = len(points)
+    cs = (Chain * n)(*[chain(p[0]) for p in points])
+    hs = (Hw * n)(*[hw(p[1]) for p in points])
+    objs = (C.c_int * n)(*[p[2] for p in points])
+    out = (Result * n)()
+    codes = (C.c_int * n)()
+    _check(_lib.mmee_chain_search_many(cs, hs, objs, n, flags, out, codes), "mmee_chain_search_many",
+           allow=(ENOFEASIBLE,))
     return list(out), list(codes)
 
 

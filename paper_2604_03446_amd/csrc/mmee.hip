@@ -87,17 +87,28 @@ int list_divisors(uint32_t X, uint32_t mode, uint32_t *out)
     return n;
 }
 
-int make_plan(const mmee_workload *w, const mmee_hw *hw, Plan &p)
+// attention as a chain (Sec. III-A): A = Q, B = K^T, D = V, E = O, one instance per head
+int chain_of(const mmee_workload *w, mmee_chain &c)
+{
+    if (!w) return MMEE_EINVAL;
+    if (w->reserved || (uint64_t)w->B * w->H > 0xffffffffull) return MMEE_EINVAL;
+    c.batch = w->B * w->H;
+    c.I = w->N; c.K = w->d; c.L = w->N; c.J = w->d;
+    c.word_bytes = w->word_bytes; c.tiling_mode = w->tiling_mode; c.c_softmax = w->c_softmax;
+    return MMEE_OK;
+}
+
+int make_plan(const mmee_chain *w, const mmee_hw *hw, Plan &p)
 {
     if (!w || !hw) return MMEE_EINVAL;
-    if (!w->B || !w->H || !w->N || !w->d || !w->word_bytes || w->tiling_mode > 1 || w->reserved) return MMEE_EINVAL;
+    if (!w->batch || !w->I || !w->K || !w->L || !w->J || !w->word_bytes || w->tiling_mode > 1) return MMEE_EINVAL;
     if (!hw->pe_rows || !hw->pe_cols || !hw->n_arrays) return MMEE_EINVAL;
     if ((uint64_t)hw->rf_bytes < 3ull * w->word_bytes) return MMEE_EINVAL;
     if (!finite_nonneg(hw->e_dram) || !finite_nonneg(hw->e_gb) || !finite_nonneg(hw->e_rf) ||
         !finite_nonneg(hw->e_mac) || !finite_nonneg(hw->dram_bw) || !finite_nonneg(hw->gb_bw))
         return MMEE_EINVAL;
     std::memset(&p, 0, sizeof(p));
-    p.dv.X[DI] = w->N; p.dv.X[DK] = w->d; p.dv.X[DL] = w->N; p.dv.X[DJ] = w->d;
+    p.dv.X[DI] = w->I; p.dv.X[DK] = w->K; p.dv.X[DL] = w->L; p.dv.X[DJ] = w->J;
     p.T = 1;
     for (int q = 0; q < 4; ++q) {
         int n = list_divisors(p.dv.X[q], w->tiling_mode, p.dv.div[q]);
@@ -108,11 +119,11 @@ int make_plan(const mmee_workload *w, const mmee_hw *hw, Plan &p)
     if (p.T > (1ull << 22)) return MMEE_EINVAL;
     p.space = p.T * ROWS_PER_TILING;
     // every count of the model must stay an exact integer in fp64
-    long double bound = (long double)w->B * w->H * (long double)w->N * w->d * (long double)w->N * w->d *
+    long double bound = (long double)w->batch * (long double)w->I * w->K * (long double)w->L * w->J *
                         (16.0L + (long double)w->c_softmax) * (long double)w->word_bytes;
     if (bound >= 9007199254740992.0L) return MMEE_EINVAL;
     ModelConst &mc = p.mc;
-    mc.BH = (double)((uint64_t)w->B * w->H);
+    mc.BH = (double)w->batch;
     mc.c_lat = mc.BH / (double)hw->n_arrays;
     uint64_t cap = hw->gb_bytes / w->word_bytes;
     mc.cap_words = cap >= (1ull << 53) ? 9007199254740992.0 : (double)cap;
@@ -307,7 +318,7 @@ int unpack_result(const Plan &p, size_t slot, int objective, uint64_t evaluated,
     return MMEE_OK;
 }
 
-bool same_problem(const mmee_workload &a, const mmee_hw &b, const mmee_workload &c, const mmee_hw &d)
+bool same_problem(const mmee_chain &a, const mmee_hw &b, const mmee_chain &c, const mmee_hw &d)
 {
     return std::memcmp(&a, &c, sizeof(a)) == 0 && b.pe_rows == d.pe_rows && b.pe_cols == d.pe_cols &&
            b.n_arrays == d.n_arrays && b.rf_bytes == d.rf_bytes && b.gb_bytes == d.gb_bytes &&
@@ -327,7 +338,7 @@ using namespace mmee;
 
 extern "C" {
 
-int mmee_space_size(const mmee_workload *w, const mmee_hw *hw, uint64_t *out)
+int mmee_chain_space_size(const mmee_chain *w, const mmee_hw *hw, uint64_t *out)
 {
     if (!out) return MMEE_EINVAL;
     Plan p;
@@ -359,7 +370,7 @@ int mmee_offline_stats(mmee_row_stats *out)
     return MMEE_OK;
 }
 
-int mmee_decode(const mmee_workload *w, const mmee_hw *hw, const uint64_t *idx, uint64_t n, mmee_mapping *out)
+int mmee_chain_decode(const mmee_chain *w, const mmee_hw *hw, const uint64_t *idx, uint64_t n, mmee_mapping *out)
 {
     if (n && (!idx || !out)) return MMEE_EINVAL;
     Plan p;
@@ -391,7 +402,8 @@ int mmee_decode(const mmee_workload *w, const mmee_hw *hw, const uint64_t *idx, 
     return MMEE_OK;
 }
 
-int mmee_eval_batch(const mmee_workload *w, const mmee_hw *hw, uint64_t first_idx, uint64_t n, mmee_cost *out_costs)
+int mmee_chain_eval_batch(const mmee_chain *w, const mmee_hw *hw, uint64_t first_idx, uint64_t n,
+                          mmee_cost *out_costs)
 {
     Plan p;
     int rc = make_plan(w, hw, p);
@@ -446,8 +458,8 @@ int mmee_eval_batch(const mmee_workload *w, const mmee_hw *hw, uint64_t first_id
     return MMEE_OK;
 }
 
-int mmee_search_many(const mmee_workload *w, const mmee_hw *hw, const int *objectives, uint32_t count,
-                     uint32_t flags, mmee_result *out, int *rc_out)
+int mmee_chain_search_many(const mmee_chain *w, const mmee_hw *hw, const int *objectives, uint32_t count,
+                           uint32_t flags, mmee_result *out, int *rc_out)
 {
     if (!count) return MMEE_OK;
     if (!w || !hw || !objectives || !out) return MMEE_EINVAL;
@@ -503,8 +515,8 @@ int mmee_search_many(const mmee_workload *w, const mmee_hw *hw, const int *objec
     return first_bad;
 }
 
-int mmee_search_multi(const mmee_workload *w, const mmee_hw *hw, const int *objectives, uint32_t n_obj,
-                      uint32_t flags, mmee_result *out)
+int mmee_chain_search_multi(const mmee_chain *w, const mmee_hw *hw, const int *objectives, uint32_t n_obj,
+                            uint32_t flags, mmee_result *out)
 {
     if (!w || !hw || !objectives || !out || n_obj < 1 || n_obj > 3) return MMEE_EINVAL;
     int seen = 0;
@@ -512,9 +524,53 @@ int mmee_search_multi(const mmee_workload *w, const mmee_hw *hw, const int *obje
         if (objectives[a] < 0 || objectives[a] > 2 || (seen & (1 << objectives[a]))) return MMEE_EINVAL;
         seen |= 1 << objectives[a];
     }
-    mmee_workload ws[3] = {*w, *w, *w};
+    mmee_chain ws[3] = {*w, *w, *w};
     mmee_hw hs[3] = {*hw, *hw, *hw};
-    return mmee_search_many(ws, hs, objectives, n_obj, flags, out, nullptr);
+    return mmee_chain_search_many(ws, hs, objectives, n_obj, flags, out, nullptr);
+}
+
+// ---- attention workloads: the chain I = L = N, K = J = d, batch = B*H --------------------------
+
+int mmee_space_size(const mmee_workload *w, const mmee_hw *hw, uint64_t *out)
+{
+    mmee_chain c;
+    int rc = chain_of(w, c);
+    return rc ? rc : mmee_chain_space_size(&c, hw, out);
+}
+
+int mmee_decode(const mmee_workload *w, const mmee_hw *hw, const uint64_t *idx, uint64_t n, mmee_mapping *out)
+{
+    mmee_chain c;
+    int rc = chain_of(w, c);
+    return rc ? rc : mmee_chain_decode(&c, hw, idx, n, out);
+}
+
+int mmee_eval_batch(const mmee_workload *w, const mmee_hw *hw, uint64_t first_idx, uint64_t n, mmee_cost *out_costs)
+{
+    mmee_chain c;
+    int rc = chain_of(w, c);
+    return rc ? rc : mmee_chain_eval_batch(&c, hw, first_idx, n, out_costs);
+}
+
+int mmee_search_many(const mmee_workload *w, const mmee_hw *hw, const int *objectives, uint32_t count,
+                     uint32_t flags, mmee_result *out, int *rc_out)
+{
+    if (!count) return MMEE_OK;
+    if (!w || !hw || !objectives || !out) return MMEE_EINVAL;
+    std::vector<mmee_chain> chains(count);
+    for (uint32_t a = 0; a < count; ++a) {
+        // a malformed workload becomes a malformed chain and is reported per entry
+        if (chain_of(w + a, chains[a])) std::memset(&chains[a], 0, sizeof(mmee_chain));
+    }
+    return mmee_chain_search_many(chains.data(), hw, objectives, count, flags, out, rc_out);
+}
+
+int mmee_search_multi(const mmee_workload *w, const mmee_hw *hw, const int *objectives, uint32_t n_obj,
+                      uint32_t flags, mmee_result *out)
+{
+    mmee_chain c;
+    int rc = chain_of(w, c);
+    return rc ? rc : mmee_chain_search_multi(&c, hw, objectives, n_obj, flags, out);
 }
 
 int mmee_search_ex(const mmee_workload *w, const mmee_hw *hw, int objective, uint32_t flags, mmee_result *out)
