@@ -77,7 +77,8 @@ class SimResult(C.Structure):
                 ("psum_violation", C.c_int32), ("coverage_error", C.c_int32)]
 
 
-OBJ_ENERGY, OBJ_LATENCY, OBJ_LATENCY_THEN_ENERGY = 0, 1, 2
+OBJ_ENERGY, OBJ_LATENCY, OBJ_LATENCY_THEN_ENERGY, OBJ_EDP = 0, 1, 2, 3
+N_OBJ = 4
 
 _lib = None
 
@@ -99,14 +100,16 @@ def lib() -> C.CDLL:
         L.orc_search.argtypes = [P(Chain), P(Hw), C.c_int,
                                  P(C.c_uint64), P(Cost), P(C.c_uint64), P(C.c_int)]
         L.orc_search_all.argtypes = [P(Chain), P(Hw), C.c_uint64, C.c_uint64,
-                                     C.c_uint64 * 3, Cost * 3, P(C.c_uint64), P(C.c_int)]
+                                     C.c_uint64 * 4, Cost * 4, P(C.c_uint64), P(C.c_int)]
+        L.orc_pareto.argtypes = [P(Chain), P(Hw), C.c_uint64, C.c_uint64, C.c_uint32,
+                                 P(C.c_uint64), P(Cost), P(C.c_uint32)]
         L.sim_run.argtypes = [C.c_uint32 * 4, C.c_uint32 * 4, C.c_uint8 * 4, C.c_uint8 * 4,
                               C.c_int, C.c_int, P(SimResult)]
         L.sim_tile_matmul.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_int,
                                       C.c_uint32, C.c_uint32, C.c_uint32,
                                       P(C.c_uint64), P(C.c_uint64), P(C.c_uint64)]
         for name in ("orc_from_attention", "orc_space_size", "orc_decode", "orc_eval", "orc_eval_mapping",
-                     "orc_eval_batch", "orc_search_range", "orc_search", "orc_search_all", "sim_run",
+                     "orc_eval_batch", "orc_search_range", "orc_search", "orc_search_all", "orc_pareto", "sim_run",
                      "sim_tile_matmul"):
             getattr(L, name).restype = C.c_int
         _lib = L
@@ -178,12 +181,21 @@ def search(w: Chain, h: Hw, objective: int, first_idx: int | None = None, n: int
 
 
 def search_all(w: Chain, h: Hw, first_idx: int | None = None, n: int | None = None):
-    """One exhaustive pass, all three objectives.  Returns (rc, [idx]*3, [Cost]*3, n_valid, threads)."""
+    """One exhaustive pass, all four objectives.  Returns (rc, [idx]*4, [Cost]*4, n_valid, threads)."""
     if first_idx is None:
         first_idx, n = 0, space_size(w, h)
-    bi, bc, nv, th = (C.c_uint64 * 3)(), (Cost * 3)(), C.c_uint64(), C.c_int()
+    bi, bc, nv, th = (C.c_uint64 * 4)(), (Cost * 4)(), C.c_uint64(), C.c_int()
     rc = lib().orc_search_all(C.byref(w), C.byref(h), first_idx, n, bi, bc, C.byref(nv), C.byref(th))
     return rc, list(bi), list(bc), nv.value, th.value
+
+
+def pareto(w: Chain, h: Hw, capacity: int = 1024, first_idx: int | None = None, n: int | None = None):
+    """Energy-latency Pareto front.  Returns (rc, [idx], [Cost]) by ascending latency."""
+    if first_idx is None:
+        first_idx, n = 0, space_size(w, h)
+    idx, cost, cnt = (C.c_uint64 * capacity)(), (Cost * capacity)(), C.c_uint32()
+    rc = lib().orc_pareto(C.byref(w), C.byref(h), first_idx, n, capacity, idx, cost, C.byref(cnt))
+    return rc, list(idx[:cnt.value]), list(cost[:cnt.value])
 
 
 def simulate(xG, xD, order, level, recompute: int, fused: int) -> SimResult:

@@ -82,7 +82,7 @@ typedef struct {
 
 enum { DIM_I = 0, DIM_K = 1, DIM_L = 2, DIM_J = 3 };
 enum { OPD_A = 0, OPD_B = 1, OPD_C = 2, OPD_D = 3, OPD_E = 4 };
-enum { OBJ_ENERGY = 0, OBJ_LATENCY = 1, OBJ_LATENCY_THEN_ENERGY = 2 };
+enum { OBJ_ENERGY = 0, OBJ_LATENCY = 1, OBJ_LATENCY_THEN_ENERGY = 2, OBJ_EDP = 3, N_OBJ = 4 };
 
 /* Own dimensions of each operand (Sec. V-A "Operand's dimensions"). */
 static const int OWN[5][2] = {
@@ -460,6 +460,9 @@ static int better(int objective, const orc_cost *a, uint64_t ia, const orc_cost 
 {
     double pa, pb, sa = 0, sb = 0;
     if (objective == OBJ_ENERGY) { pa = a->energy_pj; pb = b->energy_pj; }
+    else if (objective == OBJ_EDP) {       /* energy-delay product (Sec. VII-I) */
+        pa = a->energy_pj * a->latency_cycles; pb = b->energy_pj * b->latency_cycles;
+    }
     else { pa = a->latency_cycles; pb = b->latency_cycles; }
     if (objective == OBJ_LATENCY_THEN_ENERGY) { sa = a->energy_pj; sb = b->energy_pj; }
     if (pa != pb) return pa < pb;
@@ -475,7 +478,7 @@ int orc_search_range(const orc_chain *w, const orc_hw *hw, int objective,
 {
     tiling_space ts;
     if (check_args(w, hw) || !best_idx || !best_cost) return -1;
-    if (objective < 0 || objective > 2) return -1;
+    if (objective < 0 || objective >= N_OBJ) return -1;
     if (make_space(w, &ts)) return -1;
     uint64_t S = ts.n_tilings * ROWS_PER_TILING;
     if (first_idx > S || n > S - first_idx) return -2;
@@ -526,9 +529,9 @@ int orc_search_range(const orc_chain *w, const orc_hw *hw, int objective,
 }
 
 /* One pass over [first_idx, first_idx + n) keeping the minimum for each of the
- * three objectives at once (slot = objective code). */
+ * four objectives at once (slot = objective code). */
 int orc_search_all(const orc_chain *w, const orc_hw *hw, uint64_t first_idx, uint64_t n,
-                   uint64_t best_idx[3], orc_cost best_cost[3], uint64_t *n_valid, int *threads_used)
+                   uint64_t best_idx[N_OBJ], orc_cost best_cost[N_OBJ], uint64_t *n_valid, int *threads_used)
 {
     tiling_space ts;
     if (check_args(w, hw) || !best_idx || !best_cost) return -1;
@@ -536,16 +539,16 @@ int orc_search_all(const orc_chain *w, const orc_hw *hw, uint64_t first_idx, uin
     uint64_t S = ts.n_tilings * ROWS_PER_TILING;
     if (first_idx > S || n > S - first_idx) return -2;
     int have = 0, nthreads = 1;
-    uint64_t gidx[3] = {0, 0, 0}, gvalid = 0;
-    orc_cost gcost[3];
+    uint64_t gidx[N_OBJ] = {0, 0, 0, 0}, gvalid = 0;
+    orc_cost gcost[N_OBJ];
     memset(gcost, 0, sizeof(gcost));
     const uint64_t CH = 1u << 16;
     int64_t nchunks = (int64_t)((n + CH - 1) / CH);
 #pragma omp parallel
     {
         int lhave = 0;
-        uint64_t lidx[3] = {0, 0, 0}, lvalid = 0;
-        orc_cost lcost[3];
+        uint64_t lidx[N_OBJ] = {0, 0, 0, 0}, lvalid = 0;
+        orc_cost lcost[N_OBJ];
         memset(lcost, 0, sizeof(lcost));
 #ifdef _OPENMP
 #pragma omp single
@@ -563,7 +566,7 @@ int orc_search_all(const orc_chain *w, const orc_hw *hw, uint64_t first_idx, uin
                 eval_mapping(w, hw, &ts, &m, &c, 0);
                 if (!c.valid) continue;
                 ++lvalid;
-                for (int o = 0; o < 3; ++o)
+                for (int o = 0; o < N_OBJ; ++o)
                     if (!lhave || better(o, &c, idx, &lcost[o], lidx[o])) { lcost[o] = c; lidx[o] = idx; }
                 lhave = 1;
             }
@@ -572,7 +575,7 @@ int orc_search_all(const orc_chain *w, const orc_hw *hw, uint64_t first_idx, uin
         {
             gvalid += lvalid;
             if (lhave) {
-                for (int o = 0; o < 3; ++o)
+                for (int o = 0; o < N_OBJ; ++o)
                     if (!have || better(o, &lcost[o], lidx[o], &gcost[o], gidx[o])) { gcost[o] = lcost[o]; gidx[o] = lidx[o]; }
                 have = 1;
             }
@@ -580,8 +583,90 @@ int orc_search_all(const orc_chain *w, const orc_hw *hw, uint64_t first_idx, uin
     }
     if (threads_used) *threads_used = nthreads;
     if (n_valid) *n_valid = gvalid;
-    if (!have) { for (int o = 0; o < 3; ++o) best_cost[o].valid = 0; return -3; }
-    for (int o = 0; o < 3; ++o) { best_idx[o] = gidx[o]; best_cost[o] = gcost[o]; }
+    if (!have) { for (int o = 0; o < N_OBJ; ++o) best_cost[o].valid = 0; return -3; }
+    for (int o = 0; o < N_OBJ; ++o) { best_idx[o] = gidx[o]; best_cost[o] = gcost[o]; }
+    return 0;
+}
+
+/* Energy-latency Pareto front (Sec. VI-A, Sec. VII-C): the feasible candidates that no other
+ * candidate beats in both metrics.  Among candidates with identical (energy, latency) the lowest
+ * index stands for all.  Points come out by ascending latency (so descending energy).
+ * One plain pass: every candidate is checked against the current front.
+ * Returns 0, -3 when nothing is feasible, -5 when the front outgrows `capacity`. */
+typedef struct { double e, l; uint64_t idx; } front_pt;
+
+static int front_insert(front_pt *f, int *n, int cap, double e, double l, uint64_t idx)
+{
+    /* dominated by (or equal to, with a lower index than) a point already there? */
+    for (int a = 0; a < *n; ++a) {
+        if (f[a].e <= e && f[a].l <= l) {
+            if (f[a].e == e && f[a].l == l) { if (idx < f[a].idx) f[a].idx = idx; }
+            return 0;
+        }
+    }
+    /* it stays: drop what it dominates */
+    int m = 0;
+    for (int a = 0; a < *n; ++a)
+        if (!(e <= f[a].e && l <= f[a].l)) f[m++] = f[a];
+    if (m >= cap) return -5;
+    f[m].e = e; f[m].l = l; f[m].idx = idx;
+    *n = m + 1;
+    return 0;
+}
+
+int orc_pareto(const orc_chain *w, const orc_hw *hw, uint64_t first_idx, uint64_t n, uint32_t capacity,
+               uint64_t *idx_out, orc_cost *cost_out, uint32_t *n_out)
+{
+    tiling_space ts;
+    if (check_args(w, hw) || !idx_out || !cost_out || !n_out || !capacity || capacity > 4096) return -1;
+    if (make_space(w, &ts)) return -1;
+    uint64_t S = ts.n_tilings * ROWS_PER_TILING;
+    if (first_idx > S || n > S - first_idx) return -2;
+    front_pt global[4096];
+    int ng = 0, overflow = 0;
+    const uint64_t CH = 1u << 16;
+    int64_t nchunks = (int64_t)((n + CH - 1) / CH);
+#pragma omp parallel
+    {
+        front_pt local[4096];
+        int nl = 0, bad = 0;
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t ch = 0; ch < nchunks; ++ch) {
+            uint64_t lo = first_idx + (uint64_t)ch * CH;
+            uint64_t hi = lo + CH;
+            if (hi > first_idx + n) hi = first_idx + n;
+            for (uint64_t idx = lo; idx < hi; ++idx) {
+                orc_mapping m;
+                orc_cost c;
+                decode_idx(&ts, idx, &m);
+                eval_mapping(w, hw, &ts, &m, &c, 0);
+                if (!c.valid) continue;
+                if (front_insert(local, &nl, 4096, c.energy_pj, c.latency_cycles, idx)) bad = 1;
+            }
+        }
+#pragma omp critical
+        {
+            if (bad) overflow = 1;
+            for (int a = 0; a < nl; ++a)
+                if (front_insert(global, &ng, 4096, local[a].e, local[a].l, local[a].idx)) overflow = 1;
+        }
+    }
+    if (overflow || (uint32_t)ng > capacity) return -5;
+    if (!ng) { *n_out = 0; return -3; }
+    /* ascending latency */
+    for (int a = 1; a < ng; ++a) {
+        front_pt key = global[a];
+        int b = a - 1;
+        while (b >= 0 && global[b].l > key.l) { global[b + 1] = global[b]; --b; }
+        global[b + 1] = key;
+    }
+    for (int a = 0; a < ng; ++a) {
+        orc_mapping m;
+        idx_out[a] = global[a].idx;
+        decode_idx(&ts, global[a].idx, &m);
+        eval_mapping(w, hw, &ts, &m, &cost_out[a], 0);
+    }
+    *n_out = (uint32_t)ng;
     return 0;
 }
 

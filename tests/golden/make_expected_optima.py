@@ -1,6 +1,6 @@
 """Writes tests/golden/expected_optima.json: the optimal mapping of every
 benchmark configuration, of a few hardware-sweep points and of the two-GEMM /
-convolution-chain shapes, for all three objectives, found by the CPU oracle's exhaustive search.
+convolution-chain shapes, for all four objectives, found by the CPU oracle's exhaustive search.
 
 Calls only oracle/ and the shared input module.  Full enumeration: about
 3e10 candidate evaluations, tens of minutes on a few cores.
@@ -28,7 +28,7 @@ def record(wcfg, hcfg):
     rc, idx, cost, n_valid, threads = O.search_all(w, h)
     rec = dict(workload=wcfg, hw=hcfg, space=O.space_size(w, h), n_valid=n_valid, rc=rc,
                oracle_seconds=round(time.time() - t, 2), oracle_threads=threads, best={})
-    for o, name in enumerate(("energy", "latency", "latency_then_energy")):
+    for o, name in enumerate(("energy", "latency", "latency_then_energy", "edp")):
         c = cost[o]
         rec["best"][name] = dict(
             idx=idx[o], energy_pj=float(c.energy_pj).hex(), latency_cycles=float(c.latency_cycles).hex(),
