@@ -116,7 +116,8 @@ typedef struct mmee_row_stats {
 enum {
     MMEE_OBJ_ENERGY = 0,                /* key (energy, idx)            */
     MMEE_OBJ_LATENCY = 1,               /* key (latency, idx)           */
-    MMEE_OBJ_LATENCY_THEN_ENERGY = 2    /* key (latency, energy, idx)   */
+    MMEE_OBJ_LATENCY_THEN_ENERGY = 2,   /* key (latency, energy, idx)   */
+    MMEE_OBJ_EDP = 3                    /* key (energy * latency, idx), the energy-delay product (Sec. VII-I) */
 };
 
 enum {
@@ -129,7 +130,8 @@ enum {
     MMEE_EINVAL = -1,       /* null pointer, zero dimension, unsupported size, bad enum       */
     MMEE_ERANGE = -2,       /* index range outside [0, space)                                 */
     MMEE_ENOFEASIBLE = -3,  /* every candidate is masked; out->cost.valid = 0                 */
-    MMEE_EDEVICE = -4       /* HIP error or no device                                         */
+    MMEE_EDEVICE = -4,      /* HIP error or no device                                         */
+    MMEE_EOVERFLOW = -5     /* mmee_pareto: more front points than `capacity`                 */
 };
 
 /* Number of candidates of (workload, hw): #tilings (integer factorisations, Sec. VI-A)
@@ -152,7 +154,7 @@ int mmee_search(const mmee_workload *w, const mmee_hw *hw, int objective, mmee_r
 int mmee_search_ex(const mmee_workload *w, const mmee_hw *hw, int objective, uint32_t flags,
                    mmee_result *out);
 
-/* One pass over the space that reduces n_obj (1..3, distinct) objectives at once: all
+/* One pass over the space that reduces n_obj (1..4, distinct) objectives at once: all
  * metrics of a candidate are formed once and shared (Sec. VII-C).  out holds n_obj results. */
 int mmee_search_multi(const mmee_workload *w, const mmee_hw *hw, const int *objectives,
                       uint32_t n_obj, uint32_t flags, mmee_result *out);
@@ -163,6 +165,14 @@ int mmee_search_multi(const mmee_workload *w, const mmee_hw *hw, const int *obje
  * (per-entry codes are stored in rc[i] when rc is not null). */
 int mmee_search_many(const mmee_workload *w, const mmee_hw *hw, const int *objectives,
                      uint32_t count, uint32_t flags, mmee_result *out, int *rc);
+
+/* Energy-latency Pareto front (Sec. VI-A, Sec. VII-C): the feasible candidates that no other
+ * candidate beats in both metrics; among candidates with identical (energy, latency) the lowest
+ * index stands for all.  out receives at most `capacity` points by ascending latency (descending
+ * energy), *n_points their number.  Each point costs one pass over the space.  Returns
+ * MMEE_EOVERFLOW (with the first `capacity` points stored) when the front is longer. */
+int mmee_pareto(const mmee_workload *w, const mmee_hw *hw, uint32_t flags, mmee_result *out,
+                uint32_t capacity, uint32_t *n_points);
 
 /* The same calls for a free chain shape (Sec. VII-H).  Semantics, layouts and error codes are
  * those of the workload calls above. */
@@ -175,6 +185,8 @@ int mmee_chain_search_multi(const mmee_chain *c, const mmee_hw *hw, const int *o
                             uint32_t n_obj, uint32_t flags, mmee_result *out);
 int mmee_chain_search_many(const mmee_chain *c, const mmee_hw *hw, const int *objectives,
                            uint32_t count, uint32_t flags, mmee_result *out, int *rc);
+int mmee_chain_pareto(const mmee_chain *c, const mmee_hw *hw, uint32_t flags, mmee_result *out,
+                      uint32_t capacity, uint32_t *n_points);
 
 /* Runs the offline stage if needed (row encoding + symbolic pruning, once per process) and
  * reports its counts. */

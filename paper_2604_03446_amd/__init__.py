@@ -14,9 +14,9 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("MMEE_LIB") or os.path.join(_HERE, "libmmee.so")
 
-OBJ_ENERGY, OBJ_LATENCY, OBJ_LATENCY_THEN_ENERGY = 0, 1, 2
+OBJ_ENERGY, OBJ_LATENCY, OBJ_LATENCY_THEN_ENERGY, OBJ_EDP = 0, 1, 2, 3
 SEARCH_PRUNED, SEARCH_EXHAUSTIVE = 0, 1
-OK, EINVAL, ERANGE, ENOFEASIBLE, EDEVICE = 0, -1, -2, -3, -4
+OK, EINVAL, ERANGE, ENOFEASIBLE, EDEVICE, EOVERFLOW = 0, -1, -2, -3, -4, -5
 
 
 class MmeeError(RuntimeError):
@@ -96,6 +96,8 @@ def _load() -> C.CDLL:
     L.mmee_chain_search_multi.argtypes = [P(Chain), P(Hw), P(C.c_int), C.c_uint32, C.c_uint32, P(Result)]
     L.mmee_chain_search_many.argtypes = [P(Chain), P(Hw), P(C.c_int), C.c_uint32, C.c_uint32, P(Result),
                                          P(C.c_int)]
+    L.mmee_pareto.argtypes = [P(Workload), P(Hw), C.c_uint32, P(Result), C.c_uint32, P(C.c_uint32)]
+    L.mmee_chain_pareto.argtypes = [P(Chain), P(Hw), C.c_uint32, P(Result), C.c_uint32, P(C.c_uint32)]
     L.mmee_offline_stats.argtypes = [P(RowStats)]
     L.mmee_set_stream.argtypes = [C.c_void_p]
     L.mmee_shutdown.argtypes = []
@@ -105,7 +107,7 @@ def _load() -> C.CDLL:
     for name in ("mmee_space_size", "mmee_decode", "mmee_eval_batch", "mmee_search", "mmee_search_ex",
                  "mmee_search_multi", "mmee_search_many", "mmee_offline_stats", "mmee_set_stream",
                  "mmee_chain_space_size", "mmee_chain_decode", "mmee_chain_eval_batch",
-                 "mmee_chain_search_multi", "mmee_chain_search_many"):
+                 "mmee_chain_search_multi", "mmee_chain_search_many", "mmee_pareto", "mmee_chain_pareto"):
         getattr(L, name).restype = C.c_int
     return L
 
@@ -249,6 +251,23 @@ def mmee_chain_search_many(points, flags: int = SEARCH_PRUNED):
     _check(_lib.mmee_chain_search_many(cs, hs, objs, n, flags, out, codes), "mmee_chain_search_many",
            allow=(ENOFEASIBLE,))
     return list(out), list(codes)
+
+
+def _pareto(fn, name, problem, h, flags, capacity):
+    out = (Result * capacity)()
+    n = C.c_uint32()
+    code = _check(fn(C.byref(problem), C.byref(hw(h)), flags, out, capacity, C.byref(n)), name,
+                  allow=(ENOFEASIBLE, EOVERFLOW))
+    return code, list(out[:n.value])
+
+
+def mmee_pareto(w, h, flags: int = SEARCH_PRUNED, capacity: int = 256):
+    """Energy-latency Pareto front by ascending latency.  Returns (code, [Result])."""
+    return _pareto(_lib.mmee_pareto, "mmee_pareto", workload(w), h, flags, capacity)
+
+
+def mmee_chain_pareto(c, h, flags: int = SEARCH_PRUNED, capacity: int = 256):
+    return _pareto(_lib.mmee_chain_pareto, "mmee_chain_pareto", chain(c), h, flags, capacity)
 
 
 def mmee_offline_stats() -> RowStats:

@@ -543,10 +543,11 @@ struct SearchArgs {
     const double *btab;
     const double *ctab_s;
     ModelConst mc;
-    Key *partials;               // [gridDim.x][3]
+    Key *partials;               // [gridDim.x][N_OBJ]
     uint32_t *ticket;
     uint32_t *work_counter;
-    FinalRecord *final_out;      // [3]
+    FinalRecord *final_out;      // [N_OBJ]
+    double e_limit;              // LIMIT kernels only: candidates with energy >= e_limit are left out
     const uint64_t *ctab_e;
     DivTable const *dv;          // device copy, for the final record's mapping
 };
@@ -577,23 +578,26 @@ constexpr int SEARCH_THREADS = MMEE_THREADS;
 // keeps the optimiser from sinking a select below the operations that consume its result
 __device__ __forceinline__ void pin(double &x) { asm("" : "+v"(x)); }
 
-// MASK: bit0 energy, bit1 latency, bit2 latency-then-energy.
+// MASK: bit0 energy, bit1 latency, bit2 latency-then-energy, bit3 energy-delay product (Sec. VII-I).
 // FAST: DRAM bandwidth is 0 or a power of two and the array count is a power of two, so the
 // DRAM latency term is one exact multiply of the table value; otherwise it is divided out.
 //
 // Persistent blocks (as many as the chip holds) pull work items from a global counter.  One item =
 // SEARCH_THREADS rows of one (r, f) group (lane = row) x TC consecutive tilings (loop).
-template <int MASK, bool FAST>
-__global__ __launch_bounds__(SEARCH_THREADS, (MASK == 5 || MASK == 6 || MASK == 7) ? 2 : 4) void k_search(SearchArgs a)
+// LIMIT: only candidates whose energy is below a.e_limit take part (one step of the Pareto walk).
+constexpr int popcount4(int m) { return (m & 1) + ((m >> 1) & 1) + ((m >> 2) & 1) + ((m >> 3) & 1); }
+
+template <int MASK, bool FAST, bool LIMIT = false>
+__global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 && MASK != 4)) ? 2 : 4) void k_search(SearchArgs a)
 {
     __shared__ double tab[(TC + 1) * NENT];      // one spare row: the loop reads one tiling ahead
-    __shared__ Key wave_best[3][SEARCH_THREADS / 64];
+    __shared__ Key wave_best[N_OBJ][SEARCH_THREADS / 64];
     __shared__ uint32_t is_last;
 
     const double inf = pos_inf();
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // wave_best[o][w]: best key of wave w over all items so far; only wave w touches its slot
-    if (lane < 3) { wave_best[lane][wave].p = inf; wave_best[lane][wave].s = 0.0; wave_best[lane][wave].idx = ~0ull; }
+    if (lane < N_OBJ) { wave_best[lane][wave].p = inf; wave_best[lane][wave].s = 0.0; wave_best[lane][wave].idx = ~0ull; }
 
     // work items are handed out through a global counter; the first one is the block's own number.
     // Thread 0 asks for the next item while the current one is being processed.
@@ -631,12 +635,12 @@ __global__ __launch_bounds__(SEARCH_THREADS, (MASK == 5 || MASK == 6 || MASK == 
 
         // a lane without a row never passes the capacity test
         const double cap = live ? a.mc.cap_words : -1.0;
-        double bestE[9], bestL[9], bestLE_l[9], bestLE_e[9];
-        uint32_t codeE[9], codeL[9], codeLE[9];
+        double bestE[9], bestL[9], bestLE_l[9], bestLE_e[9], bestP[9];
+        uint32_t codeE[9], codeL[9], codeLE[9], codeP[9];
 #pragma unroll
         for (int c9 = 0; c9 < 9; ++c9) {
-            bestE[c9] = bestL[c9] = bestLE_l[c9] = bestLE_e[c9] = inf;
-            codeE[c9] = codeL[c9] = codeLE[c9] = 0;
+            bestE[c9] = bestL[c9] = bestLE_l[c9] = bestLE_e[c9] = bestP[c9] = inf;
+            codeE[c9] = codeL[c9] = codeLE[c9] = codeP[c9] = 0;
         }
 
         // Software pipeline: table values (LDS) and the per-tiling constants (scalar loads) of the
@@ -695,6 +699,17 @@ __global__ __launch_bounds__(SEARCH_THREADS, (MASK == 5 || MASK == 6 || MASK == 
                 en = en + e_rf_now;
                 en = en + e_mac_now;
                 double lat = fmax(l_dram, lat_part);
+                if constexpr (LIMIT) {
+                    bool out_of_range = !(en < a.e_limit);
+                    en = out_of_range ? inf : en;
+                    lat = out_of_range ? inf : lat;
+                }
+                if constexpr (MASK & 8) {
+                    double edp = en * lat;
+                    bool lt = edp < bestP[c9];
+                    bestP[c9] = fmin(bestP[c9], edp);
+                    codeP[c9] = lt ? tl : codeP[c9];
+                }
                 if constexpr (MASK & 1) {
                     bool lt = en < bestE[c9];
                     bestE[c9] = fmin(bestE[c9], en);
@@ -727,9 +742,9 @@ __global__ __launch_bounds__(SEARCH_THREADS, (MASK == 5 || MASK == 6 || MASK == 
         // index, so a strict < keeps the lowest index), reduce over the wave, keep the wave's best
         const uint32_t f = g >> 1;
         const uint64_t row_base = (uint64_t)(dfrow % ROWS_PER_GROUP) + 15000ull * r + 270000ull * f;
-        Key mine[3];
+        Key mine[N_OBJ];
 #pragma unroll
-        for (int o = 0; o < 3; ++o) { mine[o].p = inf; mine[o].s = 0.0; mine[o].idx = ~0ull; }
+        for (int o = 0; o < N_OBJ; ++o) { mine[o].p = inf; mine[o].s = 0.0; mine[o].idx = ~0ull; }
 #pragma unroll
         for (int c9 = 0; c9 < 9; ++c9) {
             const uint64_t combo_rows = row_base + 30000ull * (c9 % 3) + 90000ull * (c9 / 3);
@@ -752,9 +767,15 @@ __global__ __launch_bounds__(SEARCH_THREADS, (MASK == 5 || MASK == 6 || MASK == 
                     mine[2].idx = (uint64_t)(t0 + codeLE[c9]) + (uint64_t)a.mc.T * combo_rows;
                 }
             }
+            if constexpr (MASK & 8) {
+                if (bestP[c9] < mine[3].p) {
+                    mine[3].p = bestP[c9];
+                    mine[3].idx = (uint64_t)(t0 + codeP[c9]) + (uint64_t)a.mc.T * combo_rows;
+                }
+            }
         }
 #pragma unroll
-        for (int o = 0; o < 3; ++o) {
+        for (int o = 0; o < N_OBJ; ++o) {
             if (!((MASK >> o) & 1)) continue;
             // a lane that found nothing feasible must not win a tie between infinities
             if (!(mine[o].p < inf)) { mine[o].s = 0.0; mine[o].idx = ~0ull; }
@@ -767,12 +788,12 @@ __global__ __launch_bounds__(SEARCH_THREADS, (MASK == 5 || MASK == 6 || MASK == 
     __syncthreads();
     if (threadIdx.x == 0) {
 #pragma unroll
-        for (int o = 0; o < 3; ++o) {
+        for (int o = 0; o < N_OBJ; ++o) {
             if (!((MASK >> o) & 1)) continue;
             Key k = wave_best[o][0];
             for (int wv = 1; wv < SEARCH_THREADS / 64; ++wv)
                 if (key_less(wave_best[o][wv], k)) k = wave_best[o][wv];
-            Key *dst = a.partials + (uint64_t)blockIdx.x * 3 + o;
+            Key *dst = a.partials + (uint64_t)blockIdx.x * N_OBJ + o;
             __hip_atomic_store(&dst->idx, k.idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(reinterpret_cast<uint64_t *>(&dst->p), (uint64_t)__double_as_longlong(k.p),
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -789,11 +810,11 @@ __global__ __launch_bounds__(SEARCH_THREADS, (MASK == 5 || MASK == 6 || MASK == 
     // the last block to finish reduces every block's record
     __threadfence();
 #pragma unroll
-    for (int o = 0; o < 3; ++o) {
+    for (int o = 0; o < N_OBJ; ++o) {
         if (!((MASK >> o) & 1)) continue;
         Key k; k.p = inf; k.s = 0.0; k.idx = ~0ull;
         for (uint32_t b = threadIdx.x; b < gridDim.x; b += SEARCH_THREADS) {
-            Key *src = a.partials + (uint64_t)b * 3 + o;
+            Key *src = a.partials + (uint64_t)b * N_OBJ + o;
             Key c;
             c.idx = __hip_atomic_load(&src->idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             c.p = __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<uint64_t *>(&src->p),
@@ -806,7 +827,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, (MASK == 5 || MASK == 6 || MASK == 
         if (lane == 0) wave_best[o][wave] = k;
     }
     __syncthreads();
-    if (threadIdx.x < 3 && ((MASK >> threadIdx.x) & 1)) {
+    if (threadIdx.x < N_OBJ && ((MASK >> threadIdx.x) & 1)) {
         const int o = threadIdx.x;
         Key k = wave_best[o][0];
         for (int wv = 1; wv < SEARCH_THREADS / 64; ++wv)

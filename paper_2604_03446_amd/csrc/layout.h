@@ -81,6 +81,8 @@ struct ModelConst {
     uint32_t T, tpad;
 };
 
+constexpr int N_OBJ = 4;         // energy, latency, latency-then-energy, energy-delay product
+
 struct Key {            // lexicographic objective key, lowest index wins ties
     double p, s;
     uint64_t idx;

@@ -205,7 +205,7 @@ int ensure_partials(size_t nblocks)
     if (nblocks <= S.partials_cap) return MMEE_OK;
     if (S.partials) { HIP_TRY(hipStreamSynchronize(S.stream)); (void)hipFree(S.partials); }
     S.partials = nullptr; S.partials_cap = 0;
-    HIP_TRY(hipMalloc(&S.partials, sizeof(Key) * 3 * nblocks));
+    HIP_TRY(hipMalloc(&S.partials, sizeof(Key) * N_OBJ * nblocks));
     S.partials_cap = nblocks;
     return MMEE_OK;
 }
@@ -219,9 +219,9 @@ int ensure_slots(size_t n)
         (void)hipHostFree(S.final_host); (void)hipHostFree(S.dv_host);
     }
     S.slots = 0;
-    HIP_TRY(hipMalloc(&S.final_dev, sizeof(FinalRecord) * 3 * n));
+    HIP_TRY(hipMalloc(&S.final_dev, sizeof(FinalRecord) * N_OBJ * n));
     HIP_TRY(hipMalloc(&S.dv_dev, sizeof(DivTable) * n));
-    HIP_TRY(hipHostMalloc(&S.final_host, sizeof(FinalRecord) * 3 * n));
+    HIP_TRY(hipHostMalloc(&S.final_host, sizeof(FinalRecord) * N_OBJ * n));
     HIP_TRY(hipHostMalloc(&S.dv_host, sizeof(DivTable) * n));
     while (S.events.size() < 2 * n) {
         hipEvent_t e;
@@ -249,10 +249,18 @@ void launch_search_mask(bool exact_k, dim3 grid, const SearchArgs &a)
     else hipLaunchKernelGGL((k_search<MASK, false>), grid, dim3(SEARCH_THREADS), 0, S.stream, a);
 }
 
-// enqueue one pass (tables + search + readback of the final records) into slot `slot`
-int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_t *evaluated)
+// one step of the Pareto walk: latency-then-energy among candidates with energy below a.e_limit
+void launch_search_limited(bool exact_k, dim3 grid, const SearchArgs &a)
 {
-    int rc = launch_tilings(p);
+    if (exact_k) hipLaunchKernelGGL((k_search<4, true, true>), grid, dim3(SEARCH_THREADS), 0, S.stream, a);
+    else hipLaunchKernelGGL((k_search<4, false, true>), grid, dim3(SEARCH_THREADS), 0, S.stream, a);
+}
+
+// enqueue one pass (tables + search + readback of the final records) into slot `slot`
+int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_t *evaluated,
+                   const double *e_limit = nullptr, bool build_tables = true)
+{
+    int rc = build_tables ? launch_tilings(p) : MMEE_OK;
     if (rc) return rc;
     const int which = (flags & MMEE_SEARCH_EXHAUSTIVE) ? 0 : 1;
     SearchArgs a;
@@ -279,12 +287,17 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     rc = ensure_partials(nblocks);
     if (rc) return rc;
     a.partials = S.partials; a.ticket = S.ticket; a.work_counter = S.ticket + 1;
-    a.final_out = S.final_dev + 3 * slot;
+    a.final_out = S.final_dev + N_OBJ * slot;
     a.dv = S.dv_dev + slot;
     S.dv_host[slot] = p.dv;
     HIP_TRY(hipMemcpyAsync(S.dv_dev + slot, S.dv_host + slot, sizeof(DivTable), hipMemcpyHostToDevice, S.stream));
     HIP_TRY(hipEventRecord(S.events[2 * slot], S.stream));
     dim3 grid((uint32_t)nblocks);
+    if (e_limit) {
+        if (mask != 4) return MMEE_EINVAL;
+        a.e_limit = *e_limit;
+        launch_search_limited(p.exact_k, grid, a);
+    } else
     switch (mask) {
     case 1: launch_search_mask<1>(p.exact_k, grid, a); break;
     case 2: launch_search_mask<2>(p.exact_k, grid, a); break;
@@ -293,11 +306,19 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     case 5: launch_search_mask<5>(p.exact_k, grid, a); break;
     case 6: launch_search_mask<6>(p.exact_k, grid, a); break;
     case 7: launch_search_mask<7>(p.exact_k, grid, a); break;
+    case 8: launch_search_mask<8>(p.exact_k, grid, a); break;
+    case 9: launch_search_mask<9>(p.exact_k, grid, a); break;
+    case 10: launch_search_mask<10>(p.exact_k, grid, a); break;
+    case 11: launch_search_mask<11>(p.exact_k, grid, a); break;
+    case 12: launch_search_mask<12>(p.exact_k, grid, a); break;
+    case 13: launch_search_mask<13>(p.exact_k, grid, a); break;
+    case 14: launch_search_mask<14>(p.exact_k, grid, a); break;
+    case 15: launch_search_mask<15>(p.exact_k, grid, a); break;
     default: return MMEE_EINVAL;
     }
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(S.events[2 * slot + 1], S.stream));
-    HIP_TRY(hipMemcpyAsync(S.final_host + 3 * slot, S.final_dev + 3 * slot, sizeof(FinalRecord) * 3,
+    HIP_TRY(hipMemcpyAsync(S.final_host + N_OBJ * slot, S.final_dev + N_OBJ * slot, sizeof(FinalRecord) * N_OBJ,
                            hipMemcpyDeviceToHost, S.stream));
     *evaluated = nrows * p.T * 9ull;
     return MMEE_OK;
@@ -306,7 +327,7 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
 int unpack_result(const Plan &p, size_t slot, int objective, uint64_t evaluated, double seconds, double ksec,
                   mmee_result *out)
 {
-    const FinalRecord &fr = S.final_host[3 * slot + objective];
+    const FinalRecord &fr = S.final_host[N_OBJ * slot + objective];
     std::memset(out, 0, sizeof(*out));
     std::memcpy(&out->cost, fr.cost, sizeof(mmee_cost));
     std::memcpy(&out->best, fr.map, sizeof(mmee_mapping));
@@ -480,7 +501,7 @@ int mmee_chain_search_many(const mmee_chain *w, const mmee_hw *hw, const int *ob
         uint32_t b = a;
         while (b < count && same_problem(w[a], hw[a], w[b], hw[b])) {
             int o = objectives[b];
-            if (o < 0 || o > 2) { if (!ps.rc) ps.rc = MMEE_EINVAL; }
+            if (o < 0 || o >= N_OBJ) { if (!ps.rc) ps.rc = MMEE_EINVAL; }
             else if (ps.mask & (1 << o)) break;      // same objective twice: start a new pass
             else ps.mask |= 1 << o;
             ++b; ++ps.n;
@@ -518,18 +539,69 @@ int mmee_chain_search_many(const mmee_chain *w, const mmee_hw *hw, const int *ob
 int mmee_chain_search_multi(const mmee_chain *w, const mmee_hw *hw, const int *objectives, uint32_t n_obj,
                             uint32_t flags, mmee_result *out)
 {
-    if (!w || !hw || !objectives || !out || n_obj < 1 || n_obj > 3) return MMEE_EINVAL;
+    if (!w || !hw || !objectives || !out || n_obj < 1 || n_obj > N_OBJ) return MMEE_EINVAL;
     int seen = 0;
     for (uint32_t a = 0; a < n_obj; ++a) {
-        if (objectives[a] < 0 || objectives[a] > 2 || (seen & (1 << objectives[a]))) return MMEE_EINVAL;
+        if (objectives[a] < 0 || objectives[a] >= N_OBJ || (seen & (1 << objectives[a]))) return MMEE_EINVAL;
         seen |= 1 << objectives[a];
     }
-    mmee_chain ws[3] = {*w, *w, *w};
-    mmee_hw hs[3] = {*hw, *hw, *hw};
+    mmee_chain ws[N_OBJ] = {*w, *w, *w, *w};
+    mmee_hw hs[N_OBJ] = {*hw, *hw, *hw, *hw};
     return mmee_chain_search_many(ws, hs, objectives, n_obj, flags, out, nullptr);
 }
 
+// Walk along the front by ascending latency: each step is the latency-then-energy optimum among
+// the candidates whose energy is strictly below the previous point's (Sec. VII-C).
+int mmee_chain_pareto(const mmee_chain *w, const mmee_hw *hw, uint32_t flags, mmee_result *out, uint32_t capacity,
+                      uint32_t *n_points)
+{
+    if (!w || !hw || !out || !n_points || !capacity) return MMEE_EINVAL;
+    if (flags & ~(uint32_t)MMEE_SEARCH_EXHAUSTIVE) return MMEE_EINVAL;
+    *n_points = 0;
+    Plan p;
+    int rc = make_plan(w, hw, p);
+    if (rc) return rc;
+    std::lock_guard<std::mutex> guard(g_lock);
+    const double t_start = now_seconds();
+    rc = ensure_ready();
+    if (rc) return rc;
+    rc = ensure_slots(1);
+    if (rc) return rc;
+    double limit = INFINITY, ksec = 0.0;
+    uint64_t evaluated = 0;
+    for (uint32_t k = 0;; ++k) {
+        uint64_t ev = 0;
+        rc = enqueue_search(p, 4, flags, 0, &ev, &limit, k == 0);
+        if (rc) return rc;
+        HIP_TRY(hipStreamSynchronize(S.stream));
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, S.events[0], S.events[1]);
+        ksec += ms * 1e-3;
+        evaluated += ev;
+        mmee_result r;
+        rc = unpack_result(p, 0, MMEE_OBJ_LATENCY_THEN_ENERGY, 0, 0.0, 0.0, &r);
+        if (rc == MMEE_ENOFEASIBLE) break;          // nothing cheaper is left: the front is complete
+        if (k == capacity) return MMEE_EOVERFLOW;   // out holds the first `capacity` points
+        out[k] = r;
+        *n_points = k + 1;
+        limit = r.cost.energy_pj;
+    }
+    const double seconds = now_seconds() - t_start;
+    for (uint32_t k = 0; k < *n_points; ++k) {
+        out[k].evaluated = evaluated; out[k].seconds = seconds; out[k].kernel_seconds = ksec;
+    }
+    return *n_points ? MMEE_OK : MMEE_ENOFEASIBLE;
+}
+
 // ---- attention workloads: the chain I = L = N, K = J = d, batch = B*H --------------------------
+
+int mmee_pareto(const mmee_workload *w, const mmee_hw *hw, uint32_t flags, mmee_result *out, uint32_t capacity,
+                uint32_t *n_points)
+{
+    mmee_chain c;
+    int rc = chain_of(w, c);
+    return rc ? rc : mmee_chain_pareto(&c, hw, flags, out, capacity, n_points);
+}
 
 int mmee_space_size(const mmee_workload *w, const mmee_hw *hw, uint64_t *out)
 {
@@ -608,6 +680,7 @@ const char *mmee_strerror(int code)
     case MMEE_ERANGE: return "candidate index out of range";
     case MMEE_ENOFEASIBLE: return "no feasible candidate";
     case MMEE_EDEVICE: return g_last_error[0] ? g_last_error : "HIP device error";
+    case MMEE_EOVERFLOW: return "the Pareto front has more points than the caller made room for";
     default: return "unknown error";
     }
 }

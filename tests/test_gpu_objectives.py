@@ -1,0 +1,118 @@
+"""GPU parity for the energy-delay-product objective (Sec. VII-I) and the energy-latency Pareto
+front (Sec. VI-A, Sec. VII-C) against the oracle."""
+import json
+import os
+
+import pytest
+
+import oracle as O
+from inputs import CHAINS, CONFIGS
+from test_gpu_parity import INT_FIELDS, SMALL, check_result_against_oracle
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+MULTI_POINT = (dict(B=1, H=1, N=16, d=4, word_bytes=2, tiling_mode=1, c_softmax=10),
+               dict(pe_rows=4, pe_cols=4, n_arrays=1, rf_bytes=16, gb_bytes=300,
+                    e_dram=200.0, e_gb=6.0, e_rf=1.0, e_mac=1.0, dram_bw=1.0, gb_bw=2.0))
+
+
+@pytest.fixture(scope="module")
+def M():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2604_03446_amd as mod
+    return mod
+
+
+@pytest.mark.parametrize("case", range(len(SMALL) + 1))
+def test_edp_and_all_objectives_small_spaces(M, case):
+    w, h = (SMALL + [MULTI_POINT])[case]
+    ow, oh = O.workload(w), O.hw(h)
+    rc, idx, cost, _, _ = O.search_all(ow, oh)
+    assert rc == 0
+    for flags in (M.SEARCH_EXHAUSTIVE, M.SEARCH_PRUNED):
+        single = M.mmee_search_ex(w, h, M.OBJ_EDP, flags)
+        four = M.mmee_search_multi(w, h, [3, 0, 2, 1], flags)        # any order of distinct objectives
+        pair = M.mmee_search_multi(w, h, [0, 3], flags)
+        for res, obj in [(single, 3), (four[0], 3), (four[1], 0), (four[2], 2), (four[3], 1), (pair[0], 0), (pair[1], 3)]:
+            assert res.best.idx == idx[obj], (case, flags, obj)
+            assert res.cost.energy_pj == cost[obj].energy_pj and res.cost.latency_cycles == cost[obj].latency_cycles
+            check_result_against_oracle(res, ow, oh)
+
+
+def test_edp_full_configs_against_stored_oracle_optima(M):
+    with open(os.path.join(GOLDEN, "expected_optima.json")) as fh:
+        exp = json.load(fh)
+    for name, cfg in list(CONFIGS.items()) + [("chain_" + k, v) for k, v in CHAINS.items()]:
+        want = exp[name]["best"]["edp"]
+        search = M.mmee_chain_search_multi if name.startswith("chain_") else M.mmee_search_multi
+        for flags in (M.SEARCH_PRUNED, M.SEARCH_EXHAUSTIVE):
+            res = search(cfg["workload"], cfg["hw"], [M.OBJ_EDP], flags)[0]
+            assert res.best.idx == want["idx"], (name, flags)
+            assert res.cost.energy_pj == float.fromhex(want["energy_pj"])
+            assert res.cost.latency_cycles == float.fromhex(want["latency_cycles"])
+            for fld in INT_FIELDS:
+                assert getattr(res.cost, fld) == want[fld]
+
+
+def check_front(front, ow, oh):
+    for a, b in zip(front, front[1:]):
+        assert a.cost.latency_cycles < b.cost.latency_cycles and a.cost.energy_pj > b.cost.energy_pj
+    for p in front:
+        check_result_against_oracle(p, ow, oh)
+
+
+@pytest.mark.parametrize("case", range(len(SMALL) + 1))
+def test_pareto_small_spaces_against_oracle(M, case):
+    w, h = (SMALL + [MULTI_POINT])[case]
+    ow, oh = O.workload(w), O.hw(h)
+    rc, idx, cost = O.pareto(ow, oh)
+    assert rc == 0
+    for flags in (M.SEARCH_EXHAUSTIVE, M.SEARCH_PRUNED):
+        code, front = M.mmee_pareto(w, h, flags)
+        assert code == 0 and [p.best.idx for p in front] == idx, (case, flags)
+        for p, c in zip(front, cost):
+            assert p.cost.energy_pj == c.energy_pj and p.cost.latency_cycles == c.latency_cycles
+        check_front(front, ow, oh)
+    if case == len(SMALL):
+        assert len(idx) >= 3
+        code, front = M.mmee_pareto(w, h, M.SEARCH_PRUNED, capacity=2)
+        assert code == M.EOVERFLOW and [p.best.idx for p in front] == idx[:2]
+    code, front = M.mmee_pareto(w, dict(h, gb_bytes=4))
+    assert code == M.ENOFEASIBLE and front == []
+
+
+def test_pareto_tiny_against_oracle_full_enumeration(M):
+    cfg = CONFIGS["tiny"]
+    w, h = cfg["workload"], cfg["hw"]
+    ow, oh = O.workload(w), O.hw(h)
+    rc, idx, cost = O.pareto(ow, oh)
+    assert rc == 0
+    for flags in (M.SEARCH_PRUNED, M.SEARCH_EXHAUSTIVE):
+        code, front = M.mmee_pareto(w, h, flags)
+        assert code == 0 and [p.best.idx for p in front] == idx
+        check_front(front, ow, oh)
+    print("tiny front:", [(p.cost.latency_cycles, p.cost.energy_pj) for p in front], flush=True)
+
+
+@pytest.mark.parametrize("name", ["bert", "prefill", "long"])
+def test_pareto_full_configs_pruned_equals_exhaustive(M, name):
+    """At full size the front's two ends are pinned by the stored single-objective optima; the
+    pruned and the exhaustive walk must agree point by point."""
+    with open(os.path.join(GOLDEN, "expected_optima.json")) as fh:
+        exp = json.load(fh)[name]
+    cfg = CONFIGS[name]
+    w, h = cfg["workload"], cfg["hw"]
+    cp, pruned = M.mmee_pareto(w, h, M.SEARCH_PRUNED)
+    cx, full = M.mmee_pareto(w, h, M.SEARCH_EXHAUSTIVE)
+    assert cp == cx == 0 and [p.best.idx for p in pruned] == [p.best.idx for p in full]
+    check_front(pruned, O.workload(w), O.hw(h))
+    assert pruned[0].best.idx == exp["best"]["latency_then_energy"]["idx"]
+    assert pruned[-1].cost.energy_pj == float.fromhex(exp["best"]["energy"]["energy_pj"])
+    # the EDP optimum is a front point or shares its (energy, latency) with one
+    edp = exp["best"]["edp"]
+    assert any(p.cost.energy_pj == float.fromhex(edp["energy_pj"]) and
+               p.cost.latency_cycles == float.fromhex(edp["latency_cycles"]) for p in pruned)
+    print(name, "front:", [(p.cost.latency_cycles, p.cost.energy_pj) for p in pruned],
+          "kernel ms", full[0].kernel_seconds * 1e3, flush=True)
