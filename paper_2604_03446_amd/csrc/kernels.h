@@ -283,9 +283,15 @@ __device__ __forceinline__ void tile_cost(uint64_t m, uint64_t r, uint64_t n, in
 // One thread per tiling: decode the four tiling digits, derive the boundary vector and
 // store every subset product a row may select (entry-major, coalesced in the tiling).
 __global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__ btab, double *__restrict__ ctab_s,
-                                uint64_t *__restrict__ ctab_e)
+                                uint64_t *__restrict__ ctab_e, DivTable *__restrict__ dv_copy)
 {
     uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    // leave the divisor lists in device memory for the search's final record (index -> mapping)
+    if (dv_copy && blockIdx.x == 0) {
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(&dv);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(dv_copy);
+        for (uint32_t a = threadIdx.x; a < sizeof(DivTable) / 4; a += blockDim.x) dst[a] = src[a];
+    }
     if (t >= mc.T) return;
     uint64_t G[4], D[4];
     uint32_t x = t;

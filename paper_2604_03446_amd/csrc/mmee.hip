@@ -47,7 +47,7 @@ struct State {
     size_t partials_cap = 0;
     uint32_t *ticket = nullptr;
     FinalRecord *final_dev = nullptr, *final_host = nullptr;
-    DivTable *dv_dev = nullptr, *dv_host = nullptr;
+    DivTable *dv_dev = nullptr;
     size_t slots = 0;
     std::vector<hipEvent_t> events;
     void *eval_dev = nullptr;
@@ -216,13 +216,12 @@ int ensure_slots(size_t n)
     if (S.final_dev) {
         HIP_TRY(hipStreamSynchronize(S.stream));
         (void)hipFree(S.final_dev); (void)hipFree(S.dv_dev);
-        (void)hipHostFree(S.final_host); (void)hipHostFree(S.dv_host);
+        (void)hipHostFree(S.final_host);
     }
     S.slots = 0;
     HIP_TRY(hipMalloc(&S.final_dev, sizeof(FinalRecord) * N_OBJ * n));
     HIP_TRY(hipMalloc(&S.dv_dev, sizeof(DivTable) * n));
     HIP_TRY(hipHostMalloc(&S.final_host, sizeof(FinalRecord) * N_OBJ * n));
-    HIP_TRY(hipHostMalloc(&S.dv_host, sizeof(DivTable) * n));
     while (S.events.size() < 2 * n) {
         hipEvent_t e;
         HIP_TRY(hipEventCreate(&e));
@@ -232,12 +231,12 @@ int ensure_slots(size_t n)
     return MMEE_OK;
 }
 
-int launch_tilings(const Plan &p)
+int launch_tilings(const Plan &p, DivTable *dv_copy = nullptr)
 {
     int rc = ensure_tilings(p.mc.tpad);
     if (rc) return rc;
     hipLaunchKernelGGL(k_build_tilings, dim3((p.mc.T + 255) / 256), dim3(256), 0, S.stream, p.dv, p.mc, S.btab,
-                       S.ctab_s, S.ctab_e);
+                       S.ctab_s, S.ctab_e, dv_copy);
     HIP_TRY(hipGetLastError());
     return MMEE_OK;
 }
@@ -260,7 +259,8 @@ void launch_search_limited(bool exact_k, dim3 grid, const SearchArgs &a)
 int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_t *evaluated,
                    const double *e_limit = nullptr, bool build_tables = true)
 {
-    int rc = build_tables ? launch_tilings(p) : MMEE_OK;
+    if (slot >= S.slots) return MMEE_EINVAL;
+    int rc = build_tables ? launch_tilings(p, S.dv_dev + slot) : MMEE_OK;
     if (rc) return rc;
     const int which = (flags & MMEE_SEARCH_EXHAUSTIVE) ? 0 : 1;
     SearchArgs a;
@@ -289,8 +289,6 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     a.partials = S.partials; a.ticket = S.ticket; a.work_counter = S.ticket + 1;
     a.final_out = S.final_dev + N_OBJ * slot;
     a.dv = S.dv_dev + slot;
-    S.dv_host[slot] = p.dv;
-    HIP_TRY(hipMemcpyAsync(S.dv_dev + slot, S.dv_host + slot, sizeof(DivTable), hipMemcpyHostToDevice, S.stream));
     HIP_TRY(hipEventRecord(S.events[2 * slot], S.stream));
     dim3 grid((uint32_t)nblocks);
     if (e_limit) {
@@ -665,7 +663,6 @@ void mmee_shutdown(void)
     (void)hipFree(S.partials); (void)hipFree(S.ticket);
     (void)hipFree(S.final_dev); (void)hipFree(S.dv_dev); (void)hipFree(S.eval_dev);
     if (S.final_host) (void)hipHostFree(S.final_host);
-    if (S.dv_host) (void)hipHostFree(S.dv_host);
     for (hipEvent_t e : S.events) (void)hipEventDestroy(e);
     hipStream_t keep = S.stream;
     S = State();
