@@ -492,7 +492,11 @@ typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 #define MMEE_EVAL_NT 1
 #endif
 
-// Work unit = 64 consecutive tilings of one index row, one wave each (4 units per block).
+// Work unit = 64 consecutive tilings of one index row, one wave each (4 units per block).  Unit
+// boundaries are shifted per row so that every unit starts at a multiple of EVAL_ALIGN records
+// (1 KiB) in the output buffer: each store instruction then covers whole, aligned kilobytes.
+constexpr uint32_t EVAL_ALIGN = 16;
+
 __global__ __launch_bounds__(256) void k_eval_batch(EvalArgs a, uint64_t first_idx, uint64_t n, uint32_t row_first,
                                                     uint32_t units_per_row, uint32_t n_units, v4u *__restrict__ out)
 {
@@ -502,7 +506,9 @@ __global__ __launch_bounds__(256) void k_eval_batch(EvalArgs a, uint64_t first_i
     const uint32_t unit = blockIdx.x * 4 + wave;
     if (unit >= n_units) return;
     const uint32_t row = row_first + unit / units_per_row;
-    const uint32_t t = (unit % units_per_row) * 64 + lane;
+    // first tiling of the row sits at output record row*T - first_idx; back off to the alignment
+    const uint32_t shift = (uint32_t)(((uint64_t)row * a.mc.T - first_idx) % EVAL_ALIGN);
+    const uint32_t t = (unit % units_per_row) * 64 + lane - shift;           // wraps for the lanes before the row
     const uint64_t T = a.mc.T;
     const uint64_t idx = (uint64_t)row * T + t;
     const bool on = t < T && idx >= first_idx && idx - first_idx < n;
@@ -520,7 +526,8 @@ __global__ __launch_bounds__(256) void k_eval_batch(EvalArgs a, uint64_t first_i
     const unsigned long long mask = __ballot(on);
     // the wave's 64 records are consecutive in the output; lane L moves piece (L & 3) of
     // record 16 k + L / 4 on pass k
-    const uint64_t wave_first = (uint64_t)row * T + (t - lane);   // index of lane 0's candidate
+    // index of lane 0's candidate (before the row's first tiling when the unit was backed off)
+    const uint64_t wave_first = (uint64_t)row * T + (uint64_t)(int64_t)(int32_t)(t - lane);
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         uint32_t rec = 16 * k + (lane >> 2);

@@ -443,7 +443,7 @@ int mmee_chain_eval_batch(const mmee_chain *w, const mmee_hw *hw, uint64_t first
 
     EvalArgs ea;
     ea.enc = S.enc; ea.btab = S.btab; ea.ctab_e = S.ctab_e; ea.mc = p.mc;
-    const uint32_t upr = (uint32_t)((p.T + 63) / 64);      // 64-tiling units per index row
+    const uint32_t upr = (uint32_t)((p.T + EVAL_ALIGN - 1 + 63) / 64);      // 64-tiling units per index row
     // records per launch: 1 GiB of staging for host output, one launch (grid limit) for device output
     uint64_t CHUNK = on_device ? (1ull << 30) : (1ull << 24);
     CHUNK = std::min<uint64_t>(CHUNK, std::max<uint64_t>(1, (1ull << 29) / upr) * p.T);   // grid size limit

@@ -53,3 +53,25 @@ def test_host_only_calls():
     # a workload whose counts would not stay exact integers in fp64 is refused, not approximated
     with pytest.raises(M.MmeeError):
         M.mmee_space_size(dict(CONFIGS["tiny"]["workload"], N=1 << 20, d=1 << 10, H=1 << 10), CONFIGS["tiny"]["hw"])
+
+
+def test_host_factorisation_matches_naive_divisor_counts():
+    """The online tiling enumeration (integer factorisation of every extent) is host logic:
+    the space size must be the product of the divisor counts times 540000, in both tiling modes."""
+    import paper_2604_03446_amd as M
+    hw = dict(pe_rows=4, pe_cols=4, n_arrays=1, rf_bytes=64, gb_bytes=1 << 20,
+              e_dram=200.0, e_gb=6.0, e_rf=1.0, e_mac=1.0, dram_bw=64.0, gb_bw=256.0)
+
+    def nd(x, mode):
+        return sum(1 for g in range(1, x + 1) if x % g == 0 and (mode == 1 or g & (g - 1) == 0))
+
+    for I, K, L, J in [(1, 1, 1, 1), (97, 2, 3, 5), (360, 48, 1000, 7), (720, 36, 49, 1024), (5040, 1, 2, 3)]:
+        for mode in (0, 1):
+            c = dict(batch=1, I=I, K=K, L=L, J=J, word_bytes=2, tiling_mode=mode, c_softmax=0)
+            assert M.mmee_chain_space_size(c, hw) == nd(I, mode) * nd(K, mode) * nd(L, mode) * nd(J, mode) * 540000
+    # attention is the chain I = L = N, K = J = d
+    w = dict(B=2, H=3, N=360, d=48, word_bytes=2, tiling_mode=1, c_softmax=10)
+    assert M.mmee_space_size(w, hw) == (nd(360, 1) * nd(48, 1)) ** 2 * 540000
+    # an extent with more divisors than the tables hold is refused
+    with pytest.raises(M.MmeeError):
+        M.mmee_chain_space_size(dict(batch=1, I=1441440, K=1, L=1, J=1, word_bytes=2, tiling_mode=1, c_softmax=0), hw)
