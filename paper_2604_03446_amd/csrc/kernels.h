@@ -266,17 +266,19 @@ __global__ void k_compact_rows(const uint8_t *__restrict__ flags, uint32_t *rows
 // ---------------------------------------------------------------------------
 // online stage: the boundary side
 
-__device__ __forceinline__ uint64_t cdiv(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+// tile extents are 32-bit; only the column capacity C*g can exceed 32 bits (then one fold suffices)
+__device__ __forceinline__ uint64_t cdiv(uint32_t a, uint64_t b) { return b > a ? 1u : (a - 1u) / (uint32_t)b + 1u; }
 
 // words crossing buffer<->RF and cycles of one tile matmul m x r x n; mode 0 WS, 1 IS, 2 OS
-__device__ __forceinline__ void tile_cost(uint64_t m, uint64_t r, uint64_t n, int mode, uint64_t R, uint64_t C,
-                                          uint64_t g, uint64_t &words, uint64_t &cycles)
+__device__ __forceinline__ void tile_cost(uint32_t m, uint32_t r, uint32_t n, int mode, uint32_t R, uint32_t C,
+                                          uint32_t g, uint64_t &words, uint64_t &cycles)
 {
-    uint64_t rows_dim = mode == 0 ? r : m;                 // spread over PE rows
-    uint64_t cols_dim = mode == 1 ? r : n;                 // spread over PE columns
+    uint32_t rows_dim = mode == 0 ? r : m;                 // spread over PE rows
+    uint32_t cols_dim = mode == 1 ? r : n;                 // spread over PE columns
     uint64_t time_dim = mode == 0 ? m : (mode == 1 ? n : r);
     uint64_t row_folds = cdiv(rows_dim, R);
-    words = rows_dim * cols_dim + time_dim * rows_dim * cdiv(cols_dim, C * g) + time_dim * cols_dim * row_folds;
+    words = (uint64_t)rows_dim * cols_dim + time_dim * rows_dim * cdiv(cols_dim, (uint64_t)C * g) +
+            time_dim * cols_dim * row_folds;
     cycles = row_folds * cdiv(cols_dim, C) * time_dim;
 }
 
@@ -349,8 +351,8 @@ __global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__
     // stationary-mode dependent part: buffer<->RF words and cycles per tile stage
     uint64_t br1[3], cy1[3], br2[3], cy2[3];
     for (int s = 0; s < 3; ++s) {
-        tile_cost(G[DI], G[DK], G[DL], s, mc.pe_rows, mc.pe_cols, mc.g_words, br1[s], cy1[s]);
-        tile_cost(G[DI], G[DL], G[DJ], s, mc.pe_rows, mc.pe_cols, mc.g_words, br2[s], cy2[s]);
+        tile_cost((uint32_t)G[DI], (uint32_t)G[DK], (uint32_t)G[DL], s, mc.pe_rows, mc.pe_cols, mc.g_words, br1[s], cy1[s]);
+        tile_cost((uint32_t)G[DI], (uint32_t)G[DL], (uint32_t)G[DJ], s, mc.pe_rows, mc.pe_cols, mc.g_words, br2[s], cy2[s]);
     }
     const uint64_t I = dv.X[DI], K = dv.X[DK], L = dv.X[DL], J = dv.X[DJ];
     for (uint32_t r = 0; r < 2; ++r) {

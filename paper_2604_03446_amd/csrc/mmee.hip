@@ -235,7 +235,7 @@ int launch_tilings(const Plan &p, DivTable *dv_copy = nullptr)
 {
     int rc = ensure_tilings(p.mc.tpad);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_build_tilings, dim3((p.mc.T + 255) / 256), dim3(256), 0, S.stream, p.dv, p.mc, S.btab,
+    hipLaunchKernelGGL(k_build_tilings, dim3((p.mc.T + 63) / 64), dim3(64), 0, S.stream, p.dv, p.mc, S.btab,
                        S.ctab_s, S.ctab_e, dv_copy);
     HIP_TRY(hipGetLastError());
     return MMEE_OK;
