@@ -103,13 +103,15 @@ def lib() -> C.CDLL:
                                      C.c_uint64 * 4, Cost * 4, P(C.c_uint64), P(C.c_int)]
         L.orc_pareto.argtypes = [P(Chain), P(Hw), C.c_uint64, C.c_uint64, C.c_uint32,
                                  P(C.c_uint64), P(Cost), P(C.c_uint32)]
+        L.orc_front.argtypes = [P(Chain), P(Hw), C.c_int, C.c_uint64, C.c_uint64, C.c_uint32,
+                                P(C.c_uint64), P(Cost), P(C.c_uint32)]
         L.sim_run.argtypes = [C.c_uint32 * 4, C.c_uint32 * 4, C.c_uint8 * 4, C.c_uint8 * 4,
                               C.c_int, C.c_int, P(SimResult)]
         L.sim_tile_matmul.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_int,
                                       C.c_uint32, C.c_uint32, C.c_uint32,
                                       P(C.c_uint64), P(C.c_uint64), P(C.c_uint64)]
         for name in ("orc_from_attention", "orc_space_size", "orc_decode", "orc_eval", "orc_eval_mapping",
-                     "orc_eval_batch", "orc_search_range", "orc_search", "orc_search_all", "orc_pareto", "sim_run",
+                     "orc_eval_batch", "orc_search_range", "orc_search", "orc_search_all", "orc_pareto", "orc_front", "sim_run",
                      "sim_tile_matmul"):
             getattr(L, name).restype = C.c_int
         _lib = L
@@ -195,6 +197,16 @@ def pareto(w: Chain, h: Hw, capacity: int = 1024, first_idx: int | None = None, 
         first_idx, n = 0, space_size(w, h)
     idx, cost, cnt = (C.c_uint64 * capacity)(), (Cost * capacity)(), C.c_uint32()
     rc = lib().orc_pareto(C.byref(w), C.byref(h), first_idx, n, capacity, idx, cost, C.byref(cnt))
+    return rc, list(idx[:cnt.value]), list(cost[:cnt.value])
+
+
+def front_bs_da(w: Chain, h: Hw, capacity: int = 1024, first_idx: int | None = None, n: int | None = None):
+    """DRAM access versus buffer size front over all dataflows.  Returns (rc, [idx], [Cost]) by
+    ascending buffer size."""
+    if first_idx is None:
+        first_idx, n = 0, space_size(w, h)
+    idx, cost, cnt = (C.c_uint64 * capacity)(), (Cost * capacity)(), C.c_uint32()
+    rc = lib().orc_front(C.byref(w), C.byref(h), 1, first_idx, n, capacity, idx, cost, C.byref(cnt))
     return rc, list(idx[:cnt.value]), list(cost[:cnt.value])
 
 

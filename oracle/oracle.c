@@ -614,11 +614,16 @@ static int front_insert(front_pt *f, int *n, int cap, double e, double l, uint64
     return 0;
 }
 
-int orc_pareto(const orc_chain *w, const orc_hw *hw, uint64_t first_idx, uint64_t n, uint32_t capacity,
-               uint64_t *idx_out, orc_cost *cost_out, uint32_t *n_out)
+/* kind 0: (energy, latency) over the feasible candidates, listed by ascending latency.
+ * kind 1: (DRAM access, buffer size requirement) over every candidate that denotes a dataflow,
+ *         whatever the buffer capacity (the DRAM-access-versus-buffer-size curve of Sec. VII-B),
+ *         listed by ascending buffer size. */
+int orc_front(const orc_chain *w, const orc_hw *hw, int kind, uint64_t first_idx, uint64_t n, uint32_t capacity,
+              uint64_t *idx_out, orc_cost *cost_out, uint32_t *n_out)
 {
     tiling_space ts;
     if (check_args(w, hw) || !idx_out || !cost_out || !n_out || !capacity || capacity > 4096) return -1;
+    if (kind < 0 || kind > 1) return -1;
     if (make_space(w, &ts)) return -1;
     uint64_t S = ts.n_tilings * ROWS_PER_TILING;
     if (first_idx > S || n > S - first_idx) return -2;
@@ -640,8 +645,13 @@ int orc_pareto(const orc_chain *w, const orc_hw *hw, uint64_t first_idx, uint64_
                 orc_cost c;
                 decode_idx(&ts, idx, &m);
                 eval_mapping(w, hw, &ts, &m, &c, 0);
-                if (!c.valid) continue;
-                if (front_insert(local, &nl, 4096, c.energy_pj, c.latency_cycles, idx)) bad = 1;
+                if (kind == 0) {
+                    if (!c.valid) continue;
+                    if (front_insert(local, &nl, 4096, c.energy_pj, c.latency_cycles, idx)) bad = 1;
+                } else {
+                    if (c.reason == 1) continue;
+                    if (front_insert(local, &nl, 4096, (double)c.da_words, (double)c.bs_words, idx)) bad = 1;
+                }
             }
         }
 #pragma omp critical
@@ -653,7 +663,7 @@ int orc_pareto(const orc_chain *w, const orc_hw *hw, uint64_t first_idx, uint64_
     }
     if (overflow || (uint32_t)ng > capacity) return -5;
     if (!ng) { *n_out = 0; return -3; }
-    /* ascending latency */
+    /* ascending latency (kind 0) / buffer size (kind 1) */
     for (int a = 1; a < ng; ++a) {
         front_pt key = global[a];
         int b = a - 1;
@@ -668,6 +678,12 @@ int orc_pareto(const orc_chain *w, const orc_hw *hw, uint64_t first_idx, uint64_
     }
     *n_out = (uint32_t)ng;
     return 0;
+}
+
+int orc_pareto(const orc_chain *w, const orc_hw *hw, uint64_t first_idx, uint64_t n, uint32_t capacity,
+               uint64_t *idx_out, orc_cost *cost_out, uint32_t *n_out)
+{
+    return orc_front(w, hw, 0, first_idx, n, capacity, idx_out, cost_out, n_out);
 }
 
 int orc_search(const orc_chain *w, const orc_hw *hw, int objective,

@@ -95,6 +95,34 @@ def test_pareto_front_matches_the_definition(k):
     assert idx[0] == sidx[O.OBJ_LATENCY_THEN_ENERGY]
 
 
+@pytest.mark.parametrize("k", range(len(CASES)))
+def test_dram_access_versus_buffer_size_front_matches_the_definition(k):
+    """Sec. VII-B plots minimum DRAM access against buffer size requirement: the non-dominated
+    (buffer size, DRAM access) pairs over every dataflow, whatever the buffer capacity."""
+    case = CASES[k]
+    w, h = O.workload(case["w"]), O.hw(case["h"])
+    T = O.space_size(w, h) // 540000
+    first, n = case["rows"][0] * T, case["rows"][1] * T
+    c = O.eval_batch(w, h, first, n)
+    real = c["reason"] != 1
+    BS = np.where(real, c["bs_words"].astype(np.float64), np.inf)
+    DA = np.where(real, c["da_words"].astype(np.float64), np.inf)
+    want = front_by_definition(DA, BS)            # ascending buffer size, strictly falling traffic
+    rc, idx, cost = O.front_bs_da(w, h, 1024, first, n)
+    assert rc == 0 and [i - first for i in idx] == want
+    assert len(want) >= 3
+    for i, cc in zip(want, cost):
+        assert cc.bs_words == BS[i] and cc.da_words == DA[i]
+    bs = [cc.bs_words for cc in cost]
+    da = [cc.da_words for cc in cost]
+    assert bs == sorted(bs) and da == sorted(da, reverse=True)
+    # the far end is the compulsory traffic: every matrix moved once
+    X = case["w"]
+    I, K, L, J = (X["I"], X["K"], X["L"], X["J"]) if "I" in X else (X["N"], X["d"], X["N"], X["d"])
+    if case["rows"][0] >= 270000:                 # fused rows: C never touches DRAM
+        assert da[-1] == I * K + K * L + L * J + I * J
+
+
 def test_pareto_front_has_several_points_somewhere():
     w, h, first, n, E, L = all_costs(0)
     assert len(front_by_definition(E, L)) >= 3
