@@ -174,6 +174,14 @@ int mmee_search_many(const mmee_workload *w, const mmee_hw *hw, const int *objec
 int mmee_pareto(const mmee_workload *w, const mmee_hw *hw, uint32_t flags, mmee_result *out,
                 uint32_t capacity, uint32_t *n_points);
 
+/* DRAM access versus buffer size requirement (Sec. VII-B): the dataflows that no other dataflow
+ * beats in both Eq. (4) and Eq. (7), whatever the buffer capacity of hw (their cost records carry
+ * valid = 0, reason = 2 where they exceed it).  Neither metric depends on the stationary modes;
+ * the lowest index stands for equal pairs.  Points come by ascending buffer size (descending
+ * DRAM access); conventions as for mmee_pareto.  `evaluated` counts (row, tiling) pairs. */
+int mmee_front_bs_da(const mmee_workload *w, const mmee_hw *hw, uint32_t flags, mmee_result *out,
+                     uint32_t capacity, uint32_t *n_points);
+
 /* The same calls for a free chain shape (Sec. VII-H).  Semantics, layouts and error codes are
  * those of the workload calls above. */
 int mmee_chain_space_size(const mmee_chain *c, const mmee_hw *hw, uint64_t *out);
@@ -187,6 +195,8 @@ int mmee_chain_search_many(const mmee_chain *c, const mmee_hw *hw, const int *ob
                            uint32_t count, uint32_t flags, mmee_result *out, int *rc);
 int mmee_chain_pareto(const mmee_chain *c, const mmee_hw *hw, uint32_t flags, mmee_result *out,
                       uint32_t capacity, uint32_t *n_points);
+int mmee_chain_front_bs_da(const mmee_chain *c, const mmee_hw *hw, uint32_t flags, mmee_result *out,
+                           uint32_t capacity, uint32_t *n_points);
 
 /* Runs the offline stage if needed (row encoding + symbolic pruning, once per process) and
  * reports its counts. */

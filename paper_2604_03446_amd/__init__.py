@@ -98,6 +98,8 @@ def _load() -> C.CDLL:
                                          P(C.c_int)]
     L.mmee_pareto.argtypes = [P(Workload), P(Hw), C.c_uint32, P(Result), C.c_uint32, P(C.c_uint32)]
     L.mmee_chain_pareto.argtypes = [P(Chain), P(Hw), C.c_uint32, P(Result), C.c_uint32, P(C.c_uint32)]
+    L.mmee_front_bs_da.argtypes = [P(Workload), P(Hw), C.c_uint32, P(Result), C.c_uint32, P(C.c_uint32)]
+    L.mmee_chain_front_bs_da.argtypes = [P(Chain), P(Hw), C.c_uint32, P(Result), C.c_uint32, P(C.c_uint32)]
     L.mmee_offline_stats.argtypes = [P(RowStats)]
     L.mmee_set_stream.argtypes = [C.c_void_p]
     L.mmee_shutdown.argtypes = []
@@ -107,7 +109,8 @@ def _load() -> C.CDLL:
     for name in ("mmee_space_size", "mmee_decode", "mmee_eval_batch", "mmee_search", "mmee_search_ex",
                  "mmee_search_multi", "mmee_search_many", "mmee_offline_stats", "mmee_set_stream",
                  "mmee_chain_space_size", "mmee_chain_decode", "mmee_chain_eval_batch",
-                 "mmee_chain_search_multi", "mmee_chain_search_many", "mmee_pareto", "mmee_chain_pareto"):
+                 "mmee_chain_search_multi", "mmee_chain_search_many", "mmee_pareto", "mmee_chain_pareto",
+                 "mmee_front_bs_da", "mmee_chain_front_bs_da"):
         getattr(L, name).restype = C.c_int
     return L
 
@@ -268,6 +271,15 @@ def mmee_pareto(w, h, flags: int = SEARCH_PRUNED, capacity: int = 256):
 
 def mmee_chain_pareto(c, h, flags: int = SEARCH_PRUNED, capacity: int = 256):
     return _pareto(_lib.mmee_chain_pareto, "mmee_chain_pareto", chain(c), h, flags, capacity)
+
+
+def mmee_front_bs_da(w, h, flags: int = SEARCH_PRUNED, capacity: int = 1024):
+    """DRAM access versus buffer size front by ascending buffer size.  Returns (code, [Result])."""
+    return _pareto(_lib.mmee_front_bs_da, "mmee_front_bs_da", workload(w), h, flags, capacity)
+
+
+def mmee_chain_front_bs_da(c, h, flags: int = SEARCH_PRUNED, capacity: int = 1024):
+    return _pareto(_lib.mmee_chain_front_bs_da, "mmee_chain_front_bs_da", chain(c), h, flags, capacity)
 
 
 def mmee_offline_stats() -> RowStats:

@@ -593,6 +593,85 @@ constexpr int SEARCH_THREADS = MMEE_THREADS;
 // keeps the optimiser from sinking a select below the operations that consume its result
 __device__ __forceinline__ void pin(double &x) { asm("" : "+v"(x)); }
 
+// Block and grid stages of the argmin: the waves' LDS slots -> one record per block -> ticket;
+// the last block to arrive reduces all records and writes the winner's cost and mapping.
+template <int MASK>
+__device__ __forceinline__ void finish_grid(const SearchArgs &a, Key (*wave_best)[SEARCH_THREADS / 64],
+                                            uint32_t *is_last_flag)
+{
+    const double inf = pos_inf();
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int o = 0; o < N_OBJ; ++o) {
+            if (!((MASK >> o) & 1)) continue;
+            Key k = wave_best[o][0];
+            for (int wv = 1; wv < SEARCH_THREADS / 64; ++wv)
+                if (key_less(wave_best[o][wv], k)) k = wave_best[o][wv];
+            Key *dst = a.partials + (uint64_t)blockIdx.x * N_OBJ + o;
+            __hip_atomic_store(&dst->idx, k.idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(reinterpret_cast<uint64_t *>(&dst->p), (uint64_t)__double_as_longlong(k.p),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(reinterpret_cast<uint64_t *>(&dst->s), (uint64_t)__double_as_longlong(k.s),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __threadfence();
+        uint32_t ticket = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        *is_last_flag = ticket == gridDim.x - 1;
+    }
+    __syncthreads();
+    if (!*is_last_flag) return;
+
+    // the last block to finish reduces every block's record
+    __threadfence();
+#pragma unroll
+    for (int o = 0; o < N_OBJ; ++o) {
+        if (!((MASK >> o) & 1)) continue;
+        Key k; k.p = inf; k.s = 0.0; k.idx = ~0ull;
+        for (uint32_t b = threadIdx.x; b < gridDim.x; b += SEARCH_THREADS) {
+            Key *src = a.partials + (uint64_t)b * N_OBJ + o;
+            Key c;
+            c.idx = __hip_atomic_load(&src->idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            c.p = __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<uint64_t *>(&src->p),
+                                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            c.s = __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<uint64_t *>(&src->s),
+                                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            if (key_less(c, k)) k = c;
+        }
+        k = wave_min(k);
+        if (lane == 0) wave_best[o][wave] = k;
+    }
+    __syncthreads();
+    if (threadIdx.x < N_OBJ && ((MASK >> threadIdx.x) & 1)) {
+        const int o = threadIdx.x;
+        Key k = wave_best[o][0];
+        for (int wv = 1; wv < SEARCH_THREADS / 64; ++wv)
+            if (key_less(wave_best[o][wv], k)) k = wave_best[o][wv];
+        FinalRecord *fr = a.final_out + o;
+        fr->key = k;
+        mmee_cost c;
+        mmee_mapping m;
+        if (k.p < inf) {
+            EvalArgs ea;
+            ea.enc = a.enc; ea.btab = a.btab; ea.ctab_e = a.ctab_e; ea.mc = a.mc;
+            eval_candidate(ea, (uint32_t)(k.idx / a.mc.T), (uint32_t)(k.idx % a.mc.T), c);
+            decode_candidate(*a.dv, a.mc.T, k.idx, m);
+        } else {
+            c.bs_words = c.da_words = c.br_words = c.mac_total = c.comp_cycles = 0;
+            c.energy_pj = inf; c.latency_cycles = inf; c.valid = 0; c.reason = 0;
+            for (int q = 0; q < 4; ++q) { m.xG[q] = m.xD[q] = 0; m.order[q] = m.level[q] = 0; }
+            m.idx = ~0ull; m.recompute = m.stat1 = m.stat2 = m.fused = 0;
+        }
+        const uint64_t *cs = reinterpret_cast<const uint64_t *>(&c);
+        for (int q = 0; q < 8; ++q) fr->cost[q] = cs[q];
+        uint64_t mbuf[7] = {0, 0, 0, 0, 0, 0, 0};
+        __builtin_memcpy(mbuf, &m, sizeof(mmee_mapping));
+        for (int q = 0; q < 7; ++q) fr->map[q] = mbuf[q];
+    }
+    if (threadIdx.x == 0) { *a.ticket = 0; *a.work_counter = 0; }   // ready for the next launch on this stream
+}
+
 // MASK: bit0 energy, bit1 latency, bit2 latency-then-energy, bit3 energy-delay product (Sec. VII-I).
 // FAST: DRAM bandwidth is 0 or a power of two and the array count is a power of two, so the
 // DRAM latency term is one exact multiply of the table value; otherwise it is divided out.
@@ -799,76 +878,75 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
         }
     }
 
-    // wave -> block -> grid
-    __syncthreads();
-    if (threadIdx.x == 0) {
-#pragma unroll
-        for (int o = 0; o < N_OBJ; ++o) {
-            if (!((MASK >> o) & 1)) continue;
-            Key k = wave_best[o][0];
-            for (int wv = 1; wv < SEARCH_THREADS / 64; ++wv)
-                if (key_less(wave_best[o][wv], k)) k = wave_best[o][wv];
-            Key *dst = a.partials + (uint64_t)blockIdx.x * N_OBJ + o;
-            __hip_atomic_store(&dst->idx, k.idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(reinterpret_cast<uint64_t *>(&dst->p), (uint64_t)__double_as_longlong(k.p),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(reinterpret_cast<uint64_t *>(&dst->s), (uint64_t)__double_as_longlong(k.s),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        __threadfence();
-        uint32_t ticket = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        is_last = ticket == gridDim.x - 1;
-    }
-    __syncthreads();
-    if (!is_last) return;
+    finish_grid<MASK>(a, wave_best, &is_last);
+}
 
-    // the last block to finish reduces every block's record
-    __threadfence();
+// One step of the buffer-size / DRAM-access front (Sec. VII-B): the (buffer size, DRAM access,
+// index)-smallest dataflow among those whose DRAM access is below a bound.  Neither metric depends
+// on the stationary modes, so a (row, tiling) pair stands for its nine combinations through the
+// lowest-index one, and the buffer capacity plays no part.  a.e_limit carries the bound in the
+// tables' unit, B*H words.  Same items, staging and finish as k_search; result in slot 0.
+__global__ __launch_bounds__(SEARCH_THREADS, 4) void k_front_step(SearchArgs a)
+{
+    __shared__ double tab[(TC + 1) * NENT];
+    __shared__ Key wave_best[N_OBJ][SEARCH_THREADS / 64];
+    __shared__ uint32_t is_last;
+    __shared__ uint32_t s_item;
+
+    const double inf = pos_inf();
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane < N_OBJ) { wave_best[lane][wave].p = inf; wave_best[lane][wave].s = 0.0; wave_best[lane][wave].idx = ~0ull; }
+
+    uint32_t upcoming = blockIdx.x;
+    while (true) {
+        if (threadIdx.x == 0) s_item = upcoming;
+        __syncthreads();
+        const uint32_t item = s_item;
+        if (item >= a.n_items) break;
+        if (threadIdx.x == 0)
+            upcoming = gridDim.x + __hip_atomic_fetch_add(a.work_counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t chunk = item % a.n_chunks;
+        const uint32_t rb = item / a.n_chunks;
+        uint32_t g = 0;
+        while (g < 3 && rb >= a.rb_start[g + 1]) ++g;
+        const uint32_t slot = (rb - a.rb_start[g]) * SEARCH_THREADS + threadIdx.x;
+        const bool live = slot < a.group_cnt[g];
+        const uint32_t dfrow = a.rows[a.group_off[g] + (live ? slot : 0)];
+        const uint4 e = a.enc[dfrow];
+        const uint32_t t0 = chunk * TC;
+        const uint32_t nt = min((uint32_t)TC, a.mc.T - t0);
+        for (uint32_t i = threadIdx.x; i < NENT * TC; i += SEARCH_THREADS) {
+            uint32_t ent = i / TC, tl = i % TC;
+            if (tl < nt) tab[tl * NENT + ent] = a.btab[(uint64_t)ent * a.mc.tpad + t0 + tl];
+        }
+        __syncthreads();
+        uint32_t off[NSEL];
 #pragma unroll
-    for (int o = 0; o < N_OBJ; ++o) {
-        if (!((MASK >> o) & 1)) continue;
-        Key k; k.p = inf; k.s = 0.0; k.idx = ~0ull;
-        for (uint32_t b = threadIdx.x; b < gridDim.x; b += SEARCH_THREADS) {
-            Key *src = a.partials + (uint64_t)b * N_OBJ + o;
-            Key c;
-            c.idx = __hip_atomic_load(&src->idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            c.p = __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<uint64_t *>(&src->p),
-                                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            c.s = __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<uint64_t *>(&src->s),
-                                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            if (key_less(c, k)) k = c;
+        for (int k = 0; k < NSEL; ++k) off[k] = sel_of(e, k);
+        const double bound = live ? a.e_limit : -1.0;        // a lane without a row takes no part
+        double best_bs = inf, best_da = inf;
+        uint32_t code = 0;
+        for (uint32_t tl = 0; tl < nt; ++tl) {
+            const double *row_tab = tab + tl * NENT;
+            double v[NSEL];
+#pragma unroll
+            for (int k = 0; k < NSEL; ++k) v[k] = row_tab[off[k]];
+            double bs = fmax(v[0] + v[2] + v[1], v[3] + v[2] + v[4]);   // Eq. (1), (2), (4)
+            double da = v[5] + v[6] + v[7];                             // B*H * Eq. (7)
+            bool lt = da < bound && (bs < best_bs || (bs == best_bs && da < best_da));
+            best_bs = lt ? bs : best_bs;
+            best_da = lt ? da : best_da;
+            code = lt ? tl : code;
         }
-        k = wave_min(k);
-        if (lane == 0) wave_best[o][wave] = k;
+        Key mine;
+        mine.p = best_bs; mine.s = best_da;
+        const uint64_t row_base = (uint64_t)(dfrow % ROWS_PER_GROUP) + 15000ull * (g & 1) + 270000ull * (g >> 1);
+        mine.idx = (uint64_t)(t0 + code) + (uint64_t)a.mc.T * row_base;
+        if (!(mine.p < inf)) { mine.s = 0.0; mine.idx = ~0ull; }
+        Key k = wave_min(mine);
+        if (lane == 0 && key_less(k, wave_best[0][wave])) wave_best[0][wave] = k;
     }
-    __syncthreads();
-    if (threadIdx.x < N_OBJ && ((MASK >> threadIdx.x) & 1)) {
-        const int o = threadIdx.x;
-        Key k = wave_best[o][0];
-        for (int wv = 1; wv < SEARCH_THREADS / 64; ++wv)
-            if (key_less(wave_best[o][wv], k)) k = wave_best[o][wv];
-        FinalRecord *fr = a.final_out + o;
-        fr->key = k;
-        mmee_cost c;
-        mmee_mapping m;
-        if (k.p < inf) {
-            EvalArgs ea;
-            ea.enc = a.enc; ea.btab = a.btab; ea.ctab_e = a.ctab_e; ea.mc = a.mc;
-            eval_candidate(ea, (uint32_t)(k.idx / a.mc.T), (uint32_t)(k.idx % a.mc.T), c);
-            decode_candidate(*a.dv, a.mc.T, k.idx, m);
-        } else {
-            c.bs_words = c.da_words = c.br_words = c.mac_total = c.comp_cycles = 0;
-            c.energy_pj = inf; c.latency_cycles = inf; c.valid = 0; c.reason = 0;
-            for (int q = 0; q < 4; ++q) { m.xG[q] = m.xD[q] = 0; m.order[q] = m.level[q] = 0; }
-            m.idx = ~0ull; m.recompute = m.stat1 = m.stat2 = m.fused = 0;
-        }
-        const uint64_t *cs = reinterpret_cast<const uint64_t *>(&c);
-        for (int q = 0; q < 8; ++q) fr->cost[q] = cs[q];
-        uint64_t mbuf[7] = {0, 0, 0, 0, 0, 0, 0};
-        __builtin_memcpy(mbuf, &m, sizeof(mmee_mapping));
-        for (int q = 0; q < 7; ++q) fr->map[q] = mbuf[q];
-    }
-    if (threadIdx.x == 0) { *a.ticket = 0; *a.work_counter = 0; }   // ready for the next launch on this stream
+    finish_grid<1>(a, wave_best, &is_last);
 }
 
 }  // namespace mmee

@@ -257,7 +257,7 @@ void launch_search_limited(bool exact_k, dim3 grid, const SearchArgs &a)
 
 // enqueue one pass (tables + search + readback of the final records) into slot `slot`
 int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_t *evaluated,
-                   const double *e_limit = nullptr, bool build_tables = true)
+                   const double *e_limit = nullptr, bool build_tables = true, bool bs_da_step = false)
 {
     if (slot >= S.slots) return MMEE_EINVAL;
     int rc = build_tables ? launch_tilings(p, S.dv_dev + slot) : MMEE_OK;
@@ -291,7 +291,11 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     a.dv = S.dv_dev + slot;
     HIP_TRY(hipEventRecord(S.events[2 * slot], S.stream));
     dim3 grid((uint32_t)nblocks);
-    if (e_limit) {
+    if (bs_da_step) {
+        if (!e_limit) return MMEE_EINVAL;
+        a.e_limit = *e_limit;
+        hipLaunchKernelGGL(k_front_step, grid, dim3(SEARCH_THREADS), 0, S.stream, a);
+    } else if (e_limit) {
         if (mask != 4) return MMEE_EINVAL;
         a.e_limit = *e_limit;
         launch_search_limited(p.exact_k, grid, a);
@@ -318,7 +322,7 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     HIP_TRY(hipEventRecord(S.events[2 * slot + 1], S.stream));
     HIP_TRY(hipMemcpyAsync(S.final_host + N_OBJ * slot, S.final_dev + N_OBJ * slot, sizeof(FinalRecord) * N_OBJ,
                            hipMemcpyDeviceToHost, S.stream));
-    *evaluated = nrows * p.T * 9ull;
+    *evaluated = nrows * p.T * (bs_da_step ? 1ull : 9ull);
     return MMEE_OK;
 }
 
@@ -548,10 +552,12 @@ int mmee_chain_search_multi(const mmee_chain *w, const mmee_hw *hw, const int *o
     return mmee_chain_search_many(ws, hs, objectives, n_obj, flags, out, nullptr);
 }
 
-// Walk along the front by ascending latency: each step is the latency-then-energy optimum among
-// the candidates whose energy is strictly below the previous point's (Sec. VII-C).
-int mmee_chain_pareto(const mmee_chain *w, const mmee_hw *hw, uint32_t flags, mmee_result *out, uint32_t capacity,
-                      uint32_t *n_points)
+// Walk along a front.  Energy-latency (Sec. VII-C): by ascending latency, each step the
+// latency-then-energy optimum among the candidates whose energy is strictly below the previous
+// point's.  Buffer size / DRAM access (Sec. VII-B): by ascending buffer size, each step the
+// (size, traffic)-smallest dataflow whose traffic is strictly below the previous point's.
+static int walk_front(const mmee_chain *w, const mmee_hw *hw, bool bs_da, uint32_t flags, mmee_result *out,
+               uint32_t capacity, uint32_t *n_points)
 {
     if (!w || !hw || !out || !n_points || !capacity) return MMEE_EINVAL;
     if (flags & ~(uint32_t)MMEE_SEARCH_EXHAUSTIVE) return MMEE_EINVAL;
@@ -569,7 +575,7 @@ int mmee_chain_pareto(const mmee_chain *w, const mmee_hw *hw, uint32_t flags, mm
     uint64_t evaluated = 0;
     for (uint32_t k = 0;; ++k) {
         uint64_t ev = 0;
-        rc = enqueue_search(p, 4, flags, 0, &ev, &limit, k == 0);
+        rc = enqueue_search(p, bs_da ? 1 : 4, flags, 0, &ev, &limit, k == 0, bs_da);
         if (rc) return rc;
         HIP_TRY(hipStreamSynchronize(S.stream));
         float ms = 0.f;
@@ -577,18 +583,30 @@ int mmee_chain_pareto(const mmee_chain *w, const mmee_hw *hw, uint32_t flags, mm
         ksec += ms * 1e-3;
         evaluated += ev;
         mmee_result r;
-        rc = unpack_result(p, 0, MMEE_OBJ_LATENCY_THEN_ENERGY, 0, 0.0, 0.0, &r);
-        if (rc == MMEE_ENOFEASIBLE) break;          // nothing cheaper is left: the front is complete
+        rc = unpack_result(p, 0, bs_da ? 0 : MMEE_OBJ_LATENCY_THEN_ENERGY, 0, 0.0, 0.0, &r);
+        if (rc == MMEE_ENOFEASIBLE) break;          // nothing below the bound is left: the front is complete
         if (k == capacity) return MMEE_EOVERFLOW;   // out holds the first `capacity` points
         out[k] = r;
         *n_points = k + 1;
-        limit = r.cost.energy_pj;
+        limit = bs_da ? p.mc.BH * (double)r.cost.da_words : r.cost.energy_pj;
     }
     const double seconds = now_seconds() - t_start;
     for (uint32_t k = 0; k < *n_points; ++k) {
         out[k].evaluated = evaluated; out[k].seconds = seconds; out[k].kernel_seconds = ksec;
     }
     return *n_points ? MMEE_OK : MMEE_ENOFEASIBLE;
+}
+
+int mmee_chain_pareto(const mmee_chain *w, const mmee_hw *hw, uint32_t flags, mmee_result *out, uint32_t capacity,
+                      uint32_t *n_points)
+{
+    return walk_front(w, hw, false, flags, out, capacity, n_points);
+}
+
+int mmee_chain_front_bs_da(const mmee_chain *w, const mmee_hw *hw, uint32_t flags, mmee_result *out,
+                           uint32_t capacity, uint32_t *n_points)
+{
+    return walk_front(w, hw, true, flags, out, capacity, n_points);
 }
 
 // ---- attention workloads: the chain I = L = N, K = J = d, batch = B*H --------------------------
@@ -599,6 +617,14 @@ int mmee_pareto(const mmee_workload *w, const mmee_hw *hw, uint32_t flags, mmee_
     mmee_chain c;
     int rc = chain_of(w, c);
     return rc ? rc : mmee_chain_pareto(&c, hw, flags, out, capacity, n_points);
+}
+
+int mmee_front_bs_da(const mmee_workload *w, const mmee_hw *hw, uint32_t flags, mmee_result *out,
+                     uint32_t capacity, uint32_t *n_points)
+{
+    mmee_chain c;
+    int rc = chain_of(w, c);
+    return rc ? rc : mmee_chain_front_bs_da(&c, hw, flags, out, capacity, n_points);
 }
 
 int mmee_space_size(const mmee_workload *w, const mmee_hw *hw, uint64_t *out)

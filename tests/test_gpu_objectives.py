@@ -116,3 +116,48 @@ def test_pareto_full_configs_pruned_equals_exhaustive(M, name):
                p.cost.latency_cycles == float.fromhex(edp["latency_cycles"]) for p in pruned)
     print(name, "front:", [(p.cost.latency_cycles, p.cost.energy_pj) for p in pruned],
           "kernel ms", full[0].kernel_seconds * 1e3, flush=True)
+
+
+@pytest.mark.parametrize("case", range(len(SMALL) + 1))
+def test_front_bs_da_small_spaces_against_oracle(M, case):
+    """DRAM access versus buffer size (Sec. VII-B) over every dataflow, against the oracle."""
+    w, h = (SMALL + [MULTI_POINT])[case]
+    ow, oh = O.workload(w), O.hw(h)
+    rc, idx, cost = O.front_bs_da(ow, oh)
+    assert rc == 0 and len(idx) >= 3
+    for flags in (M.SEARCH_EXHAUSTIVE, M.SEARCH_PRUNED):
+        code, front = M.mmee_front_bs_da(w, h, flags)
+        assert code == 0 and [p.best.idx for p in front] == idx, (case, flags)
+        for p, c in zip(front, cost):
+            for fld in INT_FIELDS:
+                assert getattr(p.cost, fld) == getattr(c, fld)
+            assert (p.cost.valid, p.cost.reason) == (c.valid, c.reason)
+            assert p.cost.energy_pj == c.energy_pj and p.cost.latency_cycles == c.latency_cycles
+    code, front = M.mmee_front_bs_da(w, h, M.SEARCH_PRUNED, capacity=2)
+    assert code == M.EOVERFLOW and [p.best.idx for p in front] == idx[:2]
+
+
+def test_front_bs_da_chain_and_full_configs(M):
+    # a free chain shape against the oracle's enumeration of its whole space
+    c = dict(batch=2, I=12, K=3, L=8, J=6, word_bytes=2, tiling_mode=1, c_softmax=0)
+    h = dict(pe_rows=2, pe_cols=2, n_arrays=1, rf_bytes=12, gb_bytes=260,
+             e_dram=60.0, e_gb=9.0, e_rf=2.0, e_mac=1.0, dram_bw=0.75, gb_bw=3.0)
+    rc, idx, cost = O.front_bs_da(O.workload(c), O.hw(h))
+    code, front = M.mmee_chain_front_bs_da(c, h)
+    assert rc == 0 and code == 0 and [p.best.idx for p in front] == idx
+    # full-size configurations: pruned == exhaustive, monotone, ends at the compulsory traffic
+    for name in ("bert", "long"):
+        cfg = CONFIGS[name]
+        w, hw_ = cfg["workload"], cfg["hw"]
+        cp, pruned = M.mmee_front_bs_da(w, hw_, M.SEARCH_PRUNED)
+        cx, full = M.mmee_front_bs_da(w, hw_, M.SEARCH_EXHAUSTIVE)
+        assert cp == cx == 0 and [p.best.idx for p in pruned] == [p.best.idx for p in full]
+        bs = [p.cost.bs_words for p in pruned]
+        da = [p.cost.da_words for p in pruned]
+        assert bs == sorted(set(bs)) and da == sorted(set(da), reverse=True)
+        assert da[-1] == 4 * w["N"] * w["d"]
+        ow, oh = O.workload(w), O.hw(hw_)
+        for p in pruned[:: max(1, len(pruned) // 8)]:
+            _, c_, _ = O.evaluate(ow, oh, p.best.idx)
+            assert (c_.bs_words, c_.da_words) == (p.cost.bs_words, p.cost.da_words)
+        print(name, "bs-da front:", len(pruned), "points, kernel ms", full[0].kernel_seconds * 1e3, flush=True)
