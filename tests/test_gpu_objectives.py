@@ -161,3 +161,26 @@ def test_front_bs_da_chain_and_full_configs(M):
             _, c_, _ = O.evaluate(ow, oh, p.best.idx)
             assert (c_.bs_words, c_.da_words) == (p.cost.bs_words, p.cost.da_words)
         print(name, "bs-da front:", len(pruned), "points, kernel ms", full[0].kernel_seconds * 1e3, flush=True)
+
+
+def test_reconfigurable_array_shape_sweep_edp(M):
+    """Sec. VII-I: EDP-driven choice among logical PE-array shapes with at most 32x32 PEs (stationary
+    modes are free in every search).  All shapes go through one launch stream; every per-shape
+    optimum and the best shape must be the oracle's."""
+    w, h = SMALL[0]
+    shapes = [(r, c) for r in (1, 2, 4, 8, 16, 32) for c in (1, 2, 4, 8, 16, 32) if 16 <= r * c <= 1024 and r <= 4 * c and c <= 4 * r]
+    points = [(w, dict(h, pe_rows=r, pe_cols=c), M.OBJ_EDP) for r, c in shapes]
+    results, codes = M.mmee_search_many(points, M.SEARCH_PRUNED)
+    best_gpu, best_cpu = None, None
+    for (r, c), (_, hw_, _), res, code in zip(shapes, points, results, codes):
+        rc, idx, cost, _, _ = O.search_all(O.workload(w), O.hw(hw_))
+        assert rc == 0 and code == 0 and res.best.idx == idx[O.OBJ_EDP], (r, c)
+        g = res.cost.energy_pj * res.cost.latency_cycles
+        o = cost[O.OBJ_EDP].energy_pj * cost[O.OBJ_EDP].latency_cycles
+        assert g == o
+        if best_gpu is None or g < best_gpu[0]:
+            best_gpu = (g, r, c)
+        if best_cpu is None or o < best_cpu[0]:
+            best_cpu = (o, r, c)
+    assert best_gpu == best_cpu
+    print("best shape", best_gpu, flush=True)
