@@ -27,10 +27,10 @@ sys.path.insert(0, ROOT)
 # lane-operation is one operation.)
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # fp64-width operations the model needs: per candidate (gb words, e_gb product, three energy
-# additions, latency max, compare+min+select for each of the two objectives) and per
+# additions, latency max, one running minimum for each of the two objectives) and per
 # (row, tiling) pair shared by nine candidates (4 additions + max + compare for the buffer size
 # and capacity, 2 additions for DRAM access, 2 products, 2 masks).
-OPS_PER_CANDIDATE = 12 + 12 / 9
+OPS_PER_CANDIDATE = 8 + 12 / 9
 HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/*.md), scaled by what the

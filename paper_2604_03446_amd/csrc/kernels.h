@@ -74,6 +74,34 @@ template <class T> using ConstPtr = const T __attribute__((address_space(4))) *;
 typedef ConstPtr<double> ConstF64;
 template <class T> __device__ __forceinline__ ConstPtr<T> as_constant(const T *p) { return (ConstPtr<T>)p; }
 
+// value-only wave reductions and wave-uniform reads (used by the lazy argmin)
+__device__ __forceinline__ double wave_min_f64(double x)
+{
+#define MMEE_STEP_(S)                                                                                   \
+    {                                                                                                   \
+        unsigned long long b = (unsigned long long)__double_as_longlong(x);                             \
+        uint32_t lo = lane_exchange<S>((uint32_t)b), hi = lane_exchange<S>((uint32_t)(b >> 32));        \
+        x = fmin(x, __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo)));            \
+    }
+    MMEE_STEP_(0) MMEE_STEP_(1) MMEE_STEP_(2) MMEE_STEP_(3) MMEE_STEP_(4) MMEE_STEP_(5)
+#undef MMEE_STEP_
+    return x;
+}
+
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x)
+{
+    x = min(x, lane_exchange<0>(x)); x = min(x, lane_exchange<1>(x)); x = min(x, lane_exchange<2>(x));
+    x = min(x, lane_exchange<3>(x)); x = min(x, lane_exchange<4>(x)); x = min(x, lane_exchange<5>(x));
+    return x;
+}
+
+__device__ __forceinline__ double uniform_f64(double x)
+{
+    unsigned long long b = (unsigned long long)__double_as_longlong(x);
+    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
 // ---------------------------------------------------------------------------
 // offline stage: the query side
 
@@ -688,10 +716,20 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
     __shared__ Key wave_best[N_OBJ][SEARCH_THREADS / 64];
     __shared__ uint32_t is_last;
 
+    // Scalar keys (energy, latency, EDP) use the lazy argmin: the loop only tracks minima, and the
+    // position of a minimum is recovered afterwards, for the rare item whose best value reaches the
+    // wave's running best.  The lexicographic key and the bounded walk keep positions in the loop.
+    constexpr bool LAZY = !(MASK & 4) && !LIMIT;
+
     const double inf = pos_inf();
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // wave_best[o][w]: best key of wave w over all items so far; only wave w touches its slot
     if (lane < N_OBJ) { wave_best[lane][wave].p = inf; wave_best[lane][wave].s = 0.0; wave_best[lane][wave].idx = ~0ull; }
+    // lazy path: the wave's running best per key, wave-uniform
+    double run_p[N_OBJ];
+    uint64_t run_idx[N_OBJ];
+#pragma unroll
+    for (int o = 0; o < N_OBJ; ++o) { run_p[o] = inf; run_idx[o] = ~0ull; }
 
     // work items are handed out through a global counter; the first one is the block's own number.
     // Thread 0 asks for the next item while the current one is being processed.
@@ -798,6 +836,12 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
                     en = out_of_range ? inf : en;
                     lat = out_of_range ? inf : lat;
                 }
+                if constexpr (LAZY) {
+                    if constexpr (MASK & 8) bestP[c9] = fmin(bestP[c9], en * lat);
+                    if constexpr (MASK & 1) bestE[c9] = fmin(bestE[c9], en);
+                    if constexpr (MASK & 2) bestL[c9] = fmin(bestL[c9], lat);
+                    return;
+                }
                 if constexpr (MASK & 8) {
                     double edp = en * lat;
                     bool lt = edp < bestP[c9];
@@ -832,10 +876,65 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
             for (int c = 0; c < 4; ++c) { gbB[c] = cs_next[5 + c]; latB[c] = cs_next[14 + c]; }
         }
 
-        // fold the nine per-combination minima of this lane (ascending combination = ascending
-        // index, so a strict < keeps the lowest index), reduce over the wave, keep the wave's best
         const uint32_t f = g >> 1;
         const uint64_t row_base = (uint64_t)(dfrow % ROWS_PER_GROUP) + 15000ull * r + 270000ull * f;
+        if constexpr (LAZY) {
+#pragma unroll
+            for (int o = 0; o < N_OBJ; ++o) {
+                if (!((MASK >> o) & 1)) continue;
+                const double *best = o == 0 ? bestE : (o == 1 ? bestL : bestP);
+                // this lane's minimum and the lowest combination reaching it (lowest index on ties)
+                double mine_v = inf;
+                uint32_t cstar = 0;
+#pragma unroll
+                for (int c9 = 0; c9 < 9; ++c9)
+                    if (best[c9] < mine_v) { mine_v = best[c9]; cstar = c9; }
+                const double wave_v = uniform_f64(wave_min_f64(mine_v));
+                if (!(wave_v <= run_p[o])) continue;                 // the usual case: nothing new here
+                // the index row (levels/order/r/combination/f) with the lowest number among those
+                // that reach the wave's minimum: its candidates precede every other row's
+                const uint32_t my_row = (uint32_t)row_base + 30000u * (cstar % 3) + 90000u * (cstar / 3);
+                const uint32_t first_row = __builtin_amdgcn_readfirstlane(
+                    wave_min_u32((mine_v == wave_v && mine_v < inf) ? my_row : 0xFFFFFFFFu));
+                if (first_row == 0xFFFFFFFFu) continue;              // nothing feasible in this item
+                const uint64_t lowest_possible = (uint64_t)t0 + (uint64_t)a.mc.T * first_row;
+                if (!(wave_v < run_p[o] || lowest_possible < run_idx[o])) continue;
+                // Recover the tiling: the lane that owns first_row lends its selectors, and every
+                // lane re-costs one tiling of the chunk for that row and combination, with the very
+                // operations of the loop above.
+                const unsigned long long owners = __ballot(my_row == first_row && mine_v == wave_v);
+                const uint32_t src = (uint32_t)__ffsll((long long)owners) - 1u;
+                const uint32_t c_u = __builtin_amdgcn_readlane(cstar, src);
+                const double *row_tab = tab + lane * NENT;
+                double w[NSEL];
+#pragma unroll
+                for (int k = 0; k < NSEL; ++k) w[k] = row_tab[__builtin_amdgcn_readlane(off[k], src)];
+                bool ok2 = fmax(w[0] + w[2] + w[1], w[3] + w[2] + w[4]) <= a.mc.cap_words;
+                double dram2 = w[5] + w[6] + w[7];
+                double e_dram2 = ok2 ? a.mc.e_dram * dram2 : inf;
+                double l_dram2;
+                if constexpr (FAST) l_dram2 = dram2 * a.mc.dram_k;
+                else l_dram2 = a.mc.dram_bw > 0.0 ? a.mc.c_lat * (((dram2 / a.mc.BH) * a.mc.word) / a.mc.dram_bw) : 0.0;
+                l_dram2 = ok2 ? l_dram2 : inf;
+                pin(e_dram2);
+                pin(l_dram2);
+                ConstF64 cl = cs_base + (uint64_t)lane * 2 * NCS;
+                double gb2 = dram2 + cl[c_u];
+                double en2 = e_dram2 + a.mc.e_gb * gb2;
+                en2 = en2 + cl[18];
+                en2 = en2 + cl[19];
+                double lat2 = fmax(l_dram2, cl[9 + c_u]);
+                double val2 = o == 0 ? en2 : (o == 1 ? lat2 : en2 * lat2);
+                const unsigned long long hits = __ballot(lane < nt && val2 == wave_v);
+                if (!hits) continue;                                 // cannot happen: the loop found it
+                const uint64_t idx = (uint64_t)t0 + ((uint32_t)__ffsll((long long)hits) - 1u) +
+                                     (uint64_t)a.mc.T * first_row;
+                if (wave_v < run_p[o] || idx < run_idx[o]) { run_p[o] = wave_v; run_idx[o] = idx; }
+            }
+            continue;
+        }
+        // fold the nine per-combination minima of this lane (ascending combination = ascending
+        // index, so a strict < keeps the lowest index), reduce over the wave, keep the wave's best
         Key mine[N_OBJ];
 #pragma unroll
         for (int o = 0; o < N_OBJ; ++o) { mine[o].p = inf; mine[o].s = 0.0; mine[o].idx = ~0ull; }
@@ -878,6 +977,15 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
         }
     }
 
+    if constexpr (LAZY) {
+        if (lane == 0) {
+#pragma unroll
+            for (int o = 0; o < N_OBJ; ++o) {
+                if (!((MASK >> o) & 1)) continue;
+                wave_best[o][wave].p = run_p[o]; wave_best[o][wave].s = 0.0; wave_best[o][wave].idx = run_idx[o];
+            }
+        }
+    }
     finish_grid<MASK>(a, wave_best, &is_last);
 }
 
