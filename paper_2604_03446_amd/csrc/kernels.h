@@ -618,6 +618,22 @@ constexpr int BLOCKS_PER_CU = MMEE_BLOCKS_PER_CU;   // what LDS (63 KB per block
 constexpr int TC = MMEE_TC;      // tilings per block
 constexpr int SEARCH_THREADS = MMEE_THREADS;
 
+// LDS access through explicit 32-bit addresses: one address register per selector serves two
+// table rows (base and base + NENT entries) in a single paired read.
+typedef const double __attribute__((address_space(3))) *LdsF64;
+__device__ __forceinline__ uint32_t lds_address(const double *p)
+{
+    return (uint32_t)(uintptr_t)(LdsF64)p;
+}
+__device__ __forceinline__ void read_pair(uint32_t base, uint32_t row_bytes, double &first, double &second)
+{
+    uint32_t addr = base + row_bytes;
+    asm("" : "+v"(addr));                         // one register, two constant offsets
+    LdsF64 p = (LdsF64)(uintptr_t)addr;
+    first = p[0];
+    second = p[NENT];
+}
+
 // keeps the optimiser from sinking a select below the operations that consume its result
 __device__ __forceinline__ void pin(double &x) { asm("" : "+v"(x)); }
 
@@ -712,7 +728,7 @@ constexpr int popcount4(int m) { return (m & 1) + ((m >> 1) & 1) + ((m >> 2) & 1
 template <int MASK, bool FAST, bool LIMIT = false>
 __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 && MASK != 4)) ? 2 : 4) void k_search(SearchArgs a)
 {
-    __shared__ double tab[(TC + 1) * NENT];      // one spare row: the loop reads one tiling ahead
+    __shared__ double tab[TC * NENT];
     __shared__ Key wave_best[N_OBJ][SEARCH_THREADS / 64];
     __shared__ uint32_t is_last;
 
@@ -754,10 +770,12 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
         const uint32_t t0 = chunk * TC;
         const uint32_t nt = min((uint32_t)TC, a.mc.T - t0);
 
-        // stage this chunk of the boundary-side tables: global entry-major -> LDS tiling-major
+        // stage this chunk of the boundary-side tables: global entry-major -> LDS tiling-major.
+        // A ragged chunk gets its last tiling once more in the next row: the loop takes tilings in
+        // pairs, and a repeated tiling changes no minimum.
         for (uint32_t i = threadIdx.x; i < NENT * TC; i += SEARCH_THREADS) {
             uint32_t ent = i / TC, tl = i % TC;
-            if (tl < nt) tab[tl * NENT + ent] = a.btab[(uint64_t)ent * a.mc.tpad + t0 + tl];
+            if (tl <= nt) tab[tl * NENT + ent] = a.btab[(uint64_t)ent * a.mc.tpad + t0 + min(tl, nt - 1)];
         }
         __syncthreads();
 
@@ -779,11 +797,14 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
         // next tiling are requested while the current one is costed.  The constants come in two
         // halves (combinations 0..4 / 5..8) so that each half is reloaded as soon as it is spent.
         ConstF64 cs_base = as_constant(a.ctab_s + ((uint64_t)t0 * 2 + r) * NCS);
-        double v[NSEL];
-#if MMEE_PIPE
+        // Two tilings per turn: their table values come from one LDS address per selector (the
+        // second row sits NENT entries further), requested a turn ahead.
+        double v[2][NSEL];
+        uint32_t sel_addr[NSEL];
 #pragma unroll
-        for (int k = 0; k < NSEL; ++k) v[k] = tab[off[k]];
-#endif
+        for (int k = 0; k < NSEL; ++k) sel_addr[k] = lds_address(tab + off[k]);
+#pragma unroll
+        for (int k = 0; k < NSEL; ++k) read_pair(sel_addr[k], 0, v[0][k], v[1][k]);
         double gbA[5], latA[5], gbB[4], latB[4], e_rf_part, e_mac_part;
 #pragma unroll
         for (int c = 0; c < 5; ++c) { gbA[c] = cs_base[c]; latA[c] = cs_base[9 + c]; }
@@ -793,87 +814,87 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
         ConstF64 cs_cur = cs_base;
         ConstF64 const cs_end = cs_base + (uint64_t)nt * 2 * NCS;
 
-        for (uint32_t tl = 0; tl < nt; ++tl) {
-#if !MMEE_PIPE
-            {
-                const double *row_tab = tab + tl * NENT;
+        for (uint32_t tl2 = 0; tl2 < nt; tl2 += 2) {
+            double dram_words[2], e_dram_part[2], l_dram[2];
 #pragma unroll
-                for (int k = 0; k < NSEL; ++k) v[k] = row_tab[off[k]];
+            for (int u = 0; u < 2; ++u) {
+                // Eq. (1), (2), (4) and the capacity mask
+                double bs1 = v[u][0] + v[u][2] + v[u][1];
+                double bs2 = v[u][3] + v[u][2] + v[u][4];
+                bool ok = fmax(bs1, bs2) <= cap;
+                dram_words[u] = v[u][5] + v[u][6] + v[u][7];   // B*H * Eq. (7)
+                e_dram_part[u] = ok ? a.mc.e_dram * dram_words[u] : inf;
+                if constexpr (FAST) l_dram[u] = dram_words[u] * a.mc.dram_k;
+                else l_dram[u] = a.mc.dram_bw > 0.0 ? a.mc.c_lat * (((dram_words[u] / a.mc.BH) * a.mc.word) / a.mc.dram_bw) : 0.0;
+                l_dram[u] = ok ? l_dram[u] : inf;
+                pin(e_dram_part[u]);
+                pin(l_dram[u]);
             }
-#endif
-            // Eq. (1), (2), (4) and the capacity mask
-            double bs1 = v[0] + v[2] + v[1];
-            double bs2 = v[3] + v[2] + v[4];
-            bool ok = fmax(bs1, bs2) <= cap;
-            double dram_words = v[5] + v[6] + v[7];           // B*H * Eq. (7)
-            double e_dram_part = ok ? a.mc.e_dram * dram_words : inf;
-            double l_dram;
-            if constexpr (FAST) l_dram = dram_words * a.mc.dram_k;
-            else l_dram = a.mc.dram_bw > 0.0 ? a.mc.c_lat * (((dram_words / a.mc.BH) * a.mc.word) / a.mc.dram_bw) : 0.0;
-            l_dram = ok ? l_dram : inf;
-            pin(e_dram_part);
-            pin(l_dram);
-#if MMEE_PIPE
             {
-                const double *next_tab = tab + (tl + 1) * NENT;
+                // rows tl2+2 and tl2+3, kept inside the staged chunk when the loop is about to end
+                const uint32_t row_bytes = min(tl2 + 2, (uint32_t)TC - 2) * (NENT * 8);
 #pragma unroll
-                for (int k = 0; k < NSEL; ++k) v[k] = next_tab[off[k]];
+                for (int k = 0; k < NSEL; ++k) read_pair(sel_addr[k], row_bytes, v[0][k], v[1][k]);
             }
-#endif
-            ConstF64 cs_next = cs_cur + 2 * NCS;              // stay inside the table on the last turn
-            cs_next = cs_next < cs_end ? cs_next : cs_cur;
-            cs_cur = cs_next;
-            const double e_rf_now = e_rf_part, e_mac_now = e_mac_part;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const uint32_t tl = tl2 + u;
+                ConstF64 cs_next = cs_cur + 2 * NCS;          // stay inside the table on the last turn
+                cs_next = cs_next < cs_end ? cs_next : cs_cur;
+                cs_cur = cs_next;
+                const double e_rf_now = e_rf_part, e_mac_now = e_mac_part;
+                const double dw = dram_words[u], edp_ = e_dram_part[u], ld = l_dram[u];
 
-            auto cost_one = [&](int c9, double gb_part, double lat_part) {
-                double gb_words = dram_words + gb_part;
-                double en = e_dram_part + a.mc.e_gb * gb_words;
-                en = en + e_rf_now;
-                en = en + e_mac_now;
-                double lat = fmax(l_dram, lat_part);
-                if constexpr (LIMIT) {
-                    bool out_of_range = !(en < a.e_limit);
-                    en = out_of_range ? inf : en;
-                    lat = out_of_range ? inf : lat;
-                }
-                if constexpr (LAZY) {
-                    if constexpr (MASK & 8) bestP[c9] = fmin(bestP[c9], en * lat);
-                    if constexpr (MASK & 1) bestE[c9] = fmin(bestE[c9], en);
-                    if constexpr (MASK & 2) bestL[c9] = fmin(bestL[c9], lat);
-                    return;
-                }
-                if constexpr (MASK & 8) {
-                    double edp = en * lat;
-                    bool lt = edp < bestP[c9];
-                    bestP[c9] = fmin(bestP[c9], edp);
-                    codeP[c9] = lt ? tl : codeP[c9];
-                }
-                if constexpr (MASK & 1) {
-                    bool lt = en < bestE[c9];
-                    bestE[c9] = fmin(bestE[c9], en);
-                    codeE[c9] = lt ? tl : codeE[c9];
-                }
-                if constexpr (MASK & 2) {
-                    bool lt = lat < bestL[c9];
-                    bestL[c9] = fmin(bestL[c9], lat);
-                    codeL[c9] = lt ? tl : codeL[c9];
-                }
-                if constexpr (MASK & 4) {
-                    bool lt = lat < bestLE_l[c9] || (lat == bestLE_l[c9] && en < bestLE_e[c9]);
-                    bestLE_l[c9] = lt ? lat : bestLE_l[c9];
-                    bestLE_e[c9] = lt ? en : bestLE_e[c9];
-                    codeLE[c9] = lt ? tl : codeLE[c9];
-                }
-            };
+                auto cost_one = [&](int c9, double gb_part, double lat_part) {
+                    double gb_words = dw + gb_part;
+                    double en = edp_ + a.mc.e_gb * gb_words;
+                    en = en + e_rf_now;
+                    en = en + e_mac_now;
+                    double lat = fmax(ld, lat_part);
+                    if constexpr (LIMIT) {
+                        bool out_of_range = !(en < a.e_limit);
+                        en = out_of_range ? inf : en;
+                        lat = out_of_range ? inf : lat;
+                    }
+                    if constexpr (LAZY) {
+                        if constexpr (MASK & 8) bestP[c9] = fmin(bestP[c9], en * lat);
+                        if constexpr (MASK & 1) bestE[c9] = fmin(bestE[c9], en);
+                        if constexpr (MASK & 2) bestL[c9] = fmin(bestL[c9], lat);
+                        return;
+                    }
+                    if constexpr (MASK & 8) {
+                        double edp = en * lat;
+                        bool lt = edp < bestP[c9];
+                        bestP[c9] = fmin(bestP[c9], edp);
+                        codeP[c9] = lt ? tl : codeP[c9];
+                    }
+                    if constexpr (MASK & 1) {
+                        bool lt = en < bestE[c9];
+                        bestE[c9] = fmin(bestE[c9], en);
+                        codeE[c9] = lt ? tl : codeE[c9];
+                    }
+                    if constexpr (MASK & 2) {
+                        bool lt = lat < bestL[c9];
+                        bestL[c9] = fmin(bestL[c9], lat);
+                        codeL[c9] = lt ? tl : codeL[c9];
+                    }
+                    if constexpr (MASK & 4) {
+                        bool lt = lat < bestLE_l[c9] || (lat == bestLE_l[c9] && en < bestLE_e[c9]);
+                        bestLE_l[c9] = lt ? lat : bestLE_l[c9];
+                        bestLE_e[c9] = lt ? en : bestLE_e[c9];
+                        codeLE[c9] = lt ? tl : codeLE[c9];
+                    }
+                };
 #pragma unroll
-            for (int c = 0; c < 5; ++c) cost_one(c, gbA[c], latA[c]);
+                for (int c = 0; c < 5; ++c) cost_one(c, gbA[c], latA[c]);
 #pragma unroll
-            for (int c = 0; c < 5; ++c) { gbA[c] = cs_next[c]; latA[c] = cs_next[9 + c]; }
-            e_rf_part = cs_next[18]; e_mac_part = cs_next[19];
+                for (int c = 0; c < 5; ++c) { gbA[c] = cs_next[c]; latA[c] = cs_next[9 + c]; }
+                e_rf_part = cs_next[18]; e_mac_part = cs_next[19];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) cost_one(5 + c, gbB[c], latB[c]);
+                for (int c = 0; c < 4; ++c) cost_one(5 + c, gbB[c], latB[c]);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) { gbB[c] = cs_next[5 + c]; latB[c] = cs_next[14 + c]; }
+                for (int c = 0; c < 4; ++c) { gbB[c] = cs_next[5 + c]; latB[c] = cs_next[14 + c]; }
+            }
         }
 
         const uint32_t f = g >> 1;
