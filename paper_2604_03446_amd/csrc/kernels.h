@@ -311,7 +311,8 @@ __device__ __forceinline__ void tile_cost(uint32_t m, uint32_t r, uint32_t n, in
 }
 
 // One thread per tiling: decode the four tiling digits, derive the boundary vector and
-// store every subset product a row may select (entry-major, coalesced in the tiling).
+// store every subset product a row may select (entry-major, coalesced in the tiling).  The grid
+// covers the padded width mc.tpad.
 __global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__ btab, double *__restrict__ ctab_s,
                                 uint64_t *__restrict__ ctab_e, DivTable *__restrict__ dv_copy)
 {
@@ -322,9 +323,12 @@ __global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__
         uint32_t *dst = reinterpret_cast<uint32_t *>(dv_copy);
         for (uint32_t a = threadIdx.x; a < sizeof(DivTable) / 4; a += blockDim.x) dst[a] = src[a];
     }
-    if (t >= mc.T) return;
+    if (t >= mc.tpad) return;
+    // the columns between the last tiling and the padded width repeat the last tiling (the search
+    // stages tilings in pairs)
+    const bool padding = t >= mc.T;
     uint64_t G[4], D[4];
-    uint32_t x = t;
+    uint32_t x = padding ? mc.T - 1 : t;
     for (int q = 0; q < 4; ++q) {
         uint32_t digit = x % dv.ndiv[q];
         x /= dv.ndiv[q];
@@ -375,6 +379,8 @@ __global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__
         btab[(ENT_DA_C + 4) * tp + t] = 0.0;
         btab[(ENT_DA_C + ENT_RAW_DA + 4) * tp + t] = 0.0;
     }
+
+    if (padding) return;
 
     // stationary-mode dependent part: buffer<->RF words and cycles per tile stage
     uint64_t br1[3], cy1[3], br2[3], cy2[3];
@@ -518,9 +524,6 @@ __global__ void k_decode(DivTable dv, uint32_t T, const uint64_t *__restrict__ i
 // streaming (nothing reads the records back on the device).
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
-#ifndef MMEE_EVAL_NT
-#define MMEE_EVAL_NT 1
-#endif
 
 // Work unit = 64 consecutive tilings of one index row, one wave each (4 units per block).  Unit
 // boundaries are shifted per row so that every unit starts at a multiple of EVAL_ALIGN records
@@ -563,11 +566,7 @@ __global__ __launch_bounds__(256) void k_eval_batch(EvalArgs a, uint64_t first_i
         uint32_t rec = 16 * k + (lane >> 2);
         if ((mask >> rec) & 1ull) {
             uint64_t o = wave_first + rec - first_idx;
-#if MMEE_EVAL_NT
             __builtin_nontemporal_store(stage[wave][rec * 4 + (lane & 3)], &out[o * 4 + (lane & 3)]);
-#else
-            out[o * 4 + (lane & 3)] = stage[wave][rec * 4 + (lane & 3)];
-#endif
         }
     }
 }
@@ -577,12 +576,18 @@ __global__ __launch_bounds__(256) void k_eval_batch(EvalArgs a, uint64_t first_i
 
 struct SearchArgs {
     const uint4 *enc;            // encoded rows
-    const uint32_t *rows;        // compacted row ids, groups back to back
-    uint32_t group_off[4];       // start of each group's list inside rows[]
-    uint32_t group_cnt[4];
-    uint32_t rb_start[5];        // first row-block of each group, [4] = total
-    uint32_t n_chunks;           // tiling chunks
-    uint32_t n_items;            // row-blocks x tiling chunks
+    const uint32_t *rows;        // compacted row ids, one list per (r, f) group
+    // Rows are handed out per recomputation class r: the lists of (r, f=0) and (r, f=1) follow each
+    // other in one slot numbering, so that a row block may hold rows of both.
+    uint32_t cls_off[2][2];      // [r][f] start of the group's list inside rows[]
+    uint32_t cls_cnt[2][2];      // [r][f] rows in it
+    uint32_t rb_split;           // row blocks of class r = 0; the rest belong to r = 1
+    // Tilings [0, n_cc * TC) are cut into chunks of TC, the rest into n_fc chunks of TC_FINE.  Items
+    // [0, n_coarse_items) are the (row block, coarse chunk) pairs, the fine ones follow: the short
+    // items are handed out last and even out the moment at which the persistent blocks run dry.
+    uint32_t n_cc, n_fc;
+    uint32_t n_coarse_items;
+    uint32_t n_items;
     const double *btab;
     const double *ctab_s;
     ModelConst mc;
@@ -595,28 +600,11 @@ struct SearchArgs {
     DivTable const *dv;          // device copy, for the final record's mapping
 };
 
-#ifndef MMEE_TC
-#define MMEE_TC 64
-#endif
-#ifndef MMEE_THREADS
-#define MMEE_THREADS 512
-#endif
-#ifndef MMEE_PIPE
-#define MMEE_PIPE 1
-#endif
-#define MMEE_STR_(x) #x
-#define MMEE_PRAGMA_(x) _Pragma(MMEE_STR_(x))
-#ifdef MMEE_UNROLL
-#define MMEE_LOOP_UNROLL MMEE_PRAGMA_(unroll MMEE_UNROLL)
-#else
-#define MMEE_LOOP_UNROLL
-#endif
-#ifndef MMEE_BLOCKS_PER_CU
-#define MMEE_BLOCKS_PER_CU 2
-#endif
-constexpr int BLOCKS_PER_CU = MMEE_BLOCKS_PER_CU;   // what LDS (63 KB per block) lets a CU hold
-constexpr int TC = MMEE_TC;      // tilings per block
-constexpr int SEARCH_THREADS = MMEE_THREADS;
+constexpr int BLOCKS_PER_CU = 2;       // what LDS (63 KB per block) lets a CU hold
+constexpr int TC = 64;                 // tilings per coarse item
+constexpr int TC_FINE = 16;            // tilings per fine item
+constexpr int SEARCH_THREADS = 512;
+
 
 // LDS access through explicit 32-bit addresses: one address register per selector serves two
 // table rows (base and base + NENT entries) in a single paired read.
@@ -632,6 +620,66 @@ __device__ __forceinline__ void read_pair(uint32_t base, uint32_t row_bytes, dou
     LdsF64 p = (LdsF64)(uintptr_t)addr;
     first = p[0];
     second = p[NENT];
+}
+
+// What a work item covers: the recomputation class r, the tilings [t0, t0 + nt) and, per thread,
+// one dataflow row (live = false for the padding lanes of a class's last row block).
+struct ItemView {
+    uint32_t r, t0, nt;
+    uint32_t dfrow;
+    bool live, fine;
+};
+
+__device__ __forceinline__ ItemView locate_item(const SearchArgs &a, uint32_t item)
+{
+    ItemView v;
+    uint32_t rb;
+    v.fine = item >= a.n_coarse_items;
+    if (!v.fine) {
+        rb = item / a.n_cc;
+        v.t0 = (item % a.n_cc) * TC;
+        v.nt = TC;
+    } else {
+        const uint32_t j = item - a.n_coarse_items;
+        rb = j / a.n_fc;
+        v.t0 = a.n_cc * TC + (j % a.n_fc) * TC_FINE;
+        v.nt = min((uint32_t)TC_FINE, a.mc.T - v.t0);
+    }
+    v.r = rb >= a.rb_split;
+    const uint32_t slot = (rb - (v.r ? a.rb_split : 0u)) * SEARCH_THREADS + threadIdx.x;
+    const uint32_t n0 = a.cls_cnt[v.r][0], n1 = a.cls_cnt[v.r][1];
+    v.live = slot < n0 + n1;
+    const uint32_t where = !v.live ? a.cls_off[v.r][n0 ? 0 : 1]
+                                   : (slot < n0 ? a.cls_off[v.r][0] + slot : a.cls_off[v.r][1] + (slot - n0));
+    v.dfrow = a.rows[where];
+    return v;
+}
+
+// the index row (Sec. VI-A numbering: levels, order, r, stationary modes, f) of a dataflow row's
+// combination 0; dataflow rows are numbered levels/order + 15000 * (r + 2 f)
+__device__ __forceinline__ uint32_t index_row_base(uint32_t dfrow)
+{
+    const uint32_t g = dfrow / ROWS_PER_GROUP;
+    return dfrow % ROWS_PER_GROUP + 15000u * (g & 1) + 270000u * (g >> 1);
+}
+
+// Stage the tilings [t0, t0 + nt) of the boundary-side tables: global entry-major -> LDS
+// tiling-major, two tilings per thread and turn (one 16-byte load, one paired LDS write).  PAIRS =
+// tiling pairs per item.  When nt is odd the pair that starts at nt - 1 brings one column more:
+// beyond the last tiling the global table repeats it (k_build_tilings), and a repeated tiling
+// changes no minimum, so the loops may take tilings in pairs.
+template <int PAIRS>
+__device__ __forceinline__ void stage_tables(const SearchArgs &a, double *tab, uint32_t t0, uint32_t nt)
+{
+    typedef double v2f64 __attribute__((ext_vector_type(2)));
+    for (uint32_t i = threadIdx.x; i < NENT * PAIRS; i += SEARCH_THREADS) {
+        const uint32_t ent = i / PAIRS, tl = (i % PAIRS) * 2;
+        if (tl < nt) {
+            const v2f64 two = *reinterpret_cast<const v2f64 *>(a.btab + (uint64_t)ent * a.mc.tpad + t0 + tl);
+            tab[tl * NENT + ent] = two.x;
+            tab[(tl + 1) * NENT + ent] = two.y;
+        }
+    }
 }
 
 // keeps the optimiser from sinking a select below the operations that consume its result
@@ -758,25 +806,13 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
         if (item >= a.n_items) break;
         if (threadIdx.x == 0)
             upcoming = gridDim.x + __hip_atomic_fetch_add(a.work_counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const uint32_t chunk = item % a.n_chunks;
-        const uint32_t rb = item / a.n_chunks;
-        uint32_t g = 0;
-        while (g < 3 && rb >= a.rb_start[g + 1]) ++g;
-        const uint32_t slot = (rb - a.rb_start[g]) * SEARCH_THREADS + threadIdx.x;
-        const bool live = slot < a.group_cnt[g];
-        const uint32_t dfrow = a.rows[a.group_off[g] + (live ? slot : 0)];
+        const ItemView it = locate_item(a, item);
+        const bool live = it.live;
+        const uint32_t dfrow = it.dfrow;
         const uint4 e = a.enc[dfrow];
-        const uint32_t r = g & 1;
-        const uint32_t t0 = chunk * TC;
-        const uint32_t nt = min((uint32_t)TC, a.mc.T - t0);
-
-        // stage this chunk of the boundary-side tables: global entry-major -> LDS tiling-major.
-        // A ragged chunk gets its last tiling once more in the next row: the loop takes tilings in
-        // pairs, and a repeated tiling changes no minimum.
-        for (uint32_t i = threadIdx.x; i < NENT * TC; i += SEARCH_THREADS) {
-            uint32_t ent = i / TC, tl = i % TC;
-            if (tl <= nt) tab[tl * NENT + ent] = a.btab[(uint64_t)ent * a.mc.tpad + t0 + min(tl, nt - 1)];
-        }
+        const uint32_t r = it.r, t0 = it.t0, nt = it.nt;
+        if (it.fine) stage_tables<TC_FINE / 2>(a, tab, t0, nt);
+        else stage_tables<TC / 2>(a, tab, t0, nt);
         __syncthreads();
 
         uint32_t off[NSEL];
@@ -897,21 +933,21 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
             }
         }
 
-        const uint32_t f = g >> 1;
-        const uint64_t row_base = (uint64_t)(dfrow % ROWS_PER_GROUP) + 15000ull * r + 270000ull * f;
+        const uint64_t row_base = index_row_base(dfrow);
         if constexpr (LAZY) {
 #pragma unroll
             for (int o = 0; o < N_OBJ; ++o) {
                 if (!((MASK >> o) & 1)) continue;
                 const double *best = o == 0 ? bestE : (o == 1 ? bestL : bestP);
-                // this lane's minimum and the lowest combination reaching it (lowest index on ties)
-                double mine_v = inf;
-                uint32_t cstar = 0;
+                double mine_v = best[0];
 #pragma unroll
-                for (int c9 = 0; c9 < 9; ++c9)
-                    if (best[c9] < mine_v) { mine_v = best[c9]; cstar = c9; }
+                for (int c9 = 1; c9 < 9; ++c9) mine_v = fmin(mine_v, best[c9]);
                 const double wave_v = uniform_f64(wave_min_f64(mine_v));
                 if (!(wave_v <= run_p[o])) continue;                 // the usual case: nothing new here
+                // the lowest combination reaching this lane's minimum (lowest index on ties)
+                uint32_t cstar = 8;
+#pragma unroll
+                for (int c9 = 7; c9 >= 0; --c9) cstar = best[c9] == mine_v ? (uint32_t)c9 : cstar;
                 // the index row (levels/order/r/combination/f) with the lowest number among those
                 // that reach the wave's minimum: its candidates precede every other row's
                 const uint32_t my_row = (uint32_t)row_base + 30000u * (cstar % 3) + 90000u * (cstar / 3);
@@ -926,7 +962,8 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
                 const unsigned long long owners = __ballot(my_row == first_row && mine_v == wave_v);
                 const uint32_t src = (uint32_t)__ffsll((long long)owners) - 1u;
                 const uint32_t c_u = __builtin_amdgcn_readlane(cstar, src);
-                const double *row_tab = tab + lane * NENT;
+                const uint32_t tl_mine = min(lane, nt - 1);          // lanes beyond the chunk repeat its last tiling
+                const double *row_tab = tab + tl_mine * NENT;
                 double w[NSEL];
 #pragma unroll
                 for (int k = 0; k < NSEL; ++k) w[k] = row_tab[__builtin_amdgcn_readlane(off[k], src)];
@@ -939,7 +976,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
                 l_dram2 = ok2 ? l_dram2 : inf;
                 pin(e_dram2);
                 pin(l_dram2);
-                ConstF64 cl = cs_base + (uint64_t)lane * 2 * NCS;
+                ConstF64 cl = cs_base + (uint64_t)tl_mine * 2 * NCS;
                 double gb2 = dram2 + cl[c_u];
                 double en2 = e_dram2 + a.mc.e_gb * gb2;
                 en2 = en2 + cl[18];
@@ -1017,7 +1054,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
 // tables' unit, B*H words.  Same items, staging and finish as k_search; result in slot 0.
 __global__ __launch_bounds__(SEARCH_THREADS, 4) void k_front_step(SearchArgs a)
 {
-    __shared__ double tab[(TC + 1) * NENT];
+    __shared__ double tab[TC * NENT];
     __shared__ Key wave_best[N_OBJ][SEARCH_THREADS / 64];
     __shared__ uint32_t is_last;
     __shared__ uint32_t s_item;
@@ -1034,20 +1071,13 @@ __global__ __launch_bounds__(SEARCH_THREADS, 4) void k_front_step(SearchArgs a)
         if (item >= a.n_items) break;
         if (threadIdx.x == 0)
             upcoming = gridDim.x + __hip_atomic_fetch_add(a.work_counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const uint32_t chunk = item % a.n_chunks;
-        const uint32_t rb = item / a.n_chunks;
-        uint32_t g = 0;
-        while (g < 3 && rb >= a.rb_start[g + 1]) ++g;
-        const uint32_t slot = (rb - a.rb_start[g]) * SEARCH_THREADS + threadIdx.x;
-        const bool live = slot < a.group_cnt[g];
-        const uint32_t dfrow = a.rows[a.group_off[g] + (live ? slot : 0)];
+        const ItemView it = locate_item(a, item);
+        const bool live = it.live;
+        const uint32_t dfrow = it.dfrow;
         const uint4 e = a.enc[dfrow];
-        const uint32_t t0 = chunk * TC;
-        const uint32_t nt = min((uint32_t)TC, a.mc.T - t0);
-        for (uint32_t i = threadIdx.x; i < NENT * TC; i += SEARCH_THREADS) {
-            uint32_t ent = i / TC, tl = i % TC;
-            if (tl < nt) tab[tl * NENT + ent] = a.btab[(uint64_t)ent * a.mc.tpad + t0 + tl];
-        }
+        const uint32_t t0 = it.t0, nt = it.nt;
+        if (it.fine) stage_tables<TC_FINE / 2>(a, tab, t0, nt);
+        else stage_tables<TC / 2>(a, tab, t0, nt);
         __syncthreads();
         uint32_t off[NSEL];
 #pragma unroll
@@ -1069,7 +1099,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 4) void k_front_step(SearchArgs a)
         }
         Key mine;
         mine.p = best_bs; mine.s = best_da;
-        const uint64_t row_base = (uint64_t)(dfrow % ROWS_PER_GROUP) + 15000ull * (g & 1) + 270000ull * (g >> 1);
+        const uint64_t row_base = index_row_base(dfrow);
         mine.idx = (uint64_t)(t0 + code) + (uint64_t)a.mc.T * row_base;
         if (!(mine.p < inf)) { mine.s = 0.0; mine.idx = ~0ull; }
         Key k = wave_min(mine);

@@ -235,7 +235,7 @@ int launch_tilings(const Plan &p, DivTable *dv_copy = nullptr)
 {
     int rc = ensure_tilings(p.mc.tpad);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_build_tilings, dim3((p.mc.T + 63) / 64), dim3(64), 0, S.stream, p.dv, p.mc, S.btab,
+    hipLaunchKernelGGL(k_build_tilings, dim3(p.mc.tpad / 64), dim3(64), 0, S.stream, p.dv, p.mc, S.btab,
                        S.ctab_s, S.ctab_e, dv_copy);
     HIP_TRY(hipGetLastError());
     return MMEE_OK;
@@ -266,21 +266,35 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     SearchArgs a;
     std::memset(&a, 0, sizeof(a));
     a.enc = S.enc; a.rows = S.rows[which];
+    // rows: one slot numbering per recomputation class r, over the lists of (r, f=0) and (r, f=1)
     uint32_t rb = 0;
     uint64_t nrows = 0;
-    for (uint32_t g = 0; g < 4; ++g) {
-        a.group_off[g] = g * ROWS_PER_GROUP;
-        a.group_cnt[g] = S.counts[which][g];
-        a.rb_start[g] = rb;
-        rb += (S.counts[which][g] + SEARCH_THREADS - 1) / SEARCH_THREADS;
-        nrows += S.counts[which][g];
+    for (uint32_t r = 0; r < 2; ++r) {
+        uint32_t in_class = 0;
+        for (uint32_t f = 0; f < 2; ++f) {
+            const uint32_t g = r + 2 * f;
+            a.cls_off[r][f] = g * ROWS_PER_GROUP;
+            a.cls_cnt[r][f] = S.counts[which][g];
+            in_class += S.counts[which][g];
+        }
+        if (r == 0) a.rb_split = (in_class + SEARCH_THREADS - 1) / SEARCH_THREADS;
+        rb += (in_class + SEARCH_THREADS - 1) / SEARCH_THREADS;
+        nrows += in_class;
     }
-    a.rb_start[4] = rb;
-    a.n_chunks = (uint32_t)((p.T + TC - 1) / TC);
+    if (rb == 0) return MMEE_EINVAL;
+    // tilings: chunks of TC, then chunks of TC_FINE worth about four fine items per resident block
+    // (a coarse item's time), at least the ragged end
+    {
+        const uint64_t fine_chunks_wanted = (4ull * S.resident_blocks + rb - 1) / rb;
+        const uint64_t fine_tilings = std::min<uint64_t>(p.T, fine_chunks_wanted * TC_FINE);
+        a.n_cc = (uint32_t)((p.T - fine_tilings) / TC);
+        a.n_fc = (uint32_t)((p.T - (uint64_t)a.n_cc * TC + TC_FINE - 1) / TC_FINE);
+    }
     a.btab = S.btab; a.ctab_s = S.ctab_s; a.ctab_e = S.ctab_e;
     a.mc = p.mc;
-    const uint64_t n_items = (uint64_t)rb * a.n_chunks;
+    const uint64_t n_items = (uint64_t)rb * ((uint64_t)a.n_cc + a.n_fc);
     if (n_items == 0 || n_items > 0x7fffffffull) return MMEE_EINVAL;
+    a.n_coarse_items = rb * a.n_cc;
     a.n_items = (uint32_t)n_items;
     // persistent blocks: as many as the chip holds at once (LDS allows two per CU)
     const uint64_t nblocks = std::min<uint64_t>(n_items, (uint64_t)S.resident_blocks);
