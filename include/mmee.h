@@ -122,7 +122,13 @@ enum {
 
 enum {
     MMEE_SEARCH_PRUNED = 0,             /* offline symbolic pruning on (the paper's method) */
-    MMEE_SEARCH_EXHAUSTIVE = 1          /* cost every candidate that denotes a dataflow     */
+    MMEE_SEARCH_EXHAUSTIVE = 1,         /* cost every candidate that denotes a dataflow     */
+    /* When the four energies per access are whole numbers and the largest possible total stays
+     * below 2^53, every term of the energy is an exact integer and the search adds a (row, tiling)
+     * part and a (tiling, stationary modes) part per candidate; the result has the same bits as
+     * the sum taken term by term in the order of Sec. V-D.  This flag (may be or-ed with the
+     * others) keeps the term-by-term order in every case. */
+    MMEE_SEARCH_ORDERED_SUM = 2
 };
 
 enum {
@@ -137,6 +143,12 @@ enum {
 /* Number of candidates of (workload, hw): #tilings (integer factorisations, Sec. VI-A)
  * times 540000.  Pure host arithmetic. */
 int mmee_space_size(const mmee_workload *w, const mmee_hw *hw, uint64_t *out);
+
+/* *out = 1 when a search of (workload, hw) with these flags regroups the energy sum (see
+ * MMEE_SEARCH_ORDERED_SUM): whole-number energies per access, total energy of any candidate
+ * (Sec. V-D) below 2^53, and a power-of-two DRAM bandwidth and array count; else 0.  Pure host
+ * arithmetic. */
+int mmee_energy_regrouped(const mmee_workload *w, const mmee_hw *hw, uint32_t flags, int *out);
 
 /* On-device mixed-radix decode of n candidate indices (host arrays in and out). */
 int mmee_decode(const mmee_workload *w, const mmee_hw *hw, const uint64_t *idx, uint64_t n,
@@ -185,6 +197,7 @@ int mmee_front_bs_da(const mmee_workload *w, const mmee_hw *hw, uint32_t flags, 
 /* The same calls for a free chain shape (Sec. VII-H).  Semantics, layouts and error codes are
  * those of the workload calls above. */
 int mmee_chain_space_size(const mmee_chain *c, const mmee_hw *hw, uint64_t *out);
+int mmee_chain_energy_regrouped(const mmee_chain *c, const mmee_hw *hw, uint32_t flags, int *out);
 int mmee_chain_decode(const mmee_chain *c, const mmee_hw *hw, const uint64_t *idx, uint64_t n,
                       mmee_mapping *out);
 int mmee_chain_eval_batch(const mmee_chain *c, const mmee_hw *hw, uint64_t first_idx, uint64_t n,

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("MMEE_LIB") or os.path.join(_HERE, "libmmee.so")
 
 OBJ_ENERGY, OBJ_LATENCY, OBJ_LATENCY_THEN_ENERGY, OBJ_EDP = 0, 1, 2, 3
-SEARCH_PRUNED, SEARCH_EXHAUSTIVE = 0, 1
+SEARCH_PRUNED, SEARCH_EXHAUSTIVE, SEARCH_ORDERED_SUM = 0, 1, 2
 OK, EINVAL, ERANGE, ENOFEASIBLE, EDEVICE, EOVERFLOW = 0, -1, -2, -3, -4, -5
 
 
@@ -91,6 +91,8 @@ def _load() -> C.CDLL:
     L.mmee_search_many.argtypes = [P(Workload), P(Hw), P(C.c_int), C.c_uint32, C.c_uint32, P(Result),
                                    P(C.c_int)]
     L.mmee_chain_space_size.argtypes = [P(Chain), P(Hw), P(C.c_uint64)]
+    L.mmee_energy_regrouped.argtypes = [P(Workload), P(Hw), C.c_uint32, P(C.c_int)]
+    L.mmee_chain_energy_regrouped.argtypes = [P(Chain), P(Hw), C.c_uint32, P(C.c_int)]
     L.mmee_chain_decode.argtypes = [P(Chain), P(Hw), P(C.c_uint64), C.c_uint64, P(Mapping)]
     L.mmee_chain_eval_batch.argtypes = [P(Chain), P(Hw), C.c_uint64, C.c_uint64, C.c_void_p]
     L.mmee_chain_search_multi.argtypes = [P(Chain), P(Hw), P(C.c_int), C.c_uint32, C.c_uint32, P(Result)]
@@ -153,6 +155,20 @@ def mmee_space_size(w, h) -> int:
     out = C.c_uint64()
     _check(_lib.mmee_space_size(C.byref(workload(w)), C.byref(hw(h)), C.byref(out)), "mmee_space_size")
     return out.value
+
+
+def mmee_energy_regrouped(w, h, flags: int = SEARCH_PRUNED) -> bool:
+    out = C.c_int()
+    _check(_lib.mmee_energy_regrouped(C.byref(workload(w)), C.byref(hw(h)), flags, C.byref(out)),
+           "mmee_energy_regrouped")
+    return bool(out.value)
+
+
+def mmee_chain_energy_regrouped(c, h, flags: int = SEARCH_PRUNED) -> bool:
+    out = C.c_int()
+    _check(_lib.mmee_chain_energy_regrouped(C.byref(chain(c)), C.byref(hw(h)), flags, C.byref(out)),
+           "mmee_chain_energy_regrouped")
+    return bool(out.value)
 
 
 def mmee_decode(w, h, indices):

@@ -395,23 +395,25 @@ __global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__
         uint64_t mac = rho * I * K * L + I * L * J;
         uint64_t sm = rho * I * L;
         double *cs = ctab_s + ((uint64_t)t * 2 + r) * NCS;
+        const double e_rf_part = mc.e_rf * (double)(BH * 3 * mac);
+        const double e_mac_part = mc.e_mac * (double)(BH * (mac + (uint64_t)mc.c_softmax * sm));
+        cs[18] = e_rf_part;
+        cs[19] = e_mac_part;
         for (uint32_t c9 = 0; c9 < 9; ++c9) {
             uint32_t s1 = c9 % 3, s2 = c9 / 3;
             uint64_t br = st1 * br1[s1] + st2 * br2[s2];
             uint64_t cyc = st1 * cy1[s1] + st2 * cy2[s2];
             double t_gb = mc.gb_bw > 0.0 ? (double)(br * (uint64_t)mc.word) / mc.gb_bw : 0.0;
-            cs[c9] = (double)(BH * br);
+            cs[c9] = mc.regroup ? (mc.e_gb * (double)(BH * br) + e_rf_part) + e_mac_part : (double)(BH * br);
             cs[9 + c9] = mc.c_lat * fmax((double)cyc, t_gb);
             ctab_e[((uint64_t)r * NCE + c9) * tp + t] = br;
             ctab_e[((uint64_t)r * NCE + 9 + c9) * tp + t] = cyc;
             ctab_e[((uint64_t)r * NCE + 20 + c9) * tp + t] = (uint64_t)__double_as_longlong(cs[9 + c9]);
         }
-        cs[18] = mc.e_rf * (double)(BH * 3 * mac);
-        cs[19] = mc.e_mac * (double)(BH * (mac + (uint64_t)mc.c_softmax * sm));
         ctab_e[((uint64_t)r * NCE + 18) * tp + t] = mac;
         ctab_e[((uint64_t)r * NCE + 19) * tp + t] = sm;
-        ctab_e[((uint64_t)r * NCE + 29) * tp + t] = (uint64_t)__double_as_longlong(cs[18]);
-        ctab_e[((uint64_t)r * NCE + 30) * tp + t] = (uint64_t)__double_as_longlong(cs[19]);
+        ctab_e[((uint64_t)r * NCE + 29) * tp + t] = (uint64_t)__double_as_longlong(e_rf_part);
+        ctab_e[((uint64_t)r * NCE + 30) * tp + t] = (uint64_t)__double_as_longlong(e_mac_part);
     }
 }
 
@@ -602,7 +604,7 @@ struct SearchArgs {
 
 constexpr int BLOCKS_PER_CU = 2;       // what LDS (63 KB per block) lets a CU hold
 constexpr int TC = 64;                 // tilings per coarse item
-constexpr int TC_FINE = 16;            // tilings per fine item
+constexpr int TC_FINE = 32;            // tilings per fine item
 constexpr int SEARCH_THREADS = 512;
 
 
@@ -768,12 +770,15 @@ __device__ __forceinline__ void finish_grid(const SearchArgs &a, Key (*wave_best
 // FAST: DRAM bandwidth is 0 or a power of two and the array count is a power of two, so the
 // DRAM latency term is one exact multiply of the table value; otherwise it is divided out.
 //
-// Persistent blocks (as many as the chip holds) pull work items from a global counter.  One item =
-// SEARCH_THREADS rows of one (r, f) group (lane = row) x TC consecutive tilings (loop).
 // LIMIT: only candidates whose energy is below a.e_limit take part (one step of the Pareto walk).
+// REGROUP: every term of the energy is an exact integer (ModelConst::regroup), so the sum is taken
+// as (row, tiling) part + (tiling, combination) part; the bits are those of the general order.
+//
+// Persistent blocks (as many as the chip holds) pull work items from a global counter.  One item =
+// SEARCH_THREADS rows of one recomputation class (lane = row) x up to TC consecutive tilings (loop).
 constexpr int popcount4(int m) { return (m & 1) + ((m >> 1) & 1) + ((m >> 2) & 1) + ((m >> 3) & 1); }
 
-template <int MASK, bool FAST, bool LIMIT = false>
+template <int MASK, bool FAST, bool LIMIT = false, bool REGROUP = false>
 __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 && MASK != 4)) ? 2 : 4) void k_search(SearchArgs a)
 {
     __shared__ double tab[TC * NENT];
@@ -859,7 +864,8 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
                 double bs2 = v[u][3] + v[u][2] + v[u][4];
                 bool ok = fmax(bs1, bs2) <= cap;
                 dram_words[u] = v[u][5] + v[u][6] + v[u][7];   // B*H * Eq. (7)
-                e_dram_part[u] = ok ? a.mc.e_dram * dram_words[u] : inf;
+                // regrouped: all of the energy that depends on the row, (e_dram + e_gb) * B*H * DA
+                e_dram_part[u] = ok ? (REGROUP ? a.mc.e_sum : a.mc.e_dram) * dram_words[u] : inf;
                 if constexpr (FAST) l_dram[u] = dram_words[u] * a.mc.dram_k;
                 else l_dram[u] = a.mc.dram_bw > 0.0 ? a.mc.c_lat * (((dram_words[u] / a.mc.BH) * a.mc.word) / a.mc.dram_bw) : 0.0;
                 l_dram[u] = ok ? l_dram[u] : inf;
@@ -882,10 +888,15 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
                 const double dw = dram_words[u], edp_ = e_dram_part[u], ld = l_dram[u];
 
                 auto cost_one = [&](int c9, double gb_part, double lat_part) {
-                    double gb_words = dw + gb_part;
-                    double en = edp_ + a.mc.e_gb * gb_words;
-                    en = en + e_rf_now;
-                    en = en + e_mac_now;
+                    double en;
+                    if constexpr (REGROUP) {
+                        en = edp_ + gb_part;                  // row part + tiling part, both exact
+                    } else {
+                        double gb_words = dw + gb_part;
+                        en = edp_ + a.mc.e_gb * gb_words;
+                        en = en + e_rf_now;
+                        en = en + e_mac_now;
+                    }
                     double lat = fmax(ld, lat_part);
                     if constexpr (LIMIT) {
                         bool out_of_range = !(en < a.e_limit);
@@ -969,7 +980,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
                 for (int k = 0; k < NSEL; ++k) w[k] = row_tab[__builtin_amdgcn_readlane(off[k], src)];
                 bool ok2 = fmax(w[0] + w[2] + w[1], w[3] + w[2] + w[4]) <= a.mc.cap_words;
                 double dram2 = w[5] + w[6] + w[7];
-                double e_dram2 = ok2 ? a.mc.e_dram * dram2 : inf;
+                double e_dram2 = ok2 ? (REGROUP ? a.mc.e_sum : a.mc.e_dram) * dram2 : inf;
                 double l_dram2;
                 if constexpr (FAST) l_dram2 = dram2 * a.mc.dram_k;
                 else l_dram2 = a.mc.dram_bw > 0.0 ? a.mc.c_lat * (((dram2 / a.mc.BH) * a.mc.word) / a.mc.dram_bw) : 0.0;
@@ -977,10 +988,15 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
                 pin(e_dram2);
                 pin(l_dram2);
                 ConstF64 cl = cs_base + (uint64_t)tl_mine * 2 * NCS;
-                double gb2 = dram2 + cl[c_u];
-                double en2 = e_dram2 + a.mc.e_gb * gb2;
-                en2 = en2 + cl[18];
-                en2 = en2 + cl[19];
+                double en2;
+                if constexpr (REGROUP) {
+                    en2 = e_dram2 + cl[c_u];
+                } else {
+                    double gb2 = dram2 + cl[c_u];
+                    en2 = e_dram2 + a.mc.e_gb * gb2;
+                    en2 = en2 + cl[18];
+                    en2 = en2 + cl[19];
+                }
                 double lat2 = fmax(l_dram2, cl[9 + c_u]);
                 double val2 = o == 0 ? en2 : (o == 1 ? lat2 : en2 * lat2);
                 const unsigned long long hits = __ballot(lane < nt && val2 == wave_v);

@@ -53,6 +53,8 @@ constexpr uint64_t ROWS_PER_TILING = 540000; // * 9 stationary combinations
 //   [0..8]  BH * BR(combo)                      combo = s1 + 3 s2
 //   [9..17] c_lat * max(comp(combo), BR*w/gb_bw)
 //   [18]    e_rf * T_rf      [19] e_mac * T_mac
+// When the energy is regrouped (ModelConst::regroup) [0..8] hold the whole part of the energy that
+// does not depend on the row instead: e_gb * BH * BR(combo) + e_rf * T_rf + e_mac * T_mac.
 constexpr int NCS = 20;
 // per (r, field, tiling) values read by the per-candidate kernel, 64 bits each:
 //   [0..8] BR (u64)   [9..17] cycles (u64)   [18] MAC (u64)   [19] softmax elements (u64)
@@ -73,10 +75,15 @@ struct ModelConst {
     double cap_words;   // floor(gb_bytes / word_bytes)
     double word;        // word_bytes
     double e_dram, e_gb, e_rf, e_mac;
+    double e_sum;       // e_dram + e_gb, the weight of a DRAM word when the energy is regrouped
     double dram_bw, gb_bw;
     double dram_k;      // word / dram_bw / n_arrays when that is exact (powers of two), else unused
     double eval_k;      // word / dram_bw when the bandwidth is a power of two (or 0), else unused
     uint32_t bw_pow2;   // the DRAM bandwidth is 0 or a power of two
+    // The four energies are whole numbers and the largest total energy stays below 2^53: every
+    // product and partial sum of the energy is then an exact integer, the order of the additions
+    // cannot change a bit of the result, and the search adds one row part and one tiling part.
+    uint32_t regroup;
     uint32_t pe_rows, pe_cols, g_words, c_softmax;
     uint32_t T, tpad;
 };

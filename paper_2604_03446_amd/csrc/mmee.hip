@@ -63,6 +63,7 @@ struct Plan {
     uint64_t T;
     uint64_t space;
     bool exact_k;
+    bool can_regroup;   // every term of the energy is an exact integer below 2^53
 };
 
 bool finite_nonneg(double v) { return std::isfinite(v) && v >= 0.0; }
@@ -129,6 +130,19 @@ int make_plan(const mmee_chain *w, const mmee_hw *hw, Plan &p)
     mc.cap_words = cap >= (1ull << 53) ? 9007199254740992.0 : (double)cap;
     mc.word = (double)w->word_bytes;
     mc.e_dram = hw->e_dram; mc.e_gb = hw->e_gb; mc.e_rf = hw->e_rf; mc.e_mac = hw->e_mac;
+    mc.e_sum = hw->e_dram + hw->e_gb;
+    {
+        // Per instance, with P = I*K*L*J: DRAM words <= 8 P (four operands at most P each, the
+        // unfused intermediate at most I*L*(K+J+2) <= 4 P), buffer<->RF words <= 6 P (three terms
+        // per tile matmul, each at most its MAC count; MACs <= 2 P with recomputation), RF accesses
+        // 3 * MACs <= 6 P, softmax elements <= P.  The total energy bounds every partial sum.
+        auto whole = [](double v) { return v == std::floor(v); };
+        const long double P = (long double)w->batch * (long double)w->I * w->K * (long double)w->L * w->J;
+        const long double worst = P * (8.0L * hw->e_dram + 14.0L * hw->e_gb + 6.0L * hw->e_rf +
+                                       (2.0L + (long double)w->c_softmax) * hw->e_mac);
+        p.can_regroup = whole(hw->e_dram) && whole(hw->e_gb) && whole(hw->e_rf) && whole(hw->e_mac) &&
+                        worst < 9007199254740992.0L;
+    }
     mc.dram_bw = hw->dram_bw; mc.gb_bw = hw->gb_bw;
     // with a power-of-two bandwidth and array count, (B*H/n) * (words*word/bw) is the B*H-scaled
     // table value times one exactly representable constant
@@ -231,11 +245,20 @@ int ensure_slots(size_t n)
     return MMEE_OK;
 }
 
-int launch_tilings(const Plan &p, DivTable *dv_copy = nullptr)
+// the model constants of one pass: whether the energy is regrouped is settled here, for the tables
+// and for the kernel alike
+ModelConst pass_constants(const Plan &p, uint32_t flags)
 {
-    int rc = ensure_tilings(p.mc.tpad);
+    ModelConst mc = p.mc;
+    mc.regroup = (p.can_regroup && p.exact_k && !(flags & MMEE_SEARCH_ORDERED_SUM)) ? 1u : 0u;
+    return mc;
+}
+
+int launch_tilings(const Plan &p, const ModelConst &mc, DivTable *dv_copy = nullptr)
+{
+    int rc = ensure_tilings(mc.tpad);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_build_tilings, dim3(p.mc.tpad / 64), dim3(64), 0, S.stream, p.dv, p.mc, S.btab,
+    hipLaunchKernelGGL(k_build_tilings, dim3(mc.tpad / 64), dim3(64), 0, S.stream, p.dv, mc, S.btab,
                        S.ctab_s, S.ctab_e, dv_copy);
     HIP_TRY(hipGetLastError());
     return MMEE_OK;
@@ -244,14 +267,16 @@ int launch_tilings(const Plan &p, DivTable *dv_copy = nullptr)
 template <int MASK>
 void launch_search_mask(bool exact_k, dim3 grid, const SearchArgs &a)
 {
-    if (exact_k) hipLaunchKernelGGL((k_search<MASK, true>), grid, dim3(SEARCH_THREADS), 0, S.stream, a);
+    if (a.mc.regroup) hipLaunchKernelGGL((k_search<MASK, true, false, true>), grid, dim3(SEARCH_THREADS), 0, S.stream, a);
+    else if (exact_k) hipLaunchKernelGGL((k_search<MASK, true>), grid, dim3(SEARCH_THREADS), 0, S.stream, a);
     else hipLaunchKernelGGL((k_search<MASK, false>), grid, dim3(SEARCH_THREADS), 0, S.stream, a);
 }
 
 // one step of the Pareto walk: latency-then-energy among candidates with energy below a.e_limit
 void launch_search_limited(bool exact_k, dim3 grid, const SearchArgs &a)
 {
-    if (exact_k) hipLaunchKernelGGL((k_search<4, true, true>), grid, dim3(SEARCH_THREADS), 0, S.stream, a);
+    if (a.mc.regroup) hipLaunchKernelGGL((k_search<4, true, true, true>), grid, dim3(SEARCH_THREADS), 0, S.stream, a);
+    else if (exact_k) hipLaunchKernelGGL((k_search<4, true, true>), grid, dim3(SEARCH_THREADS), 0, S.stream, a);
     else hipLaunchKernelGGL((k_search<4, false, true>), grid, dim3(SEARCH_THREADS), 0, S.stream, a);
 }
 
@@ -260,7 +285,8 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
                    const double *e_limit = nullptr, bool build_tables = true, bool bs_da_step = false)
 {
     if (slot >= S.slots) return MMEE_EINVAL;
-    int rc = build_tables ? launch_tilings(p, S.dv_dev + slot) : MMEE_OK;
+    const ModelConst mc = pass_constants(p, flags);
+    int rc = build_tables ? launch_tilings(p, mc, S.dv_dev + slot) : MMEE_OK;
     if (rc) return rc;
     const int which = (flags & MMEE_SEARCH_EXHAUSTIVE) ? 0 : 1;
     SearchArgs a;
@@ -291,7 +317,7 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
         a.n_fc = (uint32_t)((p.T - (uint64_t)a.n_cc * TC + TC_FINE - 1) / TC_FINE);
     }
     a.btab = S.btab; a.ctab_s = S.ctab_s; a.ctab_e = S.ctab_e;
-    a.mc = p.mc;
+    a.mc = mc;
     const uint64_t n_items = (uint64_t)rb * ((uint64_t)a.n_cc + a.n_fc);
     if (n_items == 0 || n_items > 0x7fffffffull) return MMEE_EINVAL;
     a.n_coarse_items = rb * a.n_cc;
@@ -451,7 +477,7 @@ int mmee_chain_eval_batch(const mmee_chain *w, const mmee_hw *hw, uint64_t first
     std::lock_guard<std::mutex> guard(g_lock);
     rc = ensure_ready();
     if (rc) return rc;
-    rc = launch_tilings(p);
+    rc = launch_tilings(p, p.mc);
     if (rc) return rc;
 
     hipPointerAttribute_t attr;
@@ -500,7 +526,7 @@ int mmee_chain_search_many(const mmee_chain *w, const mmee_hw *hw, const int *ob
 {
     if (!count) return MMEE_OK;
     if (!w || !hw || !objectives || !out) return MMEE_EINVAL;
-    if (flags & ~(uint32_t)MMEE_SEARCH_EXHAUSTIVE) return MMEE_EINVAL;
+    if (flags & ~(uint32_t)(MMEE_SEARCH_EXHAUSTIVE | MMEE_SEARCH_ORDERED_SUM)) return MMEE_EINVAL;
     std::lock_guard<std::mutex> guard(g_lock);
     const double t_start = now_seconds();
     int rc = ensure_ready();
@@ -574,7 +600,7 @@ static int walk_front(const mmee_chain *w, const mmee_hw *hw, bool bs_da, uint32
                uint32_t capacity, uint32_t *n_points)
 {
     if (!w || !hw || !out || !n_points || !capacity) return MMEE_EINVAL;
-    if (flags & ~(uint32_t)MMEE_SEARCH_EXHAUSTIVE) return MMEE_EINVAL;
+    if (flags & ~(uint32_t)(MMEE_SEARCH_EXHAUSTIVE | MMEE_SEARCH_ORDERED_SUM)) return MMEE_EINVAL;
     *n_points = 0;
     Plan p;
     int rc = make_plan(w, hw, p);
@@ -639,6 +665,23 @@ int mmee_front_bs_da(const mmee_workload *w, const mmee_hw *hw, uint32_t flags, 
     mmee_chain c;
     int rc = chain_of(w, c);
     return rc ? rc : mmee_chain_front_bs_da(&c, hw, flags, out, capacity, n_points);
+}
+
+int mmee_chain_energy_regrouped(const mmee_chain *w, const mmee_hw *hw, uint32_t flags, int *out)
+{
+    if (!out || (flags & ~(uint32_t)(MMEE_SEARCH_EXHAUSTIVE | MMEE_SEARCH_ORDERED_SUM))) return MMEE_EINVAL;
+    Plan p;
+    int rc = make_plan(w, hw, p);
+    if (rc) return rc;
+    *out = (int)pass_constants(p, flags).regroup;
+    return MMEE_OK;
+}
+
+int mmee_energy_regrouped(const mmee_workload *w, const mmee_hw *hw, uint32_t flags, int *out)
+{
+    mmee_chain c;
+    int rc = chain_of(w, c);
+    return rc ? rc : mmee_chain_energy_regrouped(&c, hw, flags, out);
 }
 
 int mmee_space_size(const mmee_workload *w, const mmee_hw *hw, uint64_t *out)

@@ -75,3 +75,42 @@ def test_host_factorisation_matches_naive_divisor_counts():
     # an extent with more divisors than the tables hold is refused
     with pytest.raises(M.MmeeError):
         M.mmee_chain_space_size(dict(batch=1, I=1441440, K=1, L=1, J=1, word_bytes=2, tiling_mode=1, c_softmax=0), hw)
+
+
+def test_energy_regrouping_is_offered_only_where_it_is_exact():
+    """The search may add the energy as a row part plus a tiling part only when no rounding can
+    occur: whole-number energies per access and a total below 2^53.  The size test rests on the
+    bounds DRAM words <= 8 P, DRAM + buffer<->RF words <= 14 P, RF accesses <= 6 P and
+    MACs + c_softmax * softmax elements <= (2 + c_softmax) P per instance, P = I*K*L*J; the oracle's
+    maxima over whole small spaces (one unit energy at a time) must respect them."""
+    import numpy as np
+    import oracle as O
+    import paper_2604_03446_amd as M
+    from inputs import CONFIGS, sweep_hw
+    reg = {k: M.mmee_energy_regrouped(c["workload"], c["hw"]) for k, c in CONFIGS.items()}
+    assert reg == {"tiny": True, "bert": True, "prefill": True, "long": False}   # long: up to 2^56 pJ
+    bert = CONFIGS["bert"]
+    assert not M.mmee_energy_regrouped(bert["workload"], bert["hw"], M.SEARCH_ORDERED_SUM)
+    assert not M.mmee_energy_regrouped(bert["workload"], dict(bert["hw"], e_gb=6.5))
+    assert not M.mmee_energy_regrouped(bert["workload"], dict(bert["hw"], dram_bw=48.0))
+    assert not M.mmee_energy_regrouped(bert["workload"], dict(bert["hw"], n_arrays=3))
+    assert M.mmee_energy_regrouped(bert["workload"], dict(bert["hw"], e_dram=8.0e4))
+    assert not M.mmee_energy_regrouped(bert["workload"], dict(bert["hw"], e_dram=9.0e4))
+    assert not any(M.mmee_energy_regrouped(bert["workload"], h) for h in sweep_hw()[:8])  # fractional e_dram
+
+    small = [dict(B=1, H=2, N=8, d=2, word_bytes=2, tiling_mode=1, c_softmax=10),
+             dict(B=1, H=1, N=12, d=6, word_bytes=2, tiling_mode=0, c_softmax=3)]
+    base_hw = dict(pe_rows=2, pe_cols=4, n_arrays=1, rf_bytes=32, gb_bytes=1 << 30,
+                   e_dram=0.0, e_gb=0.0, e_rf=0.0, e_mac=0.0, dram_bw=2.0, gb_bw=64.0)
+    for w in small:
+        P = w["B"] * w["H"] * w["N"] * w["d"] * w["N"] * w["d"]
+        ow = O.workload(w)
+        for unit, coef in (("e_dram", 8), ("e_gb", 14), ("e_rf", 6), ("e_mac", 2 + w["c_softmax"])):
+            oh = O.hw({**base_hw, unit: 1.0})
+            S, worst = O.space_size(ow, oh), 0.0
+            for first in range(0, S, 1 << 22):
+                rec = O.eval_batch(ow, oh, first, min(1 << 22, S - first))
+                e = rec["energy_pj"][rec["reason"] != 1]        # every index that denotes a dataflow
+                worst = max(worst, float(e.max()))
+                assert np.all(e == np.floor(e))
+            assert 0 < worst <= coef * P, (w, unit, worst, coef * P)

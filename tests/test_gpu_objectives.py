@@ -31,7 +31,7 @@ def test_edp_and_all_objectives_small_spaces(M, case):
     ow, oh = O.workload(w), O.hw(h)
     rc, idx, cost, _, _ = O.search_all(ow, oh)
     assert rc == 0
-    for flags in (M.SEARCH_EXHAUSTIVE, M.SEARCH_PRUNED):
+    for flags in (M.SEARCH_EXHAUSTIVE, M.SEARCH_PRUNED, M.SEARCH_EXHAUSTIVE | M.SEARCH_ORDERED_SUM):
         single = M.mmee_search_ex(w, h, M.OBJ_EDP, flags)
         four = M.mmee_search_multi(w, h, [3, 0, 2, 1], flags)        # any order of distinct objectives
         pair = M.mmee_search_multi(w, h, [0, 3], flags)
@@ -69,7 +69,7 @@ def test_pareto_small_spaces_against_oracle(M, case):
     ow, oh = O.workload(w), O.hw(h)
     rc, idx, cost = O.pareto(ow, oh)
     assert rc == 0
-    for flags in (M.SEARCH_EXHAUSTIVE, M.SEARCH_PRUNED):
+    for flags in (M.SEARCH_EXHAUSTIVE, M.SEARCH_PRUNED, M.SEARCH_PRUNED | M.SEARCH_ORDERED_SUM):
         code, front = M.mmee_pareto(w, h, flags)
         assert code == 0 and [p.best.idx for p in front] == idx, (case, flags)
         for p, c in zip(front, cost):
@@ -89,7 +89,7 @@ def test_pareto_tiny_against_oracle_full_enumeration(M):
     ow, oh = O.workload(w), O.hw(h)
     rc, idx, cost = O.pareto(ow, oh)
     assert rc == 0
-    for flags in (M.SEARCH_PRUNED, M.SEARCH_EXHAUSTIVE):
+    for flags in (M.SEARCH_PRUNED, M.SEARCH_EXHAUSTIVE, M.SEARCH_EXHAUSTIVE | M.SEARCH_ORDERED_SUM):
         code, front = M.mmee_pareto(w, h, flags)
         assert code == 0 and [p.best.idx for p in front] == idx
         check_front(front, ow, oh)
