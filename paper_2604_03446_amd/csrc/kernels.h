@@ -608,20 +608,24 @@ constexpr int TC_FINE = 32;            // tilings per fine item
 constexpr int SEARCH_THREADS = 512;
 
 
-// LDS access through explicit 32-bit addresses: one address register per selector serves two
-// table rows (base and base + NENT entries) in a single paired read.
+// The staged table keeps the global layout, entry-major: the tilings of an entry are consecutive and
+// an entry's line is padded to LDS_ENT values, which spreads the entries over the banks.  One address
+// register per selector and the immediate offsets of a paired read then reach the tilings of a whole
+// loop turn.  LDS access goes through explicit 32-bit addresses.
+constexpr int LDS_ENT = 65;            // TC tilings + 1
+constexpr int TURN = 8;                // tilings per loop turn
 typedef const double __attribute__((address_space(3))) *LdsF64;
 __device__ __forceinline__ uint32_t lds_address(const double *p)
 {
     return (uint32_t)(uintptr_t)(LdsF64)p;
 }
-__device__ __forceinline__ void read_pair(uint32_t base, uint32_t row_bytes, double &first, double &second)
+// tilings tl and tl + 1 (tl a constant after unrolling) of the entry at addr
+__device__ __forceinline__ void read_tilings(uint32_t &addr, int tl, double &first, double &second)
 {
-    uint32_t addr = base + row_bytes;
     asm("" : "+v"(addr));                         // one register, two constant offsets
     LdsF64 p = (LdsF64)(uintptr_t)addr;
-    first = p[0];
-    second = p[NENT];
+    first = p[tl];
+    second = p[tl + 1];
 }
 
 // What a work item covers: the recomputation class r, the tilings [t0, t0 + nt) and, per thread,
@@ -665,21 +669,21 @@ __device__ __forceinline__ uint32_t index_row_base(uint32_t dfrow)
     return dfrow % ROWS_PER_GROUP + 15000u * (g & 1) + 270000u * (g >> 1);
 }
 
-// Stage the tilings [t0, t0 + nt) of the boundary-side tables: global entry-major -> LDS
-// tiling-major, two tilings per thread and turn (one 16-byte load, one paired LDS write).  PAIRS =
-// tiling pairs per item.  When nt is odd the pair that starts at nt - 1 brings one column more:
-// beyond the last tiling the global table repeats it (k_build_tilings), and a repeated tiling
-// changes no minimum, so the loops may take tilings in pairs.
+// Stage the tilings [t0, t0 + nt) of the boundary-side tables, entry-major in global memory and in
+// LDS, two tilings per thread and turn (one 16-byte load, one paired LDS write).  PAIRS =
+// tiling pairs per item.  nt is rounded up to whole loop turns: beyond the last tiling the global
+// table repeats it up to its padded width (k_build_tilings), and a repeated tiling changes no minimum.
 template <int PAIRS>
 __device__ __forceinline__ void stage_tables(const SearchArgs &a, double *tab, uint32_t t0, uint32_t nt)
 {
     typedef double v2f64 __attribute__((ext_vector_type(2)));
+    const uint32_t rows = (nt + TURN - 1) / TURN * TURN;
     for (uint32_t i = threadIdx.x; i < NENT * PAIRS; i += SEARCH_THREADS) {
         const uint32_t ent = i / PAIRS, tl = (i % PAIRS) * 2;
-        if (tl < nt) {
+        if (tl < rows) {
             const v2f64 two = *reinterpret_cast<const v2f64 *>(a.btab + (uint64_t)ent * a.mc.tpad + t0 + tl);
-            tab[tl * NENT + ent] = two.x;
-            tab[(tl + 1) * NENT + ent] = two.y;
+            tab[ent * LDS_ENT + tl] = two.x;
+            tab[ent * LDS_ENT + tl + 1] = two.y;
         }
     }
 }
@@ -781,7 +785,7 @@ constexpr int popcount4(int m) { return (m & 1) + ((m >> 1) & 1) + ((m >> 2) & 1
 template <int MASK, bool FAST, bool LIMIT = false, bool REGROUP = false>
 __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 && MASK != 4)) ? 2 : 4) void k_search(SearchArgs a)
 {
-    __shared__ double tab[TC * NENT];
+    __shared__ double tab[NENT * LDS_ENT];
     __shared__ Key wave_best[N_OBJ][SEARCH_THREADS / 64];
     __shared__ uint32_t is_last;
 
@@ -835,112 +839,125 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
         }
 
         // Software pipeline: table values (LDS) and the per-tiling constants (scalar loads) of the
-        // next tiling are requested while the current one is costed.  The constants come in two
+        // next tilings are requested while the current ones are costed.  The constants come in two
         // halves (combinations 0..4 / 5..8) so that each half is reloaded as soon as it is spent.
         ConstF64 cs_base = as_constant(a.ctab_s + ((uint64_t)t0 * 2 + r) * NCS);
-        // Two tilings per turn: their table values come from one LDS address per selector (the
-        // second row sits NENT entries further), requested a turn ahead.
+        // Tilings are taken in pairs, four pairs per loop turn.  A pair's table values come from
+        // one LDS address per selector: a paired read reaches every tiling of the turn through its
+        // immediate offsets, and the addresses move once a turn.
         double v[2][NSEL];
         uint32_t sel_addr[NSEL];
 #pragma unroll
-        for (int k = 0; k < NSEL; ++k) sel_addr[k] = lds_address(tab + off[k]);
+        for (int k = 0; k < NSEL; ++k) sel_addr[k] = lds_address(tab + off[k] * LDS_ENT);
 #pragma unroll
-        for (int k = 0; k < NSEL; ++k) read_pair(sel_addr[k], 0, v[0][k], v[1][k]);
+        for (int k = 0; k < NSEL; ++k) read_tilings(sel_addr[k], 0, v[0][k], v[1][k]);
         double gbA[5], latA[5], gbB[4], latB[4], e_rf_part, e_mac_part;
 #pragma unroll
         for (int c = 0; c < 5; ++c) { gbA[c] = cs_base[c]; latA[c] = cs_base[9 + c]; }
 #pragma unroll
         for (int c = 0; c < 4; ++c) { gbB[c] = cs_base[5 + c]; latB[c] = cs_base[14 + c]; }
         e_rf_part = cs_base[18]; e_mac_part = cs_base[19];
-        ConstF64 cs_cur = cs_base;
-        ConstF64 const cs_end = cs_base + (uint64_t)nt * 2 * NCS;
 
-        for (uint32_t tl2 = 0; tl2 < nt; tl2 += 2) {
-            double dram_words[2], e_dram_part[2], l_dram[2];
+        // nt rounded up to whole turns: the staged rows beyond nt repeat the last tiling
+        const uint32_t nt_turns = (nt + TURN - 1) / TURN * TURN;
+        for (uint32_t tl8 = 0; tl8 < nt_turns; tl8 += TURN) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                // Eq. (1), (2), (4) and the capacity mask
-                double bs1 = v[u][0] + v[u][2] + v[u][1];
-                double bs2 = v[u][3] + v[u][2] + v[u][4];
-                bool ok = fmax(bs1, bs2) <= cap;
-                dram_words[u] = v[u][5] + v[u][6] + v[u][7];   // B*H * Eq. (7)
-                // regrouped: all of the energy that depends on the row, (e_dram + e_gb) * B*H * DA
-                e_dram_part[u] = ok ? (REGROUP ? a.mc.e_sum : a.mc.e_dram) * dram_words[u] : inf;
-                if constexpr (FAST) l_dram[u] = dram_words[u] * a.mc.dram_k;
-                else l_dram[u] = a.mc.dram_bw > 0.0 ? a.mc.c_lat * (((dram_words[u] / a.mc.BH) * a.mc.word) / a.mc.dram_bw) : 0.0;
-                l_dram[u] = ok ? l_dram[u] : inf;
-                pin(e_dram_part[u]);
-                pin(l_dram[u]);
-            }
-            {
-                // rows tl2+2 and tl2+3, kept inside the staged chunk when the loop is about to end
-                const uint32_t row_bytes = min(tl2 + 2, (uint32_t)TC - 2) * (NENT * 8);
+            for (int q = 0; q < TURN / 2; ++q) {
+                double dram_words[2], e_dram_part[2], l_dram[2];
 #pragma unroll
-                for (int k = 0; k < NSEL; ++k) read_pair(sel_addr[k], row_bytes, v[0][k], v[1][k]);
-            }
+                for (int u = 0; u < 2; ++u) {
+                    // Eq. (1), (2), (4) and the capacity mask
+                    double bs1 = v[u][0] + v[u][2] + v[u][1];
+                    double bs2 = v[u][3] + v[u][2] + v[u][4];
+                    bool ok = fmax(bs1, bs2) <= cap;
+                    dram_words[u] = v[u][5] + v[u][6] + v[u][7];   // B*H * Eq. (7)
+                    // regrouped: all of the energy that depends on the row, (e_dram + e_gb) * B*H * DA
+                    e_dram_part[u] = (REGROUP ? a.mc.e_sum : a.mc.e_dram) * dram_words[u];
+                    if constexpr (FAST) l_dram[u] = dram_words[u] * a.mc.dram_k;
+                    else l_dram[u] = a.mc.dram_bw > 0.0 ? a.mc.c_lat * (((dram_words[u] / a.mc.BH) * a.mc.word) / a.mc.dram_bw) : 0.0;
+                    // a candidate over capacity costs +inf: neither term is negative, so the larger
+                    // of the term and (0 or +inf) is the term or +inf
+                    const double over = __hiloint2double(ok ? 0 : 0x7ff00000, 0);
+                    e_dram_part[u] = fmax(e_dram_part[u], over);
+                    l_dram[u] = fmax(l_dram[u], over);
+                    pin(e_dram_part[u]);
+                    pin(l_dram[u]);
+                }
+                // request the next pair's rows; at the end of a turn the addresses move on, except
+                // on the last turn, which reads its last pair again
+                if (q < TURN / 2 - 1) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const uint32_t tl = tl2 + u;
-                ConstF64 cs_next = cs_cur + 2 * NCS;          // stay inside the table on the last turn
-                cs_next = cs_next < cs_end ? cs_next : cs_cur;
-                cs_cur = cs_next;
-                const double e_rf_now = e_rf_part, e_mac_now = e_mac_part;
-                const double dw = dram_words[u], edp_ = e_dram_part[u], ld = l_dram[u];
+                    for (int k = 0; k < NSEL; ++k) read_tilings(sel_addr[k], 2 * (q + 1), v[0][k], v[1][k]);
+                } else {
+                    const uint32_t step = tl8 + TURN < nt_turns ? TURN * 8 : (TURN - 2) * 8;
+#pragma unroll
+                    for (int k = 0; k < NSEL; ++k) sel_addr[k] += step;
+#pragma unroll
+                    for (int k = 0; k < NSEL; ++k) read_tilings(sel_addr[k], 0, v[0][k], v[1][k]);
+                }
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const uint32_t tl = tl8 + 2 * q + u;
+                    // the next tiling's constants; past the end, the last tiling's once more
+                    ConstF64 cs_next = cs_base + (uint64_t)(min(tl + 1, nt - 1) * (2 * NCS));
+                    const double e_rf_now = e_rf_part, e_mac_now = e_mac_part;
+                    const double dw = dram_words[u], edp_ = e_dram_part[u], ld = l_dram[u];
 
-                auto cost_one = [&](int c9, double gb_part, double lat_part) {
-                    double en;
-                    if constexpr (REGROUP) {
-                        en = edp_ + gb_part;                  // row part + tiling part, both exact
-                    } else {
-                        double gb_words = dw + gb_part;
-                        en = edp_ + a.mc.e_gb * gb_words;
-                        en = en + e_rf_now;
-                        en = en + e_mac_now;
-                    }
-                    double lat = fmax(ld, lat_part);
-                    if constexpr (LIMIT) {
-                        bool out_of_range = !(en < a.e_limit);
-                        en = out_of_range ? inf : en;
-                        lat = out_of_range ? inf : lat;
-                    }
-                    if constexpr (LAZY) {
-                        if constexpr (MASK & 8) bestP[c9] = fmin(bestP[c9], en * lat);
-                        if constexpr (MASK & 1) bestE[c9] = fmin(bestE[c9], en);
-                        if constexpr (MASK & 2) bestL[c9] = fmin(bestL[c9], lat);
-                        return;
-                    }
-                    if constexpr (MASK & 8) {
-                        double edp = en * lat;
-                        bool lt = edp < bestP[c9];
-                        bestP[c9] = fmin(bestP[c9], edp);
-                        codeP[c9] = lt ? tl : codeP[c9];
-                    }
-                    if constexpr (MASK & 1) {
-                        bool lt = en < bestE[c9];
-                        bestE[c9] = fmin(bestE[c9], en);
-                        codeE[c9] = lt ? tl : codeE[c9];
-                    }
-                    if constexpr (MASK & 2) {
-                        bool lt = lat < bestL[c9];
-                        bestL[c9] = fmin(bestL[c9], lat);
-                        codeL[c9] = lt ? tl : codeL[c9];
-                    }
-                    if constexpr (MASK & 4) {
-                        bool lt = lat < bestLE_l[c9] || (lat == bestLE_l[c9] && en < bestLE_e[c9]);
-                        bestLE_l[c9] = lt ? lat : bestLE_l[c9];
-                        bestLE_e[c9] = lt ? en : bestLE_e[c9];
-                        codeLE[c9] = lt ? tl : codeLE[c9];
-                    }
-                };
+                    auto cost_one = [&](int c9, double gb_part, double lat_part) {
+                        double en;
+                        if constexpr (REGROUP) {
+                            en = edp_ + gb_part;                  // row part + tiling part, both exact
+                        } else {
+                            double gb_words = dw + gb_part;
+                            en = edp_ + a.mc.e_gb * gb_words;
+                            en = en + e_rf_now;
+                            en = en + e_mac_now;
+                        }
+                        double lat = fmax(ld, lat_part);
+                        if constexpr (LIMIT) {
+                            bool out_of_range = !(en < a.e_limit);
+                            en = out_of_range ? inf : en;
+                            lat = out_of_range ? inf : lat;
+                        }
+                        if constexpr (LAZY) {
+                            if constexpr (MASK & 8) bestP[c9] = fmin(bestP[c9], en * lat);
+                            if constexpr (MASK & 1) bestE[c9] = fmin(bestE[c9], en);
+                            if constexpr (MASK & 2) bestL[c9] = fmin(bestL[c9], lat);
+                            return;
+                        }
+                        if constexpr (MASK & 8) {
+                            double edp = en * lat;
+                            bool lt = edp < bestP[c9];
+                            bestP[c9] = fmin(bestP[c9], edp);
+                            codeP[c9] = lt ? tl : codeP[c9];
+                        }
+                        if constexpr (MASK & 1) {
+                            bool lt = en < bestE[c9];
+                            bestE[c9] = fmin(bestE[c9], en);
+                            codeE[c9] = lt ? tl : codeE[c9];
+                        }
+                        if constexpr (MASK & 2) {
+                            bool lt = lat < bestL[c9];
+                            bestL[c9] = fmin(bestL[c9], lat);
+                            codeL[c9] = lt ? tl : codeL[c9];
+                        }
+                        if constexpr (MASK & 4) {
+                            bool lt = (lat < bestLE_l[c9]) | ((lat == bestLE_l[c9]) & (en < bestLE_e[c9]));
+                            bestLE_l[c9] = lt ? lat : bestLE_l[c9];
+                            bestLE_e[c9] = lt ? en : bestLE_e[c9];
+                            codeLE[c9] = lt ? tl : codeLE[c9];
+                        }
+                    };
 #pragma unroll
-                for (int c = 0; c < 5; ++c) cost_one(c, gbA[c], latA[c]);
+                    for (int c = 0; c < 5; ++c) cost_one(c, gbA[c], latA[c]);
 #pragma unroll
-                for (int c = 0; c < 5; ++c) { gbA[c] = cs_next[c]; latA[c] = cs_next[9 + c]; }
-                e_rf_part = cs_next[18]; e_mac_part = cs_next[19];
+                    for (int c = 0; c < 5; ++c) { gbA[c] = cs_next[c]; latA[c] = cs_next[9 + c]; }
+                    e_rf_part = cs_next[18]; e_mac_part = cs_next[19];
 #pragma unroll
-                for (int c = 0; c < 4; ++c) cost_one(5 + c, gbB[c], latB[c]);
+                    for (int c = 0; c < 4; ++c) cost_one(5 + c, gbB[c], latB[c]);
 #pragma unroll
-                for (int c = 0; c < 4; ++c) { gbB[c] = cs_next[5 + c]; latB[c] = cs_next[14 + c]; }
+                    for (int c = 0; c < 4; ++c) { gbB[c] = cs_next[5 + c]; latB[c] = cs_next[14 + c]; }
+                }
             }
         }
 
@@ -974,10 +991,9 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
                 const uint32_t src = (uint32_t)__ffsll((long long)owners) - 1u;
                 const uint32_t c_u = __builtin_amdgcn_readlane(cstar, src);
                 const uint32_t tl_mine = min(lane, nt - 1);          // lanes beyond the chunk repeat its last tiling
-                const double *row_tab = tab + tl_mine * NENT;
                 double w[NSEL];
 #pragma unroll
-                for (int k = 0; k < NSEL; ++k) w[k] = row_tab[__builtin_amdgcn_readlane(off[k], src)];
+                for (int k = 0; k < NSEL; ++k) w[k] = tab[__builtin_amdgcn_readlane(off[k], src) * LDS_ENT + tl_mine];
                 bool ok2 = fmax(w[0] + w[2] + w[1], w[3] + w[2] + w[4]) <= a.mc.cap_words;
                 double dram2 = w[5] + w[6] + w[7];
                 double e_dram2 = ok2 ? (REGROUP ? a.mc.e_sum : a.mc.e_dram) * dram2 : inf;
@@ -1070,7 +1086,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
 // tables' unit, B*H words.  Same items, staging and finish as k_search; result in slot 0.
 __global__ __launch_bounds__(SEARCH_THREADS, 4) void k_front_step(SearchArgs a)
 {
-    __shared__ double tab[TC * NENT];
+    __shared__ double tab[NENT * LDS_ENT];
     __shared__ Key wave_best[N_OBJ][SEARCH_THREADS / 64];
     __shared__ uint32_t is_last;
     __shared__ uint32_t s_item;
@@ -1102,10 +1118,9 @@ __global__ __launch_bounds__(SEARCH_THREADS, 4) void k_front_step(SearchArgs a)
         double best_bs = inf, best_da = inf;
         uint32_t code = 0;
         for (uint32_t tl = 0; tl < nt; ++tl) {
-            const double *row_tab = tab + tl * NENT;
             double v[NSEL];
 #pragma unroll
-            for (int k = 0; k < NSEL; ++k) v[k] = row_tab[off[k]];
+            for (int k = 0; k < NSEL; ++k) v[k] = tab[off[k] * LDS_ENT + tl];
             double bs = fmax(v[0] + v[2] + v[1], v[3] + v[2] + v[4]);   // Eq. (1), (2), (4)
             double da = v[5] + v[6] + v[7];                             // B*H * Eq. (7)
             bool lt = da < bound && (bs < best_bs || (bs == best_bs && da < best_da));
