@@ -590,6 +590,12 @@ struct SearchArgs {
     uint32_t n_cc, n_fc;
     uint32_t n_coarse_items;
     uint32_t n_items;
+    // k_search_dense: the (order, r, f) classes that denote dataflows (order + 24 * (r + 2 f)),
+    // and the split of its items: chunks [0, d_ncc) are handed out as groups of whole tasks
+    // (d_gc groups per chunk), the chunks after them as groups of fifths of tasks (d_gf per chunk)
+    const uint32_t *cls;
+    uint32_t n_cls;
+    uint32_t d_ncc, d_gc, d_gf;
     const double *btab;
     const double *ctab_s;
     ModelConst mc;
@@ -673,12 +679,12 @@ __device__ __forceinline__ uint32_t index_row_base(uint32_t dfrow)
 // LDS, two tilings per thread and turn (one 16-byte load, one paired LDS write).  PAIRS =
 // tiling pairs per item.  nt is rounded up to whole loop turns: beyond the last tiling the global
 // table repeats it up to its padded width (k_build_tilings), and a repeated tiling changes no minimum.
-template <int PAIRS>
+template <int PAIRS, int THREADS = SEARCH_THREADS>
 __device__ __forceinline__ void stage_tables(const SearchArgs &a, double *tab, uint32_t t0, uint32_t nt)
 {
     typedef double v2f64 __attribute__((ext_vector_type(2)));
     const uint32_t rows = (nt + TURN - 1) / TURN * TURN;
-    for (uint32_t i = threadIdx.x; i < NENT * PAIRS; i += SEARCH_THREADS) {
+    for (uint32_t i = threadIdx.x; i < NENT * PAIRS; i += THREADS) {
         const uint32_t ent = i / PAIRS, tl = (i % PAIRS) * 2;
         if (tl < rows) {
             const v2f64 two = *reinterpret_cast<const v2f64 *>(a.btab + (uint64_t)ent * a.mc.tpad + t0 + tl);
@@ -693,8 +699,8 @@ __device__ __forceinline__ void pin(double &x) { asm("" : "+v"(x)); }
 
 // Block and grid stages of the argmin: the waves' LDS slots -> one record per block -> ticket;
 // the last block to arrive reduces all records and writes the winner's cost and mapping.
-template <int MASK>
-__device__ __forceinline__ void finish_grid(const SearchArgs &a, Key (*wave_best)[SEARCH_THREADS / 64],
+template <int MASK, int THREADS = SEARCH_THREADS>
+__device__ __forceinline__ void finish_grid(const SearchArgs &a, Key (*wave_best)[THREADS / 64],
                                             uint32_t *is_last_flag)
 {
     const double inf = pos_inf();
@@ -705,7 +711,7 @@ __device__ __forceinline__ void finish_grid(const SearchArgs &a, Key (*wave_best
         for (int o = 0; o < N_OBJ; ++o) {
             if (!((MASK >> o) & 1)) continue;
             Key k = wave_best[o][0];
-            for (int wv = 1; wv < SEARCH_THREADS / 64; ++wv)
+            for (int wv = 1; wv < THREADS / 64; ++wv)
                 if (key_less(wave_best[o][wv], k)) k = wave_best[o][wv];
             Key *dst = a.partials + (uint64_t)blockIdx.x * N_OBJ + o;
             __hip_atomic_store(&dst->idx, k.idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -727,7 +733,7 @@ __device__ __forceinline__ void finish_grid(const SearchArgs &a, Key (*wave_best
     for (int o = 0; o < N_OBJ; ++o) {
         if (!((MASK >> o) & 1)) continue;
         Key k; k.p = inf; k.s = 0.0; k.idx = ~0ull;
-        for (uint32_t b = threadIdx.x; b < gridDim.x; b += SEARCH_THREADS) {
+        for (uint32_t b = threadIdx.x; b < gridDim.x; b += THREADS) {
             Key *src = a.partials + (uint64_t)b * N_OBJ + o;
             Key c;
             c.idx = __hip_atomic_load(&src->idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -744,7 +750,7 @@ __device__ __forceinline__ void finish_grid(const SearchArgs &a, Key (*wave_best
     if (threadIdx.x < N_OBJ && ((MASK >> threadIdx.x) & 1)) {
         const int o = threadIdx.x;
         Key k = wave_best[o][0];
-        for (int wv = 1; wv < SEARCH_THREADS / 64; ++wv)
+        for (int wv = 1; wv < THREADS / 64; ++wv)
             if (key_less(wave_best[o][wv], k)) k = wave_best[o][wv];
         FinalRecord *fr = a.final_out + o;
         fr->key = k;
@@ -1077,6 +1083,320 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
         }
     }
     finish_grid<MASK>(a, wave_best, &is_last);
+}
+
+// ---------------------------------------------------------------------------
+// Exhaustive search over the full row set.
+//
+// The rows of one (order, r, f) class are the 5^4 buffering levels, and the selectors split: those of
+// A and B (buffer, retained, DRAM) depend on (p_A, p_B) only, those of D and E on (p_D, p_E) only,
+// those of C on the class (k_build_rows).  So here a lane is a tiling, a wave takes the 125 rows of a
+// (class, p_E) task, all selectors are wave-uniform, and a row's three sums are formed from an
+// (A, B) part shared by five rows and a (D, E) part held in registers: 3 + 3/5 LDS reads and
+// 10 + 3/5 operations per (row, tiling) before the nine combinations, whose per-tiling constants
+// are lane registers for the whole task.  All of these sums are exact integers below 2^53 (the
+// host refuses a workload where they are not), so their association is free.
+//
+// A block stages one chunk of TC tilings, as k_search does, and its waves take neighbouring tasks.
+// Persistent blocks, global work counter and grid finish as in k_search; the last chunks are handed
+// out in fifths of tasks (one p_D each) to even out the end.  The host sends single-key passes
+// here: the 18 per-tiling constants, the (D, E) parts and one key's nine minima fit 128 registers
+// (four waves per SIMD), two keys' minima do not.
+constexpr int DENSE_THREADS = 512;           // eight waves, two blocks per CU
+constexpr int DENSE_BLOCKS_PER_CU = 2;
+constexpr int DENSE_WAVES = DENSE_THREADS / 64;
+
+template <int MASK, bool FAST, bool LIMIT = false, bool REGROUP = false>
+__global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
+{
+    __shared__ double tab[NENT * LDS_ENT];
+    __shared__ Key wave_best[N_OBJ][DENSE_WAVES];
+    __shared__ uint32_t is_last;
+    __shared__ uint32_t s_item;
+
+    constexpr bool LAZY = !(MASK & 4) && !LIMIT;
+    const double inf = pos_inf();
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (lane < N_OBJ) { wave_best[lane][wave].p = inf; wave_best[lane][wave].s = 0.0; wave_best[lane][wave].idx = ~0ull; }
+    double run_p[N_OBJ];
+    uint64_t run_idx[N_OBJ];
+#pragma unroll
+    for (int o = 0; o < N_OBJ; ++o) { run_p[o] = inf; run_idx[o] = ~0ull; }
+    // encoded rows through the constant address space: wave-uniform row numbers, scalar loads
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    struct EncTable {
+        ConstPtr<u32x4> p;
+        __device__ __forceinline__ uint4 operator[](uint32_t row) const
+        {
+            const u32x4 v = p[row];
+            return make_uint4(v.x, v.y, v.z, v.w);
+        }
+    };
+    const EncTable enc = {(ConstPtr<u32x4>)a.enc};
+    ConstPtr<uint32_t> cls_list = as_constant(a.cls);
+
+    uint32_t upcoming = blockIdx.x;
+    while (true) {
+        if (threadIdx.x == 0) s_item = upcoming;
+        __syncthreads();                          // also: the previous item's LDS readers are done
+        const uint32_t item = s_item;
+        if (item >= a.n_items) break;
+        if (threadIdx.x == 0)
+            upcoming = gridDim.x + __hip_atomic_fetch_add(a.work_counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool fine = item >= a.n_coarse_items;
+        uint32_t chunk, group;
+        if (!fine) { chunk = item / a.d_gc; group = item % a.d_gc; }
+        else { const uint32_t j = item - a.n_coarse_items; chunk = a.d_ncc + j / a.d_gf; group = j % a.d_gf; }
+        const uint32_t t0 = chunk * TC;
+        const uint32_t nt = min((uint32_t)TC, a.mc.T - t0);
+        stage_tables<TC / 2, DENSE_THREADS>(a, tab, t0, nt);
+        __syncthreads();
+
+        const uint32_t per_class = fine ? 25u : 5u;
+        const uint32_t task = group * DENSE_WAVES + wave;
+        if (task >= a.n_cls * per_class) continue;            // no barrier below: safe to leave early
+        const uint32_t cls = cls_list[task / per_class], part = task % per_class;
+        const uint32_t rank = cls % 24, g = cls / 24, r = g & 1;
+        const uint32_t pE = fine ? part / 5 : part, pd0 = fine ? part % 5 : 0u, npd = fine ? 1u : 5u;
+        const uint32_t row0 = 625u * rank + ROWS_PER_GROUP * g;         // (p_A, p_B, p_D, p_E) = 0
+        const uint32_t row_de0 = row0 + 25u * (pd0 + 5u * pE);          // first row of the task
+
+        // this lane's tiling: beyond the chunk, its last tiling once more, masked out by the capacity
+        const uint32_t tl = min(lane, nt - 1);
+        const double cap = lane < nt ? a.mc.cap_words : -1.0;
+        const double *cs = a.ctab_s + ((uint64_t)(t0 + tl) * 2 + r) * NCS;
+        double gb[9], latc[9];
+#pragma unroll
+        for (int c = 0; c < 9; ++c) { gb[c] = cs[c]; latc[c] = cs[9 + c]; }
+        const double e_rf_part = REGROUP ? 0.0 : cs[18], e_mac_part = REGROUP ? 0.0 : cs[19];
+        const double *col = tab + tl;                         // entry e of this tiling: col[e * LDS_ENT]
+
+        // the class row and the task's (D, E) rows: all requested before the first is used
+        const uint4 e_c = enc[row0];
+        uint4 e_de5[5];
+#pragma unroll
+        for (int q = 0; q < 5; ++q) e_de5[q] = enc[row_de0 + 25u * min((uint32_t)q, npd - 1)];
+        const double c_bs = col[sel_of(e_c, 2) * LDS_ENT], c_da = col[sel_of(e_c, 7) * LDS_ENT];
+
+        double bestE[9], bestL[9], bestLE_l[9], bestLE_e[9], bestP[9];
+        uint32_t codeE[9], codeL[9], codeLE[9], codeP[9];
+#pragma unroll
+        for (int c9 = 0; c9 < 9; ++c9) {
+            bestE[c9] = bestL[c9] = bestLE_l[c9] = bestLE_e[c9] = bestP[c9] = inf;
+            codeE[c9] = codeL[c9] = codeLE[c9] = codeP[c9] = 0;
+        }
+
+        // one row of this lane's tiling: Eq. (1), (2), (4), the capacity mask, B*H * Eq. (7), then
+        // the nine combinations.  code = the row's place in the task, in index order.
+        auto cost_row = [&](double bs1, double bs2, double dram_words, uint32_t code) {
+            bool ok = fmax(bs1, bs2) <= cap;
+            double e_part = (REGROUP ? a.mc.e_sum : a.mc.e_dram) * dram_words;
+            double l_dram;
+            if constexpr (FAST) l_dram = dram_words * a.mc.dram_k;
+            else l_dram = a.mc.dram_bw > 0.0 ? a.mc.c_lat * (((dram_words / a.mc.BH) * a.mc.word) / a.mc.dram_bw) : 0.0;
+            const double over = __hiloint2double(ok ? 0 : 0x7ff00000, 0);
+            e_part = fmax(e_part, over);
+            l_dram = fmax(l_dram, over);
+            pin(e_part);
+            pin(l_dram);
+#pragma unroll
+            for (int c9 = 0; c9 < 9; ++c9) {
+                double en;
+                if constexpr (REGROUP) {
+                    en = e_part + gb[c9];
+                } else {
+                    double gb_words = dram_words + gb[c9];
+                    en = e_part + a.mc.e_gb * gb_words;
+                    en = en + e_rf_part;
+                    en = en + e_mac_part;
+                }
+                double lat = fmax(l_dram, latc[c9]);
+                if constexpr (LIMIT) {
+                    bool out_of_range = !(en < a.e_limit);
+                    en = out_of_range ? inf : en;
+                    lat = out_of_range ? inf : lat;
+                }
+                if constexpr (LAZY) {
+                    if constexpr (MASK & 8) bestP[c9] = fmin(bestP[c9], en * lat);
+                    if constexpr (MASK & 1) bestE[c9] = fmin(bestE[c9], en);
+                    if constexpr (MASK & 2) bestL[c9] = fmin(bestL[c9], lat);
+                } else {
+                    if constexpr (MASK & 8) {
+                        double edp = en * lat;
+                        bool lt = edp < bestP[c9];
+                        bestP[c9] = fmin(bestP[c9], edp);
+                        codeP[c9] = lt ? code : codeP[c9];
+                    }
+                    if constexpr (MASK & 1) {
+                        bool lt = en < bestE[c9];
+                        bestE[c9] = fmin(bestE[c9], en);
+                        codeE[c9] = lt ? code : codeE[c9];
+                    }
+                    if constexpr (MASK & 2) {
+                        bool lt = lat < bestL[c9];
+                        bestL[c9] = fmin(bestL[c9], lat);
+                        codeL[c9] = lt ? code : codeL[c9];
+                    }
+                    if constexpr (MASK & 4) {
+                        bool lt = (lat < bestLE_l[c9]) | ((lat == bestLE_l[c9]) & (en < bestLE_e[c9]));
+                        bestLE_l[c9] = lt ? lat : bestLE_l[c9];
+                        bestLE_e[c9] = lt ? en : bestLE_e[c9];
+                        codeLE[c9] = lt ? code : codeLE[c9];
+                    }
+                }
+            }
+        };
+
+        if constexpr (LAZY) {
+            // (D, E) parts of the task's p_D values in registers; the (A, B) parts are read one step
+            // ahead of their use and their selectors one step ahead of that
+            double y_ret[5], y_bs[5], y_da[5];
+#pragma unroll
+            for (int q = 0; q < 5; ++q) {
+                // the class's C terms ride on the (D, E) parts
+                y_ret[q] = c_bs + col[sel_of(e_de5[q], 1) * LDS_ENT];
+                y_bs[q] = col[sel_of(e_de5[q], 3) * LDS_ENT] + c_bs;
+                y_da[q] = c_da + col[sel_of(e_de5[q], 6) * LDS_ENT];
+            }
+            double x_bs = col[sel_of(e_c, 0) * LDS_ENT], x_ret = col[sel_of(e_c, 4) * LDS_ENT],
+                   x_da = col[sel_of(e_c, 5) * LDS_ENT];                  // row0 is (p_A, p_B) = 0
+            uint4 e_ab = enc[row0 + 1];
+            for (uint32_t ab = 0; ab < 25; ++ab) {
+                const double now_bs = x_bs, now_ret = x_ret, now_da = x_da;
+                x_bs = col[sel_of(e_ab, 0) * LDS_ENT];
+                x_ret = col[sel_of(e_ab, 4) * LDS_ENT];
+                x_da = col[sel_of(e_ab, 5) * LDS_ENT];
+                e_ab = enc[row0 + min(ab + 2, 24u)];
+#pragma unroll
+                for (int q = 0; q < 5; ++q)
+                    if ((uint32_t)q < npd) cost_row(now_bs + y_ret[q], y_bs[q] + now_ret, now_da + y_da[q], 0);
+            }
+        } else {
+            // index order (p_D, then (p_A, p_B)): a strict < then keeps the lowest index on ties
+            for (uint32_t q = 0; q < npd; ++q) {
+                const uint4 e_de = enc[row_de0 + 25u * q];
+                const double y_ret = col[sel_of(e_de, 1) * LDS_ENT], y_bs = col[sel_of(e_de, 3) * LDS_ENT],
+                             y_da = col[sel_of(e_de, 6) * LDS_ENT];
+                for (uint32_t ab = 0; ab < 25; ++ab) {
+                    const uint4 e_ab = enc[row0 + ab];
+                    const double x_bs = col[sel_of(e_ab, 0) * LDS_ENT], x_ret = col[sel_of(e_ab, 4) * LDS_ENT],
+                                 x_da = col[sel_of(e_ab, 5) * LDS_ENT];
+                    cost_row((x_bs + c_bs) + y_ret, (y_bs + c_bs) + x_ret, (x_da + y_da) + c_da, q * 25u + ab);
+                }
+            }
+        }
+
+        // index row (Sec. VI-A numbering) of the task's row number `code`, combination 0
+        auto index_row_of = [&](uint32_t code) { return index_row_base(row_de0 + 25u * (code / 25u) + code % 25u); };
+
+        if constexpr (LAZY) {
+#pragma unroll
+            for (int o = 0; o < N_OBJ; ++o) {
+                if (!((MASK >> o) & 1)) continue;
+                const double *best = o == 0 ? bestE : (o == 1 ? bestL : bestP);
+                double mine_v = best[0];
+#pragma unroll
+                for (int c9 = 1; c9 < 9; ++c9) mine_v = fmin(mine_v, best[c9]);
+                const double wave_v = uniform_f64(wave_min_f64(mine_v));
+                if (!(wave_v <= run_p[o]) || !(wave_v < inf)) continue;  // the usual case: nothing new here
+                // the lowest combination in which some tiling reaches the minimum: its candidates
+                // precede those of every higher combination
+                uint32_t cstar = 9;
+#pragma unroll
+                for (int c9 = 8; c9 >= 0; --c9) cstar = best[c9] == wave_v ? (uint32_t)c9 : cstar;
+                const uint32_t c_u = __builtin_amdgcn_readfirstlane(wave_min_u32(cstar));
+                const uint32_t combo_rows = 30000u * (c_u % 3) + 90000u * (c_u / 3);
+                const uint64_t lowest_possible = (uint64_t)t0 + (uint64_t)a.mc.T * (index_row_of(0) + combo_rows);
+                if (!(wave_v < run_p[o] || lowest_possible < run_idx[o])) continue;
+                // Recover the row: go through the task's rows in index order and cost them again for
+                // combination c_u, with the very operations of the loop above; the first row in which
+                // a tiling reaches the minimum holds the lowest index, at its lowest such tiling.
+                double gb_u = gb[0], latc_u = latc[0];
+#pragma unroll
+                for (int c9 = 1; c9 < 9; ++c9) { gb_u = c_u == (uint32_t)c9 ? gb[c9] : gb_u; latc_u = c_u == (uint32_t)c9 ? latc[c9] : latc_u; }
+                for (uint32_t code = 0; code < npd * 25u; ++code) {
+                    const uint4 e_de = enc[row_de0 + 25u * (code / 25u)];
+                    const uint4 e_ab = enc[row0 + code % 25u];
+                    const double bs1 = (col[sel_of(e_ab, 0) * LDS_ENT] + c_bs) + col[sel_of(e_de, 1) * LDS_ENT];
+                    const double bs2 = col[sel_of(e_de, 3) * LDS_ENT] + (c_bs + col[sel_of(e_ab, 4) * LDS_ENT]);
+                    const double dram2 = (col[sel_of(e_ab, 5) * LDS_ENT] + c_da) + col[sel_of(e_de, 6) * LDS_ENT];
+                    const bool ok2 = fmax(bs1, bs2) <= cap;
+                    double e2 = (REGROUP ? a.mc.e_sum : a.mc.e_dram) * dram2;
+                    double l2;
+                    if constexpr (FAST) l2 = dram2 * a.mc.dram_k;
+                    else l2 = a.mc.dram_bw > 0.0 ? a.mc.c_lat * (((dram2 / a.mc.BH) * a.mc.word) / a.mc.dram_bw) : 0.0;
+                    const double over2 = __hiloint2double(ok2 ? 0 : 0x7ff00000, 0);
+                    e2 = fmax(e2, over2);
+                    l2 = fmax(l2, over2);
+                    pin(e2);
+                    pin(l2);
+                    double en2;
+                    if constexpr (REGROUP) {
+                        en2 = e2 + gb_u;
+                    } else {
+                        double gb2 = dram2 + gb_u;
+                        en2 = e2 + a.mc.e_gb * gb2;
+                        en2 = en2 + e_rf_part;
+                        en2 = en2 + e_mac_part;
+                    }
+                    const double lat2 = fmax(l2, latc_u);
+                    const double val2 = o == 0 ? en2 : (o == 1 ? lat2 : en2 * lat2);
+                    const unsigned long long hits = __ballot(val2 == wave_v);
+                    if (!hits) continue;
+                    const uint64_t idx = (uint64_t)t0 + ((uint32_t)__ffsll((long long)hits) - 1u) +
+                                         (uint64_t)a.mc.T * (index_row_of(code) + combo_rows);
+                    if (wave_v < run_p[o] || idx < run_idx[o]) { run_p[o] = wave_v; run_idx[o] = idx; }
+                    break;
+                }
+            }
+            continue;
+        }
+        // eager keys: fold the nine per-combination minima of this lane (ascending combination =
+        // ascending index), reduce over the wave, keep the wave's best
+        Key mine[N_OBJ];
+#pragma unroll
+        for (int o = 0; o < N_OBJ; ++o) { mine[o].p = inf; mine[o].s = 0.0; mine[o].idx = ~0ull; }
+#pragma unroll
+        for (int c9 = 0; c9 < 9; ++c9) {
+            const uint32_t combo_rows = 30000u * (c9 % 3) + 90000u * (c9 / 3);
+            auto idx_of = [&](uint32_t code) { return (uint64_t)(t0 + tl) + (uint64_t)a.mc.T * (index_row_of(code) + combo_rows); };
+            if constexpr (MASK & 1) {
+                if (bestE[c9] < mine[0].p) { mine[0].p = bestE[c9]; mine[0].idx = idx_of(codeE[c9]); }
+            }
+            if constexpr (MASK & 2) {
+                if (bestL[c9] < mine[1].p) { mine[1].p = bestL[c9]; mine[1].idx = idx_of(codeL[c9]); }
+            }
+            if constexpr (MASK & 4) {
+                if (bestLE_l[c9] < mine[2].p || (bestLE_l[c9] == mine[2].p && bestLE_e[c9] < mine[2].s)) {
+                    mine[2].p = bestLE_l[c9];
+                    mine[2].s = bestLE_e[c9];
+                    mine[2].idx = idx_of(codeLE[c9]);
+                }
+            }
+            if constexpr (MASK & 8) {
+                if (bestP[c9] < mine[3].p) { mine[3].p = bestP[c9]; mine[3].idx = idx_of(codeP[c9]); }
+            }
+        }
+#pragma unroll
+        for (int o = 0; o < N_OBJ; ++o) {
+            if (!((MASK >> o) & 1)) continue;
+            if (!(mine[o].p < inf)) { mine[o].s = 0.0; mine[o].idx = ~0ull; }
+            Key k = wave_min(mine[o]);
+            if (lane == 0 && key_less(k, wave_best[o][wave])) wave_best[o][wave] = k;
+        }
+    }
+
+    if constexpr (LAZY) {
+        if (lane == 0) {
+#pragma unroll
+            for (int o = 0; o < N_OBJ; ++o) {
+                if (!((MASK >> o) & 1)) continue;
+                wave_best[o][wave].p = run_p[o]; wave_best[o][wave].s = 0.0; wave_best[o][wave].idx = run_idx[o];
+            }
+        }
+    }
+    finish_grid<MASK, DENSE_THREADS>(a, wave_best, &is_last);
 }
 
 // One step of the buffer-size / DRAM-access front (Sec. VII-B): the (buffer size, DRAM access,

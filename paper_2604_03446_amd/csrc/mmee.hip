@@ -39,6 +39,8 @@ struct State {
     uint32_t *rows[2] = {nullptr, nullptr};     // [0] every row that denotes a dataflow, [1] survivors
     uint32_t *counts_dev = nullptr;
     uint32_t counts[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+    uint32_t *cls_dev = nullptr;                // (order, r, f) classes whose rows denote dataflows
+    uint32_t n_cls = 0;
     // online scratch, grown on demand
     double *btab = nullptr, *ctab_s = nullptr;
     uint64_t *ctab_e = nullptr;
@@ -198,6 +200,31 @@ int ensure_ready()
     HIP_TRY(hipMemcpyAsync(h, S.counts_dev, sizeof(h), hipMemcpyDeviceToHost, S.stream));
     HIP_TRY(hipStreamSynchronize(S.stream));
     for (int g = 0; g < 4; ++g) { S.counts[0][g] = h[g]; S.counts[1][g] = h[4 + g]; }
+    {
+        // whether a row denotes a dataflow depends on (order, r, f) only: list those classes
+        std::vector<uint8_t> flags(N_DFROWS);
+        HIP_TRY(hipMemcpy(flags.data(), S.flags, N_DFROWS, hipMemcpyDeviceToHost));
+        std::vector<uint32_t> cls;
+        for (uint32_t g = 0; g < N_GROUPS; ++g)
+            for (uint32_t rank = 0; rank < 24; ++rank) {
+                uint32_t on = 0;
+                for (uint32_t q = 0; q < 625; ++q) on += flags[g * ROWS_PER_GROUP + rank * 625 + q] & 1u;
+                if (on != 0 && on != 625) {
+                    std::snprintf(g_last_error, sizeof(g_last_error), "row validity is not uniform within a class");
+                    return MMEE_EDEVICE;
+                }
+                if (on) cls.push_back(rank + 24 * g);
+            }
+        uint64_t rows = 0;
+        for (int g = 0; g < 4; ++g) rows += S.counts[0][g];
+        if (cls.empty() || cls.size() * 625ull != rows) {
+            std::snprintf(g_last_error, sizeof(g_last_error), "class list does not match the row list");
+            return MMEE_EDEVICE;
+        }
+        HIP_TRY(hipMalloc(&S.cls_dev, sizeof(uint32_t) * 96));
+        HIP_TRY(hipMemcpy(S.cls_dev, cls.data(), sizeof(uint32_t) * cls.size(), hipMemcpyHostToDevice));
+        S.n_cls = (uint32_t)cls.size();
+    }
     S.ready = true;
     return MMEE_OK;
 }
@@ -280,6 +307,21 @@ void launch_search_limited(bool exact_k, dim3 grid, const SearchArgs &a)
     else hipLaunchKernelGGL((k_search<4, false, true>), grid, dim3(SEARCH_THREADS), 0, S.stream, a);
 }
 
+template <int MASK>
+void launch_dense_mask(bool exact_k, dim3 grid, const SearchArgs &a)
+{
+    if (a.mc.regroup) hipLaunchKernelGGL((k_search_dense<MASK, true, false, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
+    else if (exact_k) hipLaunchKernelGGL((k_search_dense<MASK, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
+    else hipLaunchKernelGGL((k_search_dense<MASK, false>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
+}
+
+void launch_dense_limited(bool exact_k, dim3 grid, const SearchArgs &a)
+{
+    if (a.mc.regroup) hipLaunchKernelGGL((k_search_dense<4, true, true, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
+    else if (exact_k) hipLaunchKernelGGL((k_search_dense<4, true, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
+    else hipLaunchKernelGGL((k_search_dense<4, false, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
+}
+
 // enqueue one pass (tables + search + readback of the final records) into slot `slot`
 int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_t *evaluated,
                    const double *e_limit = nullptr, bool build_tables = true, bool bs_da_step = false)
@@ -318,12 +360,31 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     }
     a.btab = S.btab; a.ctab_s = S.ctab_s; a.ctab_e = S.ctab_e;
     a.mc = mc;
-    const uint64_t n_items = (uint64_t)rb * ((uint64_t)a.n_cc + a.n_fc);
+    // One key over the full row set goes through the dense kernel (lane = tiling, wave = 125 rows of
+    // a class).  With several keys its accumulators no longer fit four waves per SIMD, and the
+    // row-per-lane kernel is the faster one.
+    const bool dense = which == 0 && !bs_da_step && (mask & (mask - 1)) == 0;
+    uint64_t n_items;
+    if (dense) {
+        a.cls = S.cls_dev; a.n_cls = S.n_cls;
+        const uint32_t n_chunks = (uint32_t)((p.T + TC - 1) / TC);
+        a.d_gc = (S.n_cls * 5 + DENSE_WAVES - 1) / DENSE_WAVES;
+        a.d_gf = (S.n_cls * 25 + DENSE_WAVES - 1) / DENSE_WAVES;
+        // fifths of tasks for the last chunks: about one whole-task item per resident block
+        const uint32_t dense_blocks = S.resident_blocks / BLOCKS_PER_CU * DENSE_BLOCKS_PER_CU;
+        const uint32_t fine_chunks = std::min<uint32_t>(n_chunks, (dense_blocks + a.d_gc - 1) / a.d_gc);
+        a.d_ncc = n_chunks - fine_chunks;
+        a.n_coarse_items = a.d_ncc * a.d_gc;
+        n_items = (uint64_t)a.n_coarse_items + (uint64_t)fine_chunks * a.d_gf;
+    } else {
+        n_items = (uint64_t)rb * ((uint64_t)a.n_cc + a.n_fc);
+        a.n_coarse_items = rb * a.n_cc;
+    }
     if (n_items == 0 || n_items > 0x7fffffffull) return MMEE_EINVAL;
-    a.n_coarse_items = rb * a.n_cc;
     a.n_items = (uint32_t)n_items;
     // persistent blocks: as many as the chip holds at once (LDS allows two per CU)
-    const uint64_t nblocks = std::min<uint64_t>(n_items, (uint64_t)S.resident_blocks);
+    const uint64_t nblocks = std::min<uint64_t>(
+        n_items, dense ? (uint64_t)S.resident_blocks / BLOCKS_PER_CU * DENSE_BLOCKS_PER_CU : (uint64_t)S.resident_blocks);
     rc = ensure_partials(nblocks);
     if (rc) return rc;
     a.partials = S.partials; a.ticket = S.ticket; a.work_counter = S.ticket + 1;
@@ -338,8 +399,17 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     } else if (e_limit) {
         if (mask != 4) return MMEE_EINVAL;
         a.e_limit = *e_limit;
-        launch_search_limited(p.exact_k, grid, a);
-    } else
+        if (dense) launch_dense_limited(p.exact_k, grid, a);
+        else launch_search_limited(p.exact_k, grid, a);
+    } else if (dense)
+    switch (mask) {
+    case 1: launch_dense_mask<1>(p.exact_k, grid, a); break;
+    case 2: launch_dense_mask<2>(p.exact_k, grid, a); break;
+    case 4: launch_dense_mask<4>(p.exact_k, grid, a); break;
+    case 8: launch_dense_mask<8>(p.exact_k, grid, a); break;
+    default: return MMEE_EINVAL;
+    }
+    else
     switch (mask) {
     case 1: launch_search_mask<1>(p.exact_k, grid, a); break;
     case 2: launch_search_mask<2>(p.exact_k, grid, a); break;
@@ -740,7 +810,7 @@ void mmee_shutdown(void)
 {
     std::lock_guard<std::mutex> guard(g_lock);
     if (S.ready || S.btab || S.partials) (void)hipStreamSynchronize(S.stream);
-    (void)hipFree(S.enc); (void)hipFree(S.sig); (void)hipFree(S.flags);
+    (void)hipFree(S.enc); (void)hipFree(S.sig); (void)hipFree(S.flags); (void)hipFree(S.cls_dev);
     (void)hipFree(S.rows[0]); (void)hipFree(S.rows[1]); (void)hipFree(S.counts_dev);
     (void)hipFree(S.btab); (void)hipFree(S.ctab_s); (void)hipFree(S.ctab_e);
     (void)hipFree(S.partials); (void)hipFree(S.ticket);
