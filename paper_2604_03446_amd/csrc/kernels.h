@@ -584,6 +584,7 @@ struct SearchArgs {
     uint32_t cls_off[2][2];      // [r][f] start of the group's list inside rows[]
     uint32_t cls_cnt[2][2];      // [r][f] rows in it
     uint32_t rb_split;           // row blocks of class r = 0; the rest belong to r = 1
+    uint32_t n_rb;               // row blocks in all
     // Tilings [0, n_cc * TC) are cut into chunks of TC, the rest into n_fc chunks of TC_FINE.  Items
     // [0, n_coarse_items) are the (row block, coarse chunk) pairs, the fine ones follow: the short
     // items are handed out last and even out the moment at which the persistent blocks run dry.
@@ -647,14 +648,16 @@ __device__ __forceinline__ ItemView locate_item(const SearchArgs &a, uint32_t it
     ItemView v;
     uint32_t rb;
     v.fine = item >= a.n_coarse_items;
+    // neighbouring items share their tilings: blocks that run side by side read the same table slice
+    // and the same per-tiling constants
     if (!v.fine) {
-        rb = item / a.n_cc;
-        v.t0 = (item % a.n_cc) * TC;
+        rb = item % a.n_rb;
+        v.t0 = (item / a.n_rb) * TC;
         v.nt = TC;
     } else {
         const uint32_t j = item - a.n_coarse_items;
-        rb = j / a.n_fc;
-        v.t0 = a.n_cc * TC + (j % a.n_fc) * TC_FINE;
+        rb = j % a.n_rb;
+        v.t0 = a.n_cc * TC + (j / a.n_rb) * TC_FINE;
         v.nt = min((uint32_t)TC_FINE, a.mc.T - v.t0);
     }
     v.r = rb >= a.rb_split;
@@ -683,16 +686,34 @@ template <int PAIRS, int THREADS = SEARCH_THREADS>
 __device__ __forceinline__ void stage_tables(const SearchArgs &a, double *tab, uint32_t t0, uint32_t nt)
 {
     typedef double v2f64 __attribute__((ext_vector_type(2)));
+    constexpr int TURNS = (NENT * PAIRS + THREADS - 1) / THREADS;
     const uint32_t rows = (nt + TURN - 1) / TURN * TURN;
-    for (uint32_t i = threadIdx.x; i < NENT * PAIRS; i += THREADS) {
+    // the addresses are worked out anew for every item: kept across items they would cost registers
+    uint32_t tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    // all loads first, then all LDS writes: one memory latency per item, not one per turn
+    v2f64 two[TURNS];
+#pragma unroll
+    for (int k = 0; k < TURNS; ++k) {
+        const uint32_t i = tid + k * THREADS;
         const uint32_t ent = i / PAIRS, tl = (i % PAIRS) * 2;
-        if (tl < rows) {
-            const v2f64 two = *reinterpret_cast<const v2f64 *>(a.btab + (uint64_t)ent * a.mc.tpad + t0 + tl);
-            tab[ent * LDS_ENT + tl] = two.x;
-            tab[ent * LDS_ENT + tl + 1] = two.y;
+        two[k] = v2f64{0.0, 0.0};
+        if (i < NENT * PAIRS && tl < rows)
+            two[k] = *reinterpret_cast<const v2f64 *>(a.btab + (uint64_t)ent * a.mc.tpad + t0 + tl);
+    }
+#pragma unroll
+    for (int k = 0; k < TURNS; ++k) {
+        const uint32_t i = tid + k * THREADS;
+        const uint32_t ent = i / PAIRS, tl = (i % PAIRS) * 2;
+        if (i < NENT * PAIRS && tl < rows) {
+            tab[ent * LDS_ENT + tl] = two[k].x;
+            tab[ent * LDS_ENT + tl + 1] = two[k].y;
         }
     }
 }
+
+// s_waitcnt lgkmcnt(0) with the other counters left alone (vmcnt 63, expcnt 7)
+__device__ __forceinline__ void wait_lds_and_scalar_loads() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
 // keeps the optimiser from sinking a select below the operations that consume its result
 __device__ __forceinline__ void pin(double &x) { asm("" : "+v"(x)); }
@@ -844,31 +865,40 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
             codeE[c9] = codeL[c9] = codeLE[c9] = codeP[c9] = 0;
         }
 
-        // Software pipeline: table values (LDS) and the per-tiling constants (scalar loads) of the
-        // next tilings are requested while the current ones are costed.  The constants come in two
-        // halves (combinations 0..4 / 5..8) so that each half is reloaded as soon as it is spent.
+        // Software pipeline in explicit stages.  LDS reads and scalar loads share one counter and
+        // scalar loads return out of order, so every wait drains both: requests are therefore issued
+        // right after a wait and met by the next one, most of a tiling's arithmetic later.
+        //   A  row part of both tilings of a pair (uses the table values read a pair ago)
+        //   B  request the next pair's table values and the second tiling's constants (set Y)
+        //   C  nine combinations of the first tiling (set X)          -> wait
+        //   D  request the next pair's first tiling's constants (set X)
+        //   E  nine combinations of the second tiling (set Y)         -> wait
+        // Four pairs per loop turn: a paired LDS read reaches every tiling of the turn from one
+        // address per selector through its immediate offsets, and the addresses move once a turn.
         ConstF64 cs_base = as_constant(a.ctab_s + ((uint64_t)t0 * 2 + r) * NCS);
-        // Tilings are taken in pairs, four pairs per loop turn.  A pair's table values come from
-        // one LDS address per selector: a paired read reaches every tiling of the turn through its
-        // immediate offsets, and the addresses move once a turn.
+        struct TilingConstants { double gb[9], lat[9], e_rf, e_mac; };
+        auto request = [&](TilingConstants &c, uint32_t tl) {
+            ConstF64 cs = cs_base + (uint64_t)(min(tl, nt - 1) * (2 * NCS));   // past the end: the last tiling again
+#pragma unroll
+            for (int q = 0; q < 9; ++q) { c.gb[q] = cs[q]; c.lat[q] = cs[9 + q]; }
+            if constexpr (!REGROUP) { c.e_rf = cs[18]; c.e_mac = cs[19]; }
+        };
         double v[2][NSEL];
         uint32_t sel_addr[NSEL];
 #pragma unroll
         for (int k = 0; k < NSEL; ++k) sel_addr[k] = lds_address(tab + off[k] * LDS_ENT);
 #pragma unroll
         for (int k = 0; k < NSEL; ++k) read_tilings(sel_addr[k], 0, v[0][k], v[1][k]);
-        double gbA[5], latA[5], gbB[4], latB[4], e_rf_part, e_mac_part;
-#pragma unroll
-        for (int c = 0; c < 5; ++c) { gbA[c] = cs_base[c]; latA[c] = cs_base[9 + c]; }
-#pragma unroll
-        for (int c = 0; c < 4; ++c) { gbB[c] = cs_base[5 + c]; latB[c] = cs_base[14 + c]; }
-        e_rf_part = cs_base[18]; e_mac_part = cs_base[19];
+        TilingConstants X, Y;
+        request(X, 0);
 
-        // nt rounded up to whole turns: the staged rows beyond nt repeat the last tiling
+        // nt rounded up to whole turns: the staged tilings beyond nt repeat the last one
         const uint32_t nt_turns = (nt + TURN - 1) / TURN * TURN;
         for (uint32_t tl8 = 0; tl8 < nt_turns; tl8 += TURN) {
 #pragma unroll
             for (int q = 0; q < TURN / 2; ++q) {
+                const uint32_t tl_pair = tl8 + 2 * q;
+                // ---- A
                 double dram_words[2], e_dram_part[2], l_dram[2];
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
@@ -889,8 +919,9 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
                     pin(e_dram_part[u]);
                     pin(l_dram[u]);
                 }
-                // request the next pair's rows; at the end of a turn the addresses move on, except
-                // on the last turn, which reads its last pair again
+                __builtin_amdgcn_sched_barrier(0);
+                // ---- B: at the end of a turn the addresses move on, except on the last turn, which
+                // reads its last pair again
                 if (q < TURN / 2 - 1) {
 #pragma unroll
                     for (int k = 0; k < NSEL; ++k) read_tilings(sel_addr[k], 2 * (q + 1), v[0][k], v[1][k]);
@@ -901,25 +932,24 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
 #pragma unroll
                     for (int k = 0; k < NSEL; ++k) read_tilings(sel_addr[k], 0, v[0][k], v[1][k]);
                 }
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const uint32_t tl = tl8 + 2 * q + u;
-                    // the next tiling's constants; past the end, the last tiling's once more
-                    ConstF64 cs_next = cs_base + (uint64_t)(min(tl + 1, nt - 1) * (2 * NCS));
-                    const double e_rf_now = e_rf_part, e_mac_now = e_mac_part;
-                    const double dw = dram_words[u], edp_ = e_dram_part[u], ld = l_dram[u];
+                request(Y, tl_pair + 1);
+                __builtin_amdgcn_sched_barrier(0);
 
-                    auto cost_one = [&](int c9, double gb_part, double lat_part) {
+                auto combinations = [&](const TilingConstants &c, int u) {
+                    const uint32_t tl = tl_pair + u;
+                    const double dw = dram_words[u], edp_ = e_dram_part[u], ld = l_dram[u];
+#pragma unroll
+                    for (int c9 = 0; c9 < 9; ++c9) {
                         double en;
                         if constexpr (REGROUP) {
-                            en = edp_ + gb_part;                  // row part + tiling part, both exact
+                            en = edp_ + c.gb[c9];                 // row part + tiling part, both exact
                         } else {
-                            double gb_words = dw + gb_part;
+                            double gb_words = dw + c.gb[c9];
                             en = edp_ + a.mc.e_gb * gb_words;
-                            en = en + e_rf_now;
-                            en = en + e_mac_now;
+                            en = en + c.e_rf;
+                            en = en + c.e_mac;
                         }
-                        double lat = fmax(ld, lat_part);
+                        double lat = fmax(ld, c.lat[c9]);
                         if constexpr (LIMIT) {
                             bool out_of_range = !(en < a.e_limit);
                             en = out_of_range ? inf : en;
@@ -929,7 +959,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
                             if constexpr (MASK & 8) bestP[c9] = fmin(bestP[c9], en * lat);
                             if constexpr (MASK & 1) bestE[c9] = fmin(bestE[c9], en);
                             if constexpr (MASK & 2) bestL[c9] = fmin(bestL[c9], lat);
-                            return;
+                            continue;
                         }
                         if constexpr (MASK & 8) {
                             double edp = en * lat;
@@ -953,17 +983,21 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
                             bestLE_e[c9] = lt ? en : bestLE_e[c9];
                             codeLE[c9] = lt ? tl : codeLE[c9];
                         }
-                    };
-#pragma unroll
-                    for (int c = 0; c < 5; ++c) cost_one(c, gbA[c], latA[c]);
-#pragma unroll
-                    for (int c = 0; c < 5; ++c) { gbA[c] = cs_next[c]; latA[c] = cs_next[9 + c]; }
-                    e_rf_part = cs_next[18]; e_mac_part = cs_next[19];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) cost_one(5 + c, gbB[c], latB[c]);
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) { gbB[c] = cs_next[5 + c]; latB[c] = cs_next[14 + c]; }
-                }
+                    }
+                };
+                // ---- C
+                combinations(X, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                wait_lds_and_scalar_loads();
+                __builtin_amdgcn_sched_barrier(0);
+                // ---- D
+                request(X, tl_pair + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                // ---- E
+                combinations(Y, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                wait_lds_and_scalar_loads();
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
 

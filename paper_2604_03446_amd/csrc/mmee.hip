@@ -350,6 +350,7 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
         nrows += in_class;
     }
     if (rb == 0) return MMEE_EINVAL;
+    a.n_rb = rb;
     // tilings: chunks of TC, then chunks of TC_FINE worth about four fine items per resident block
     // (a coarse item's time), at least the ragged end
     {
