@@ -310,13 +310,16 @@ __device__ __forceinline__ void tile_cost(uint32_t m, uint32_t r, uint32_t n, in
     cycles = row_folds * cdiv(cols_dim, C) * time_dim;
 }
 
-// One thread per tiling: decode the four tiling digits, derive the boundary vector and
-// store every subset product a row may select (entry-major, coalesced in the tiling).  The grid
-// covers the padded width mc.tpad.
-__global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__ btab, double *__restrict__ ctab_s,
-                                uint64_t *__restrict__ ctab_e, DivTable *__restrict__ dv_copy)
+// Five threads per tiling (one wave per share of the entries, 64 tilings per block): decode the four
+// tiling digits, derive the boundary vector and store the subset products a row may select
+// (entry-major, coalesced in the tiling).  The grid covers the padded width mc.tpad.
+constexpr int BUILD_PARTS = 5;
+__global__ __launch_bounds__(64 * BUILD_PARTS) void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__ btab,
+                                                                    double *__restrict__ ctab_s, uint64_t *__restrict__ ctab_e,
+                                                                    DivTable *__restrict__ dv_copy)
 {
-    uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t t = blockIdx.x * 64 + (threadIdx.x & 63);
+    const uint32_t part = threadIdx.x >> 6;
     // leave the divisor lists in device memory for the search's final record (index -> mapping)
     if (dv_copy && blockIdx.x == 0) {
         const uint32_t *src = reinterpret_cast<const uint32_t *>(&dv);
@@ -325,7 +328,7 @@ __global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__
     }
     if (t >= mc.tpad) return;
     // the columns between the last tiling and the padded width repeat the last tiling (the search
-    // stages tilings in pairs)
+    // takes tilings in groups)
     const bool padding = t >= mc.T;
     uint64_t G[4], D[4];
     uint32_t x = padding ? mc.T - 1 : t;
@@ -337,59 +340,69 @@ __global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__
     }
     const uint64_t tp = mc.tpad;
     const uint64_t BH = (uint64_t)mc.BH;
-    const int own[5][2] = {{DI, DK}, {DK, DL}, {DI, DL}, {DL, DJ}, {DI, DJ}};
-    uint64_t bs[5][5];                                       // option 4 = absent
-    for (int X = 0; X < 5; ++X) {
-        uint64_t tile = G[own[X][0]] * G[own[X][1]];
-        uint64_t d0 = D[own[X][0]], d1 = D[own[X][1]];
-        bs[X][0] = tile; bs[X][1] = tile * d0; bs[X][2] = tile * d1; bs[X][3] = tile * d0 * d1;
-        bs[X][4] = 0;
-    }
-    const int da_own[4][2] = {{DI, DK}, {DK, DL}, {DL, DJ}, {DI, DJ}};
-    const int da_other[4][2] = {{DL, DJ}, {DI, DJ}, {DI, DK}, {DK, DL}};
-    uint64_t da[4][4];
-    for (int y = 0; y < 4; ++y) {
-        uint64_t whole = (uint64_t)dv.X[da_own[y][0]] * dv.X[da_own[y][1]];
-        uint64_t n0 = D[da_other[y][0]], n1 = D[da_other[y][1]];
-        da[y][0] = whole; da[y][1] = whole * n0; da[y][2] = whole * n1; da[y][3] = whole * n0 * n1;
-    }
-    for (int b = 0; b < 4; ++b)
-        for (int a = 0; a < 4; ++a) {
-            btab[(ENT_BS_AB + a + 4 * b) * tp + t] = (double)(bs[OA][a] + bs[OB][b]);
-            btab[(ENT_BS_DE + a + 4 * b) * tp + t] = (double)(bs[OD][a] + bs[OE][b]);
-            btab[(ENT_DA_AB + a + 4 * b) * tp + t] = (double)(BH * (da[0][a] + da[1][b]));
-            btab[(ENT_DA_DE + a + 4 * b) * tp + t] = (double)(BH * (da[2][a] + da[3][b]));
-            btab[(ENT_DA_AB + ENT_RAW_DA + a + 4 * b) * tp + t] = (double)(da[0][a] + da[1][b]);
-            btab[(ENT_DA_DE + ENT_RAW_DA + a + 4 * b) * tp + t] = (double)(da[2][a] + da[3][b]);
+    if (part == 0 || part == 2) {
+        const int own[5][2] = {{DI, DK}, {DK, DL}, {DI, DL}, {DL, DJ}, {DI, DJ}};
+        uint64_t bs[5][5];                                       // option 4 = absent
+        for (int X = 0; X < 5; ++X) {
+            uint64_t tile = G[own[X][0]] * G[own[X][1]];
+            uint64_t d0 = D[own[X][0]], d1 = D[own[X][1]];
+            bs[X][0] = tile; bs[X][1] = tile * d0; bs[X][2] = tile * d1; bs[X][3] = tile * d0 * d1;
+            bs[X][4] = 0;
         }
-    for (int b = 0; b < 5; ++b)
-        for (int a = 0; a < 5; ++a) {
-            btab[(ENT_RET_DE + a + 5 * b) * tp + t] = (double)(bs[OD][a] + bs[OE][b]);
-            btab[(ENT_RET_AB + a + 5 * b) * tp + t] = (double)(bs[OA][a] + bs[OB][b]);
+        if (part == 0) {
+            for (int b = 0; b < 4; ++b)
+                for (int a = 0; a < 4; ++a) {
+                    btab[(ENT_BS_AB + a + 4 * b) * tp + t] = (double)(bs[OA][a] + bs[OB][b]);
+                    btab[(ENT_BS_DE + a + 4 * b) * tp + t] = (double)(bs[OD][a] + bs[OE][b]);
+                }
+            for (int c = 0; c < 4; ++c) btab[(ENT_BS_C + c) * tp + t] = (double)bs[OC][c];
+            // unfused C: spilled by Op1, fetched by Op2, plus one softmax pass over S and P
+            uint64_t whole = (uint64_t)dv.X[DI] * dv.X[DL];
+            for (uint32_t c = 0; c < 4; ++c) {
+                uint64_t spill = (c & 1) ? D[DK] : 1, fetch = (c & 2) ? D[DJ] : 1;
+                btab[(ENT_DA_C + c) * tp + t] = (double)(BH * whole * (spill + fetch + 2));
+                btab[(ENT_DA_C + ENT_RAW_DA + c) * tp + t] = (double)(whole * (spill + fetch + 2));
+            }
+            btab[(ENT_DA_C + 4) * tp + t] = 0.0;
+            btab[(ENT_DA_C + ENT_RAW_DA + 4) * tp + t] = 0.0;
+        } else {
+            for (int b = 0; b < 5; ++b)
+                for (int a = 0; a < 5; ++a) {
+                    btab[(ENT_RET_DE + a + 5 * b) * tp + t] = (double)(bs[OD][a] + bs[OE][b]);
+                    btab[(ENT_RET_AB + a + 5 * b) * tp + t] = (double)(bs[OA][a] + bs[OB][b]);
+                }
         }
-    for (int c = 0; c < 4; ++c) btab[(ENT_BS_C + c) * tp + t] = (double)bs[OC][c];
-    {
-        // unfused C: spilled by Op1, fetched by Op2, plus one softmax pass over S and P
-        uint64_t whole = (uint64_t)dv.X[DI] * dv.X[DL];
-        for (uint32_t c = 0; c < 4; ++c) {
-            uint64_t spill = (c & 1) ? D[DK] : 1, fetch = (c & 2) ? D[DJ] : 1;
-            btab[(ENT_DA_C + c) * tp + t] = (double)(BH * whole * (spill + fetch + 2));
-            btab[(ENT_DA_C + ENT_RAW_DA + c) * tp + t] = (double)(whole * (spill + fetch + 2));
-        }
-        btab[(ENT_DA_C + 4) * tp + t] = 0.0;
-        btab[(ENT_DA_C + ENT_RAW_DA + 4) * tp + t] = 0.0;
+        return;
     }
-
+    if (part == 1) {
+        const int da_own[4][2] = {{DI, DK}, {DK, DL}, {DL, DJ}, {DI, DJ}};
+        const int da_other[4][2] = {{DL, DJ}, {DI, DJ}, {DI, DK}, {DK, DL}};
+        uint64_t da[4][4];
+        for (int y = 0; y < 4; ++y) {
+            uint64_t whole = (uint64_t)dv.X[da_own[y][0]] * dv.X[da_own[y][1]];
+            uint64_t n0 = D[da_other[y][0]], n1 = D[da_other[y][1]];
+            da[y][0] = whole; da[y][1] = whole * n0; da[y][2] = whole * n1; da[y][3] = whole * n0 * n1;
+        }
+        for (int b = 0; b < 4; ++b)
+            for (int a = 0; a < 4; ++a) {
+                btab[(ENT_DA_AB + a + 4 * b) * tp + t] = (double)(BH * (da[0][a] + da[1][b]));
+                btab[(ENT_DA_DE + a + 4 * b) * tp + t] = (double)(BH * (da[2][a] + da[3][b]));
+                btab[(ENT_DA_AB + ENT_RAW_DA + a + 4 * b) * tp + t] = (double)(da[0][a] + da[1][b]);
+                btab[(ENT_DA_DE + ENT_RAW_DA + a + 4 * b) * tp + t] = (double)(da[2][a] + da[3][b]);
+            }
+        return;
+    }
     if (padding) return;
 
-    // stationary-mode dependent part: buffer<->RF words and cycles per tile stage
+    // parts 3 and 4 (r = 0 / 1), stationary-mode dependent: buffer<->RF words and cycles per tile stage
     uint64_t br1[3], cy1[3], br2[3], cy2[3];
     for (int s = 0; s < 3; ++s) {
         tile_cost((uint32_t)G[DI], (uint32_t)G[DK], (uint32_t)G[DL], s, mc.pe_rows, mc.pe_cols, mc.g_words, br1[s], cy1[s]);
         tile_cost((uint32_t)G[DI], (uint32_t)G[DL], (uint32_t)G[DJ], s, mc.pe_rows, mc.pe_cols, mc.g_words, br2[s], cy2[s]);
     }
     const uint64_t I = dv.X[DI], K = dv.X[DK], L = dv.X[DL], J = dv.X[DJ];
-    for (uint32_t r = 0; r < 2; ++r) {
+    {
+        const uint32_t r = part - 3;
         uint64_t rho = r ? D[DJ] : 1;                         // producer repeated per j tile (Sec. V-D)
         uint64_t st1 = rho * D[DI] * D[DK] * D[DL], st2 = D[DI] * D[DL] * D[DJ];
         uint64_t mac = rho * I * K * L + I * L * J;
@@ -404,11 +417,12 @@ __global__ void k_build_tilings(DivTable dv, ModelConst mc, double *__restrict__
             uint64_t br = st1 * br1[s1] + st2 * br2[s2];
             uint64_t cyc = st1 * cy1[s1] + st2 * cy2[s2];
             double t_gb = mc.gb_bw > 0.0 ? (double)(br * (uint64_t)mc.word) / mc.gb_bw : 0.0;
+            const double c_lat_part = mc.c_lat * fmax((double)cyc, t_gb);
             cs[c9] = mc.regroup ? (mc.e_gb * (double)(BH * br) + e_rf_part) + e_mac_part : (double)(BH * br);
-            cs[9 + c9] = mc.c_lat * fmax((double)cyc, t_gb);
+            cs[9 + c9] = c_lat_part;
             ctab_e[((uint64_t)r * NCE + c9) * tp + t] = br;
             ctab_e[((uint64_t)r * NCE + 9 + c9) * tp + t] = cyc;
-            ctab_e[((uint64_t)r * NCE + 20 + c9) * tp + t] = (uint64_t)__double_as_longlong(cs[9 + c9]);
+            ctab_e[((uint64_t)r * NCE + 20 + c9) * tp + t] = (uint64_t)__double_as_longlong(c_lat_part);
         }
         ctab_e[((uint64_t)r * NCE + 18) * tp + t] = mac;
         ctab_e[((uint64_t)r * NCE + 19) * tp + t] = sm;

@@ -48,7 +48,8 @@ struct State {
     Key *partials = nullptr;
     size_t partials_cap = 0;
     uint32_t *ticket = nullptr;
-    FinalRecord *final_dev = nullptr, *final_host = nullptr;
+    // result records: pinned host memory that the search's last block writes directly
+    FinalRecord *final_host = nullptr, *final_map = nullptr;     // host address / device address
     DivTable *dv_dev = nullptr;
     size_t slots = 0;
     std::vector<hipEvent_t> events;
@@ -254,15 +255,15 @@ int ensure_partials(size_t nblocks)
 int ensure_slots(size_t n)
 {
     if (n <= S.slots) return MMEE_OK;
-    if (S.final_dev) {
+    if (S.final_host) {
         HIP_TRY(hipStreamSynchronize(S.stream));
-        (void)hipFree(S.final_dev); (void)hipFree(S.dv_dev);
+        (void)hipFree(S.dv_dev);
         (void)hipHostFree(S.final_host);
     }
-    S.slots = 0;
-    HIP_TRY(hipMalloc(&S.final_dev, sizeof(FinalRecord) * N_OBJ * n));
+    S.slots = 0; S.final_host = nullptr; S.final_map = nullptr; S.dv_dev = nullptr;
     HIP_TRY(hipMalloc(&S.dv_dev, sizeof(DivTable) * n));
-    HIP_TRY(hipHostMalloc(&S.final_host, sizeof(FinalRecord) * N_OBJ * n));
+    HIP_TRY(hipHostMalloc(&S.final_host, sizeof(FinalRecord) * N_OBJ * n, hipHostMallocMapped));
+    HIP_TRY(hipHostGetDevicePointer(reinterpret_cast<void **>(&S.final_map), S.final_host, 0));
     while (S.events.size() < 2 * n) {
         hipEvent_t e;
         HIP_TRY(hipEventCreate(&e));
@@ -285,7 +286,7 @@ int launch_tilings(const Plan &p, const ModelConst &mc, DivTable *dv_copy = null
 {
     int rc = ensure_tilings(mc.tpad);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_build_tilings, dim3(mc.tpad / 64), dim3(64), 0, S.stream, p.dv, mc, S.btab,
+    hipLaunchKernelGGL(k_build_tilings, dim3(mc.tpad / 64), dim3(64 * BUILD_PARTS), 0, S.stream, p.dv, mc, S.btab,
                        S.ctab_s, S.ctab_e, dv_copy);
     HIP_TRY(hipGetLastError());
     return MMEE_OK;
@@ -389,7 +390,7 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     rc = ensure_partials(nblocks);
     if (rc) return rc;
     a.partials = S.partials; a.ticket = S.ticket; a.work_counter = S.ticket + 1;
-    a.final_out = S.final_dev + N_OBJ * slot;
+    a.final_out = S.final_map + N_OBJ * slot;
     a.dv = S.dv_dev + slot;
     HIP_TRY(hipEventRecord(S.events[2 * slot], S.stream));
     dim3 grid((uint32_t)nblocks);
@@ -431,8 +432,6 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     }
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(S.events[2 * slot + 1], S.stream));
-    HIP_TRY(hipMemcpyAsync(S.final_host + N_OBJ * slot, S.final_dev + N_OBJ * slot, sizeof(FinalRecord) * N_OBJ,
-                           hipMemcpyDeviceToHost, S.stream));
     *evaluated = nrows * p.T * (bs_da_step ? 1ull : 9ull);
     return MMEE_OK;
 }
@@ -815,7 +814,7 @@ void mmee_shutdown(void)
     (void)hipFree(S.rows[0]); (void)hipFree(S.rows[1]); (void)hipFree(S.counts_dev);
     (void)hipFree(S.btab); (void)hipFree(S.ctab_s); (void)hipFree(S.ctab_e);
     (void)hipFree(S.partials); (void)hipFree(S.ticket);
-    (void)hipFree(S.final_dev); (void)hipFree(S.dv_dev); (void)hipFree(S.eval_dev);
+    (void)hipFree(S.dv_dev); (void)hipFree(S.eval_dev);
     if (S.final_host) (void)hipHostFree(S.final_host);
     for (hipEvent_t e : S.events) (void)hipEventDestroy(e);
     hipStream_t keep = S.stream;
