@@ -260,13 +260,15 @@ __global__ void k_prune_rows(const uint32_t *__restrict__ sig, uint8_t *flags)
 
 // Stable compaction of the rows whose flag bit `which` is set: wave ballot for the position
 // inside the wave, LDS prefix over the waves of the block.  One block per (list, group).
-__global__ void k_compact_rows(const uint8_t *__restrict__ flags, uint32_t *rows_valid, uint32_t *rows_kept,
-                               uint32_t *counts)
+__global__ void k_compact_rows(const uint8_t *__restrict__ flags, const uint4 *__restrict__ enc, uint32_t *rows_valid,
+                               uint32_t *rows_kept, uint4 *enc_valid, uint4 *enc_kept, uint32_t *counts)
 {
     __shared__ uint32_t wave_cnt[16];
     __shared__ uint32_t running;
     const uint32_t g = blockIdx.x & 3, which = blockIdx.x >> 2;
     uint32_t *out = (which ? rows_kept : rows_valid) + g * ROWS_PER_GROUP;
+    // the encoded rows in list order, row number in the spare word: one load per lane and item
+    uint4 *out_enc = (which ? enc_kept : enc_valid) + g * ROWS_PER_GROUP;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     if (threadIdx.x == 0) running = 0;
     __syncthreads();
@@ -279,7 +281,13 @@ __global__ void k_compact_rows(const uint8_t *__restrict__ flags, uint32_t *rows
         __syncthreads();
         uint32_t base = running;
         for (uint32_t wv = 0; wv < wave; ++wv) base += wave_cnt[wv];
-        if (on) out[base + before] = g * ROWS_PER_GROUP + row;
+        if (on) {
+            const uint32_t dfrow = g * ROWS_PER_GROUP + row;
+            uint4 e = enc[dfrow];
+            e.w = dfrow;
+            out[base + before] = dfrow;
+            out_enc[base + before] = e;
+        }
         __syncthreads();
         if (threadIdx.x == 0) {
             uint32_t tot = 0;
@@ -593,6 +601,7 @@ __global__ __launch_bounds__(256) void k_eval_batch(EvalArgs a, uint64_t first_i
 struct SearchArgs {
     const uint4 *enc;            // encoded rows
     const uint32_t *rows;        // compacted row ids, one list per (r, f) group
+    const uint4 *row_enc;        // their encoded rows in the same order, row id in .w
     // Rows are handed out per recomputation class r: the lists of (r, f=0) and (r, f=1) follow each
     // other in one slot numbering, so that a row block may hold rows of both.
     uint32_t cls_off[2][2];      // [r][f] start of the group's list inside rows[]
@@ -654,6 +663,7 @@ __device__ __forceinline__ void read_tilings(uint32_t &addr, int tl, double &fir
 struct ItemView {
     uint32_t r, t0, nt;
     uint32_t dfrow;
+    uint4 e;                     // the row's selectors
     bool live, fine;
 };
 
@@ -680,7 +690,8 @@ __device__ __forceinline__ ItemView locate_item(const SearchArgs &a, uint32_t it
     v.live = slot < n0 + n1;
     const uint32_t where = !v.live ? a.cls_off[v.r][n0 ? 0 : 1]
                                    : (slot < n0 ? a.cls_off[v.r][0] + slot : a.cls_off[v.r][1] + (slot - n0));
-    v.dfrow = a.rows[where];
+    v.e = a.row_enc[where];
+    v.dfrow = v.e.w;
     return v;
 }
 
@@ -859,7 +870,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
         const ItemView it = locate_item(a, item);
         const bool live = it.live;
         const uint32_t dfrow = it.dfrow;
-        const uint4 e = a.enc[dfrow];
+        const uint4 e = it.e;
         const uint32_t r = it.r, t0 = it.t0, nt = it.nt;
         if (it.fine) stage_tables<TC_FINE / 2>(a, tab, t0, nt);
         else stage_tables<TC / 2>(a, tab, t0, nt);
@@ -1474,7 +1485,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 4) void k_front_step(SearchArgs a)
         const ItemView it = locate_item(a, item);
         const bool live = it.live;
         const uint32_t dfrow = it.dfrow;
-        const uint4 e = a.enc[dfrow];
+        const uint4 e = it.e;
         const uint32_t t0 = it.t0, nt = it.nt;
         if (it.fine) stage_tables<TC_FINE / 2>(a, tab, t0, nt);
         else stage_tables<TC / 2>(a, tab, t0, nt);

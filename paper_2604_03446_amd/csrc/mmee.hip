@@ -37,6 +37,7 @@ struct State {
     uint32_t *sig = nullptr;
     uint8_t *flags = nullptr;
     uint32_t *rows[2] = {nullptr, nullptr};     // [0] every row that denotes a dataflow, [1] survivors
+    uint4 *row_enc[2] = {nullptr, nullptr};     // the encoded rows in list order
     uint32_t *counts_dev = nullptr;
     uint32_t counts[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
     uint32_t *cls_dev = nullptr;                // (order, r, f) classes whose rows denote dataflows
@@ -190,11 +191,16 @@ int ensure_ready()
     HIP_TRY(hipMemset(S.ticket, 0, 2 * sizeof(uint32_t)));
     HIP_TRY(hipMemset(S.rows[0], 0, sizeof(uint32_t) * N_DFROWS));
     HIP_TRY(hipMemset(S.rows[1], 0, sizeof(uint32_t) * N_DFROWS));
+    for (int w = 0; w < 2; ++w) {
+        HIP_TRY(hipMalloc(&S.row_enc[w], sizeof(uint4) * N_DFROWS));
+        HIP_TRY(hipMemset(S.row_enc[w], 0, sizeof(uint4) * N_DFROWS));
+    }
     // offline stage: encode every (order, levels, r, f) row, prune, compact
     hipLaunchKernelGGL(k_build_rows, dim3((N_DFROWS + 255) / 256), dim3(256), 0, S.stream, S.enc, S.sig);
     hipLaunchKernelGGL(k_prune_rows, dim3((ROWS_PER_GROUP + 255) / 256, N_GROUPS), dim3(256), 0, S.stream, S.sig,
                        S.flags);
-    hipLaunchKernelGGL(k_compact_rows, dim3(8), dim3(1024), 0, S.stream, S.flags, S.rows[0], S.rows[1],
+    hipLaunchKernelGGL(k_compact_rows, dim3(8), dim3(1024), 0, S.stream, S.flags, S.enc, S.rows[0], S.rows[1],
+                       S.row_enc[0], S.row_enc[1],
                        S.counts_dev);
     HIP_TRY(hipGetLastError());
     uint32_t h[8];
@@ -334,7 +340,7 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     const int which = (flags & MMEE_SEARCH_EXHAUSTIVE) ? 0 : 1;
     SearchArgs a;
     std::memset(&a, 0, sizeof(a));
-    a.enc = S.enc; a.rows = S.rows[which];
+    a.enc = S.enc; a.rows = S.rows[which]; a.row_enc = S.row_enc[which];
     // rows: one slot numbering per recomputation class r, over the lists of (r, f=0) and (r, f=1)
     uint32_t rb = 0;
     uint64_t nrows = 0;
@@ -812,6 +818,7 @@ void mmee_shutdown(void)
     if (S.ready || S.btab || S.partials) (void)hipStreamSynchronize(S.stream);
     (void)hipFree(S.enc); (void)hipFree(S.sig); (void)hipFree(S.flags); (void)hipFree(S.cls_dev);
     (void)hipFree(S.rows[0]); (void)hipFree(S.rows[1]); (void)hipFree(S.counts_dev);
+    (void)hipFree(S.row_enc[0]); (void)hipFree(S.row_enc[1]);
     (void)hipFree(S.btab); (void)hipFree(S.ctab_s); (void)hipFree(S.ctab_e);
     (void)hipFree(S.partials); (void)hipFree(S.ticket);
     (void)hipFree(S.dv_dev); (void)hipFree(S.eval_dev);
