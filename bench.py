@@ -62,8 +62,8 @@ def main():
                     help="run the timed steps only (for rocprofv3): no oracle, no extra legs")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU; --gpus %d is not supported "
-                 "(the index space would shard trivially, see DESIGN.md)" % args.gpus)
+        sys.exit("bench.py: the library runs on one GPU; --gpus %d is not supported "
+                 "(the index space would shard by contiguous index ranges, one final min)" % args.gpus)
 
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"

@@ -1035,8 +1035,8 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
                 double mine_v = best[0];
 #pragma unroll
                 for (int c9 = 1; c9 < 9; ++c9) mine_v = fmin(mine_v, best[c9]);
+                if (!__ballot(mine_v <= run_p[o])) continue;         // the usual case: no lane reaches the running best
                 const double wave_v = uniform_f64(wave_min_f64(mine_v));
-                if (!(wave_v <= run_p[o])) continue;                 // the usual case: nothing new here
                 // the lowest combination reaching this lane's minimum (lowest index on ties)
                 uint32_t cstar = 8;
 #pragma unroll
@@ -1357,8 +1357,8 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
                 double mine_v = best[0];
 #pragma unroll
                 for (int c9 = 1; c9 < 9; ++c9) mine_v = fmin(mine_v, best[c9]);
+                if (!__ballot(mine_v <= run_p[o] && mine_v < inf)) continue;   // the usual case: nothing new here
                 const double wave_v = uniform_f64(wave_min_f64(mine_v));
-                if (!(wave_v <= run_p[o]) || !(wave_v < inf)) continue;  // the usual case: nothing new here
                 // the lowest combination in which some tiling reaches the minimum: its candidates
                 // precede those of every higher combination
                 uint32_t cstar = 9;
