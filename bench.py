@@ -38,9 +38,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/*.md), scaled by what the
 # same counters read for a 1 GiB device-to-device copy (x2.0 and x1.0).  Valid only for the kernel
 # sources they were taken with: any change to the sources turns "traffic" into null.
-COUNTERS_TAKEN_WITH = "16dec2988f3822610f1aaca6ef0c5265b1e0012bfb83500135f791b5ddd70c55"
-SEARCH_TRAFFIC_BYTES = 28577.7 * 1024 * 2.0 + 325.1 * 1024 * 1.0
-EVAL_TRAFFIC_BYTES = 22405.4 * 1024 * 2.0 + 4197594.9 * 1024 * 1.0
+COUNTERS_TAKEN_WITH = "c399aac4b317b877675cf718fb7ba54b20e62be822879247249babba14a83058"
+SEARCH_TRAFFIC_BYTES = 26807.6 * 1024 * 2.0 + 325.1 * 1024 * 1.0
+EVAL_TRAFFIC_BYTES = 21936.0 * 1024 * 2.0 + 4197425.8 * 1024 * 1.0
 
 
 def kernel_sources_digest():
