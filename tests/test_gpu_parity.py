@@ -293,3 +293,31 @@ def test_offline_stage_counts(M):
     kept = list(st.rows_kept)
     assert kept[1] == 0 and all(0 < kept[g] < st.rows_valid[g] for g in (0, 2, 3))
     print("rows kept per group", kept, flush=True)
+
+
+def test_regrouped_energy_sum_near_its_exactness_bound(M):
+    """Whole-number energies whose largest total energy sits just below 2^53: the regrouped sum must
+    pick the same candidates, with the same bits, as the sum taken term by term; beyond the bound
+    the library must fall back by itself.  Every key, one at a time (dense kernel) and together."""
+    base = CONFIGS["prefill"]
+    w = base["workload"]
+    P = w["B"] * w["H"] * w["N"] * w["d"] * w["N"] * w["d"]
+    ow = O.workload(w)
+    for e_dram, e_gb, e_rf, e_mac in ((440.0, 19.0, 3.0, 2.0), (97.0, 211.0, 1.0, 5.0)):
+        h = dict(base["hw"], e_dram=e_dram, e_gb=e_gb, e_rf=e_rf, e_mac=e_mac)
+        worst = P * (8 * e_dram + 14 * e_gb + 6 * e_rf + (2 + w["c_softmax"]) * e_mac)
+        assert 0.9 * 2 ** 53 < worst < 2 ** 53
+        assert M.mmee_energy_regrouped(w, h, M.SEARCH_EXHAUSTIVE)
+        assert not M.mmee_energy_regrouped(w, dict(h, e_dram=e_dram + 60.0), M.SEARCH_EXHAUSTIVE)
+        oh = O.hw(h)
+        for flags in (M.SEARCH_EXHAUSTIVE, M.SEARCH_PRUNED):
+            ordered = M.mmee_search_multi(w, h, [0, 1, 2, 3], flags | M.SEARCH_ORDERED_SUM)
+            together = M.mmee_search_multi(w, h, [0, 1, 2, 3], flags)
+            singles = [M.mmee_search_ex(w, h, obj, flags) for obj in (0, 1, 2, 3)]
+            for obj in range(4):
+                for res in (together[obj], singles[obj]):
+                    assert res.best.idx == ordered[obj].best.idx, (e_dram, flags, obj)
+                    assert res.cost.energy_pj == ordered[obj].cost.energy_pj
+                    assert res.cost.latency_cycles == ordered[obj].cost.latency_cycles
+                check_result_against_oracle(ordered[obj], ow, oh)
+                assert ordered[obj].cost.energy_pj == float(int(ordered[obj].cost.energy_pj)) < 2 ** 53
