@@ -875,6 +875,9 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
         if (it.fine) stage_tables<TC_FINE / 2>(a, tab, t0, nt);
         else stage_tables<TC / 2>(a, tab, t0, nt);
         __syncthreads();
+        // a wave without a single row (the pruned lists are short) has nothing to cost; it meets the
+        // others again at the barrier on top of the loop
+        if (!__ballot(live)) continue;
 
         uint32_t off[NSEL];
 #pragma unroll
@@ -1490,6 +1493,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 4) void k_front_step(SearchArgs a)
         if (it.fine) stage_tables<TC_FINE / 2>(a, tab, t0, nt);
         else stage_tables<TC / 2>(a, tab, t0, nt);
         __syncthreads();
+        if (!__ballot(live)) continue;                       // a wave without a single row
         uint32_t off[NSEL];
 #pragma unroll
         for (int k = 0; k < NSEL; ++k) off[k] = sel_of(e, k);
