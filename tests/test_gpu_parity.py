@@ -321,3 +321,63 @@ def test_regrouped_energy_sum_near_its_exactness_bound(M):
                     assert res.cost.latency_cycles == ordered[obj].cost.latency_cycles
                 check_result_against_oracle(ordered[obj], ow, oh)
                 assert ordered[obj].cost.energy_pj == float(int(ordered[obj].cost.energy_pj)) < 2 ** 53
+
+
+DEGENERATE = [
+    # one tiling only; a prime extent (two divisors); head dim 1; a chunk boundary: 64 and 65 tilings
+    dict(B=1, H=1, N=1, d=1, word_bytes=2, tiling_mode=1, c_softmax=10),
+    dict(B=1, H=3, N=7, d=1, word_bytes=2, tiling_mode=1, c_softmax=0),
+    dict(B=2, H=1, N=128, d=1, word_bytes=4, tiling_mode=0, c_softmax=10),     # 8 * 1 * 8 * 1 = 64 tilings
+    dict(B=1, H=1, N=6561, d=5, word_bytes=2, tiling_mode=1, c_softmax=10),    # 9 * 2 * 9 * 2 = 324 tilings, no power of two
+]
+
+
+@pytest.mark.parametrize("case", range(len(DEGENERATE)))
+def test_search_degenerate_shapes_against_oracle_enumeration(M, case):
+    """Edge shapes through every kernel: each key alone (dense kernel when exhaustive), all keys in
+    one pass, pruned and exhaustive, against the oracle's full enumeration."""
+    w = DEGENERATE[case]
+    h = dict(pe_rows=4, pe_cols=4, n_arrays=1, rf_bytes=64, gb_bytes=1 << 16,
+             e_dram=200.0, e_gb=6.0, e_rf=1.0, e_mac=1.0, dram_bw=16.0, gb_bw=64.0)
+    ow, oh = O.workload(w), O.hw(h)
+    rc, idx, cost, n_valid, _ = O.search_all(ow, oh)
+    assert rc == 0 and n_valid > 0
+    S = O.space_size(ow, oh)
+    assert M.mmee_space_size(w, h) == S
+    first, n = 0, min(S, 300000)
+    assert_costs_equal(M.mmee_eval_batch(w, h, first, n), O.eval_batch(ow, oh, first, n), case)
+    assert_costs_equal(M.mmee_eval_batch(w, h, S - n, n), O.eval_batch(ow, oh, S - n, n), case)
+    for flags in (M.SEARCH_EXHAUSTIVE, M.SEARCH_PRUNED, M.SEARCH_EXHAUSTIVE | M.SEARCH_ORDERED_SUM):
+        singles = [M.mmee_search_ex(w, h, obj, flags) for obj in range(4)]
+        multi = M.mmee_search_multi(w, h, [0, 1, 2, 3], flags)
+        for obj in range(4):
+            for res in (singles[obj], multi[obj]):
+                assert res.best.idx == idx[obj], (case, flags, obj)
+                assert res.cost.energy_pj == cost[obj].energy_pj
+                assert res.cost.latency_cycles == cost[obj].latency_cycles
+                check_result_against_oracle(res, ow, oh)
+
+
+def test_search_widest_divisor_lists(M):
+    """The largest divisor list the tables hold (720720 has 240 divisors): 57600 tilings, 3.1e10
+    candidates.  The oracle cannot enumerate that in a test, so: pruned == exhaustive for every key,
+    the winners' records are the oracle's, and no candidate of an oracle-searched index window around
+    each winner beats it."""
+    w = dict(B=1, H=1, N=720720, d=1, word_bytes=2, tiling_mode=1, c_softmax=10)
+    h = dict(CONFIGS["bert"]["hw"], gb_bytes=1 << 22)
+    ow, oh = O.workload(w), O.hw(h)
+    assert M.mmee_space_size(w, h) == 240 * 240 * 540000
+    full = M.mmee_search_multi(w, h, [0, 1, 2, 3], M.SEARCH_EXHAUSTIVE)
+    pruned = M.mmee_search_multi(w, h, [0, 1, 2, 3], M.SEARCH_PRUNED)
+    singles = [M.mmee_search_ex(w, h, obj, M.SEARCH_EXHAUSTIVE) for obj in range(4)]
+    T = 240 * 240
+    for obj in range(4):
+        assert full[obj].best.idx == pruned[obj].best.idx == singles[obj].best.idx, obj
+        check_result_against_oracle(full[obj], ow, oh)
+        # all tilings of the winner's index row, and of the row before it
+        row = full[obj].best.idx // T
+        lo = max(row - 1, 0) * T
+        rc, bi, c, nv, _ = O.search(ow, oh, obj, lo, (row + 1) * T - lo)
+        assert rc == 0 and bi == full[obj].best.idx, (obj, bi)
+    with pytest.raises(M.MmeeError):                      # one divisor too many for the tables
+        M.mmee_space_size(dict(w, N=1441440), h)
