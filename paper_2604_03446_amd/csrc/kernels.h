@@ -607,6 +607,10 @@ struct SearchArgs {
     uint32_t cls_off[2][2];      // [r][f] start of the group's list inside rows[]
     uint32_t cls_cnt[2][2];      // [r][f] rows in it
     uint32_t rb_split;           // row blocks of class r = 0; the rest belong to r = 1
+    // A class of at most 256 rows (the pruned lists) is one row block whose waves share the work
+    // differently: wave_split[r] = S > 1 means the rows fill 8 / S waves and each of them comes S
+    // times, once per S-th of the item's tilings.  S = 1: one row per thread, all tilings.
+    uint32_t wave_split[2];
     uint32_t n_rb;               // row blocks in all
     // Tilings [0, n_cc * TC) are cut into chunks of TC, the rest into n_fc chunks of TC_FINE.  Items
     // [0, n_coarse_items) are the (row block, coarse chunk) pairs, the fine ones follow: the short
@@ -662,6 +666,7 @@ __device__ __forceinline__ void read_tilings(uint32_t &addr, int tl, double &fir
 // one dataflow row (live = false for the padding lanes of a class's last row block).
 struct ItemView {
     uint32_t r, t0, nt;
+    uint32_t tl_lo, tl_hi;       // this wave's share of the tilings [0, nt rounded up to whole turns)
     uint32_t dfrow;
     uint4 e;                     // the row's selectors
     bool live, fine;
@@ -685,9 +690,25 @@ __device__ __forceinline__ ItemView locate_item(const SearchArgs &a, uint32_t it
         v.nt = min((uint32_t)TC_FINE, a.mc.T - v.t0);
     }
     v.r = rb >= a.rb_split;
-    const uint32_t slot = (rb - (v.r ? a.rb_split : 0u)) * SEARCH_THREADS + threadIdx.x;
     const uint32_t n0 = a.cls_cnt[v.r][0], n1 = a.cls_cnt[v.r][1];
-    v.live = slot < n0 + n1;
+    const uint32_t turns = (v.nt + TURN - 1) / TURN;
+    const uint32_t split = a.wave_split[v.r];
+    uint32_t slot;
+    if (split > 1) {
+        // waves_for_rows waves hold the rows; wave w takes row group w % waves_for_rows and the
+        // (w / waves_for_rows)-th share of the turns
+        const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        const uint32_t waves_for_rows = (n0 + n1 + 63) / 64;
+        const uint32_t share = wave / waves_for_rows;
+        slot = share < split ? (wave % waves_for_rows) * 64 + lane : 0xFFFFFFFFu;
+        v.tl_lo = min(share, split) * turns / split * TURN;
+        v.tl_hi = min(share + 1, split) * turns / split * TURN;
+    } else {
+        slot = (rb - (v.r ? a.rb_split : 0u)) * SEARCH_THREADS + threadIdx.x;
+        v.tl_lo = 0;
+        v.tl_hi = turns * TURN;
+    }
+    v.live = slot < n0 + n1 && v.tl_lo < v.tl_hi;
     const uint32_t where = !v.live ? a.cls_off[v.r][n0 ? 0 : 1]
                                    : (slot < n0 ? a.cls_off[v.r][0] + slot : a.cls_off[v.r][1] + (slot - n0));
     v.e = a.row_enc[where];
@@ -872,6 +893,8 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
         const uint32_t dfrow = it.dfrow;
         const uint4 e = it.e;
         const uint32_t r = it.r, t0 = it.t0, nt = it.nt;
+        // this wave's tilings of the chunk (all of them unless the class is a short list)
+        const uint32_t tl_lo = __builtin_amdgcn_readfirstlane(it.tl_lo), tl_hi = __builtin_amdgcn_readfirstlane(it.tl_hi);
         if (it.fine) stage_tables<TC_FINE / 2>(a, tab, t0, nt);
         else stage_tables<TC / 2>(a, tab, t0, nt);
         __syncthreads();
@@ -914,15 +937,14 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
         double v[2][NSEL];
         uint32_t sel_addr[NSEL];
 #pragma unroll
-        for (int k = 0; k < NSEL; ++k) sel_addr[k] = lds_address(tab + off[k] * LDS_ENT);
+        for (int k = 0; k < NSEL; ++k) sel_addr[k] = lds_address(tab + off[k] * LDS_ENT + tl_lo);
 #pragma unroll
         for (int k = 0; k < NSEL; ++k) read_tilings(sel_addr[k], 0, v[0][k], v[1][k]);
         TilingConstants X, Y;
-        request(X, 0);
+        request(X, tl_lo);
 
-        // nt rounded up to whole turns: the staged tilings beyond nt repeat the last one
-        const uint32_t nt_turns = (nt + TURN - 1) / TURN * TURN;
-        for (uint32_t tl8 = 0; tl8 < nt_turns; tl8 += TURN) {
+        // whole turns: the staged tilings beyond nt repeat the last one
+        for (uint32_t tl8 = tl_lo; tl8 < tl_hi; tl8 += TURN) {
 #pragma unroll
             for (int q = 0; q < TURN / 2; ++q) {
                 const uint32_t tl_pair = tl8 + 2 * q;
@@ -954,7 +976,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
 #pragma unroll
                     for (int k = 0; k < NSEL; ++k) read_tilings(sel_addr[k], 2 * (q + 1), v[0][k], v[1][k]);
                 } else {
-                    const uint32_t step = tl8 + TURN < nt_turns ? TURN * 8 : (TURN - 2) * 8;
+                    const uint32_t step = tl8 + TURN < tl_hi ? TURN * 8 : (TURN - 2) * 8;
 #pragma unroll
                     for (int k = 0; k < NSEL; ++k) sel_addr[k] += step;
 #pragma unroll
@@ -1083,7 +1105,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
                 }
                 double lat2 = fmax(l_dram2, cl[9 + c_u]);
                 double val2 = o == 0 ? en2 : (o == 1 ? lat2 : en2 * lat2);
-                const unsigned long long hits = __ballot(lane < nt && val2 == wave_v);
+                const unsigned long long hits = __ballot(lane >= tl_lo && lane < min(tl_hi, nt) && val2 == wave_v);
                 if (!hits) continue;                                 // cannot happen: the loop found it
                 const uint64_t idx = (uint64_t)t0 + ((uint32_t)__ffsll((long long)hits) - 1u) +
                                      (uint64_t)a.mc.T * first_row;

@@ -355,13 +355,18 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
         if (r == 0) a.rb_split = (in_class + SEARCH_THREADS - 1) / SEARCH_THREADS;
         rb += (in_class + SEARCH_THREADS - 1) / SEARCH_THREADS;
         nrows += in_class;
+        // a short list fills few waves: let them come several times, each with a share of the tilings
+        const uint32_t waves_for_rows = (in_class + 63) / 64;
+        a.wave_split[r] = (!bs_da_step && waves_for_rows >= 1 && waves_for_rows <= 4) ? (SEARCH_THREADS / 64) / waves_for_rows : 1u;
     }
+    const bool short_lists = a.wave_split[0] > 1 || a.wave_split[1] > 1;
     if (rb == 0) return MMEE_EINVAL;
     a.n_rb = rb;
     // tilings: chunks of TC, then chunks of TC_FINE worth about four fine items per resident block
     // (a coarse item's time), at least the ragged end
     {
-        const uint64_t fine_chunks_wanted = (4ull * S.resident_blocks + rb - 1) / rb;
+        // (short lists split an item's tilings over the waves instead: only the ragged end is fine)
+        const uint64_t fine_chunks_wanted = short_lists ? 0 : (4ull * S.resident_blocks + rb - 1) / rb;
         const uint64_t fine_tilings = std::min<uint64_t>(p.T, fine_chunks_wanted * TC_FINE);
         a.n_cc = (uint32_t)((p.T - fine_tilings) / TC);
         a.n_fc = (uint32_t)((p.T - (uint64_t)a.n_cc * TC + TC_FINE - 1) / TC_FINE);
