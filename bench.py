@@ -38,9 +38,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/*.md), scaled by what the
 # same counters read for a 1 GiB device-to-device copy (x2.0 and x1.0).  Valid only for the kernel
 # sources they were taken with: any change to the sources turns "traffic" into null.
-COUNTERS_TAKEN_WITH = "29ea9b75c06bce181f7fb6c5b4c8ee1059370be9a18190355aa1862a5ba38331"
-SEARCH_TRAFFIC_BYTES = 27961.9 * 1024 * 2.0 + 325.1 * 1024 * 1.0
-EVAL_TRAFFIC_BYTES = 21881.2 * 1024 * 2.0 + 4197544.5 * 1024 * 1.0
+COUNTERS_TAKEN_WITH = "2ee5b26062fbf4e15fb71cc2b05e8cc9dea8b30f106c8327ec722ba2f1fb9f55"
+SEARCH_TRAFFIC_BYTES = 27565.8 * 1024 * 2.0 + 325.1 * 1024 * 1.0
+EVAL_TRAFFIC_BYTES = 21880.5 * 1024 * 2.0 + 4197342.5 * 1024 * 1.0
 
 
 def kernel_sources_digest():
