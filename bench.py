@@ -79,7 +79,7 @@ def main():
     offline_ms = (time.perf_counter() - t0) * 1e3
 
     cfg = CONFIGS["bert"]
-    w, h = cfg["workload"], cfg["hw"]
+    w, h = M.workload(cfg["workload"]), M.hw(cfg["hw"])      # C structs once, not per call
     objectives = [M.OBJ_ENERGY, M.OBJ_LATENCY]
     regrouped = M.mmee_energy_regrouped(w, h, M.SEARCH_EXHAUSTIVE)
     ops = OPS_PER_CANDIDATE[regrouped]
@@ -150,19 +150,20 @@ def main():
         tto = {}
         for name, c in CONFIGS.items():
             objs = c["objectives"]
+            cw, ch = M.workload(c["workload"]), M.hw(c["hw"])
             for _ in range(5):
-                M.mmee_search_multi(c["workload"], c["hw"], objs, M.SEARCH_PRUNED)
+                M.mmee_search_multi(cw, ch, objs, M.SEARCH_PRUNED)
             n = 50
             t1 = time.perf_counter()
             for _ in range(n):
-                r = M.mmee_search_multi(c["workload"], c["hw"], objs, M.SEARCH_PRUNED)
+                r = M.mmee_search_multi(cw, ch, objs, M.SEARCH_PRUNED)
             dt_p = (time.perf_counter() - t1) / n
             for _ in range(2):
-                M.mmee_search_multi(c["workload"], c["hw"], objs, M.SEARCH_EXHAUSTIVE)
+                M.mmee_search_multi(cw, ch, objs, M.SEARCH_EXHAUSTIVE)
             n = 10
             t1 = time.perf_counter()
             for _ in range(n):
-                rx = M.mmee_search_multi(c["workload"], c["hw"], objs, M.SEARCH_EXHAUSTIVE)
+                rx = M.mmee_search_multi(cw, ch, objs, M.SEARCH_EXHAUSTIVE)
             dt_x = (time.perf_counter() - t1) / n
             assert [a.best.idx for a in r] == [a.best.idx for a in rx]
             tto[name] = {"pruned_ms": dt_p * 1e3, "pruned_candidates": r[0].evaluated,
@@ -203,7 +204,7 @@ def main():
 
     if not args.no_cpu_baseline and not args.profile_only:
         import oracle as O
-        ow, oh = O.workload(w), O.hw(h)
+        ow, oh = O.workload(cfg["workload"]), O.hw(cfg["hw"])
         t1 = time.perf_counter()
         rc, idx, cost, n_valid, threads = O.search_all(ow, oh)
         dt = time.perf_counter() - t1
