@@ -365,8 +365,11 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     // tilings: chunks of TC, then chunks of TC_FINE worth about four fine items per resident block
     // (a coarse item's time), at least the ragged end
     {
-        // (short lists split an item's tilings over the waves instead: only the ragged end is fine)
-        const uint64_t fine_chunks_wanted = short_lists ? 0 : (4ull * S.resident_blocks + rb - 1) / rb;
+        // (short lists split an item's tilings over the waves instead: short chunks only while one
+        // round of blocks takes them all)
+        const uint64_t all_fine = (p.T + TC_FINE - 1) / TC_FINE;
+        const uint64_t fine_chunks_wanted = short_lists ? (rb * all_fine <= S.resident_blocks ? all_fine : 0)
+                                                        : (4ull * S.resident_blocks + rb - 1) / rb;
         const uint64_t fine_tilings = std::min<uint64_t>(p.T, fine_chunks_wanted * TC_FINE);
         a.n_cc = (uint32_t)((p.T - fine_tilings) / TC);
         a.n_fc = (uint32_t)((p.T - (uint64_t)a.n_cc * TC + TC_FINE - 1) / TC_FINE);
