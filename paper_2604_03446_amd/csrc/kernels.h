@@ -632,6 +632,8 @@ struct SearchArgs {
     uint32_t *work_counter;
     FinalRecord *final_out;      // [N_OBJ]
     double e_limit;              // LIMIT kernels only: candidates with energy >= e_limit are left out
+    Key *final_key_dev;          // [N_OBJ] the winning keys once more, in device memory, for a pass that follows
+    const Key *lat_cap;          // LATCAP kernels only: candidates with a latency above lat_cap->p are left out
     const uint64_t *ctab_e;
     DivTable const *dv;          // device copy, for the final record's mapping
 };
@@ -821,6 +823,7 @@ __device__ __forceinline__ void finish_grid(const SearchArgs &a, Key (*wave_best
             if (key_less(wave_best[o][wv], k)) k = wave_best[o][wv];
         FinalRecord *fr = a.final_out + o;
         fr->key = k;
+        if (a.final_key_dev) a.final_key_dev[o] = k;
         mmee_cost c;
         mmee_mapping m;
         if (k.p < inf) {
@@ -1190,9 +1193,10 @@ constexpr int DENSE_THREADS = 512;           // eight waves, two blocks per CU
 constexpr int DENSE_BLOCKS_PER_CU = 2;
 constexpr int DENSE_WAVES = DENSE_THREADS / 64;
 
-template <int MASK, bool FAST, bool LIMIT = false, bool REGROUP = false>
+template <int MASK, bool FAST, bool LIMIT = false, bool REGROUP = false, bool LATCAP = false>
 __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
 {
+    static_assert(!LATCAP || (MASK == 1 && !LIMIT), "the latency cap goes with the energy key alone");
     __shared__ double tab[NENT * LDS_ENT];
     __shared__ Key wave_best[N_OBJ][DENSE_WAVES];
     __shared__ uint32_t is_last;
@@ -1219,6 +1223,11 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
     };
     const EncTable enc = {(ConstPtr<u32x4>)a.enc};
     ConstPtr<uint32_t> cls_list = as_constant(a.cls);
+    // LATCAP: the second pass of the (latency, energy) key over the full row set.  The first pass found
+    // the lowest latency; a candidate's latency max(l_dram, constant) stays within it exactly when both
+    // parts do, so the cap masks rows and combinations separately and the pass costs what an
+    // energy-only pass costs.
+    const double lat_cap = LATCAP ? uniform_f64(a.lat_cap->p) : inf;
 
     uint32_t upcoming = blockIdx.x;
     while (true) {
@@ -1254,6 +1263,12 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
 #pragma unroll
         for (int c = 0; c < 9; ++c) { gb[c] = cs[c]; latc[c] = cs[9 + c]; }
         const double e_rf_part = REGROUP ? 0.0 : cs[18], e_mac_part = REGROUP ? 0.0 : cs[19];
+        double too_slow[9];                                   // 0, or +inf for a combination beyond the cap
+#pragma unroll
+        for (int c = 0; c < 9; ++c) {
+            too_slow[c] = LATCAP && !(latc[c] <= lat_cap) ? inf : 0.0;
+            if constexpr (LATCAP && REGROUP) gb[c] = fmax(gb[c], too_slow[c]);
+        }
         const double *col = tab + tl;                         // entry e of this tiling: col[e * LDS_ENT]
 
         // the class row and the task's (D, E) rows: all requested before the first is used
@@ -1279,6 +1294,7 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
             double l_dram;
             if constexpr (FAST) l_dram = dram_words * a.mc.dram_k;
             else l_dram = a.mc.dram_bw > 0.0 ? a.mc.c_lat * (((dram_words / a.mc.BH) * a.mc.word) / a.mc.dram_bw) : 0.0;
+            if constexpr (LATCAP) ok = ok & (l_dram <= lat_cap);
             const double over = __hiloint2double(ok ? 0 : 0x7ff00000, 0);
             e_part = fmax(e_part, over);
             l_dram = fmax(l_dram, over);
@@ -1294,6 +1310,7 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
                     en = e_part + a.mc.e_gb * gb_words;
                     en = en + e_rf_part;
                     en = en + e_mac_part;
+                    if constexpr (LATCAP) en = fmax(en, too_slow[c9]);
                 }
                 double lat = fmax(l_dram, latc[c9]);
                 if constexpr (LIMIT) {
@@ -1396,20 +1413,25 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
                 // Recover the row: go through the task's rows in index order and cost them again for
                 // combination c_u, with the very operations of the loop above; the first row in which
                 // a tiling reaches the minimum holds the lowest index, at its lowest such tiling.
-                double gb_u = gb[0], latc_u = latc[0];
+                double gb_u = gb[0], latc_u = latc[0], slow_u = too_slow[0];
 #pragma unroll
-                for (int c9 = 1; c9 < 9; ++c9) { gb_u = c_u == (uint32_t)c9 ? gb[c9] : gb_u; latc_u = c_u == (uint32_t)c9 ? latc[c9] : latc_u; }
+                for (int c9 = 1; c9 < 9; ++c9) {
+                    gb_u = c_u == (uint32_t)c9 ? gb[c9] : gb_u;
+                    latc_u = c_u == (uint32_t)c9 ? latc[c9] : latc_u;
+                    slow_u = c_u == (uint32_t)c9 ? too_slow[c9] : slow_u;
+                }
                 for (uint32_t code = 0; code < npd * 25u; ++code) {
                     const uint4 e_de = enc[row_de0 + 25u * (code / 25u)];
                     const uint4 e_ab = enc[row0 + code % 25u];
                     const double bs1 = (col[sel_of(e_ab, 0) * LDS_ENT] + c_bs) + col[sel_of(e_de, 1) * LDS_ENT];
                     const double bs2 = col[sel_of(e_de, 3) * LDS_ENT] + (c_bs + col[sel_of(e_ab, 4) * LDS_ENT]);
                     const double dram2 = (col[sel_of(e_ab, 5) * LDS_ENT] + c_da) + col[sel_of(e_de, 6) * LDS_ENT];
-                    const bool ok2 = fmax(bs1, bs2) <= cap;
+                    bool ok2 = fmax(bs1, bs2) <= cap;
                     double e2 = (REGROUP ? a.mc.e_sum : a.mc.e_dram) * dram2;
                     double l2;
                     if constexpr (FAST) l2 = dram2 * a.mc.dram_k;
                     else l2 = a.mc.dram_bw > 0.0 ? a.mc.c_lat * (((dram2 / a.mc.BH) * a.mc.word) / a.mc.dram_bw) : 0.0;
+                    if constexpr (LATCAP) ok2 = ok2 & (l2 <= lat_cap);
                     const double over2 = __hiloint2double(ok2 ? 0 : 0x7ff00000, 0);
                     e2 = fmax(e2, over2);
                     l2 = fmax(l2, over2);
@@ -1423,6 +1445,7 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
                         en2 = e2 + a.mc.e_gb * gb2;
                         en2 = en2 + e_rf_part;
                         en2 = en2 + e_mac_part;
+                        if constexpr (LATCAP) en2 = fmax(en2, slow_u);
                     }
                     const double lat2 = fmax(l2, latc_u);
                     const double val2 = o == 0 ? en2 : (o == 1 ? lat2 : en2 * lat2);

@@ -40,6 +40,7 @@ struct State {
     uint4 *row_enc[2] = {nullptr, nullptr};     // the encoded rows in list order
     uint32_t *counts_dev = nullptr;
     uint32_t counts[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+    Key *key_dev = nullptr;                     // [N_OBJ] winning keys of a pass, for the pass that follows it
     uint32_t *cls_dev = nullptr;                // (order, r, f) classes whose rows denote dataflows
     uint32_t n_cls = 0;
     // online scratch, grown on demand
@@ -187,6 +188,7 @@ int ensure_ready()
     HIP_TRY(hipMalloc(&S.rows[0], sizeof(uint32_t) * N_DFROWS));
     HIP_TRY(hipMalloc(&S.rows[1], sizeof(uint32_t) * N_DFROWS));
     HIP_TRY(hipMalloc(&S.counts_dev, sizeof(uint32_t) * 8));
+    HIP_TRY(hipMalloc(&S.key_dev, sizeof(Key) * N_OBJ));
     HIP_TRY(hipMalloc(&S.ticket, 2 * sizeof(uint32_t)));        // [0] finish ticket, [1] work counter
     HIP_TRY(hipMemset(S.ticket, 0, 2 * sizeof(uint32_t)));
     HIP_TRY(hipMemset(S.rows[0], 0, sizeof(uint32_t) * N_DFROWS));
@@ -322,6 +324,14 @@ void launch_dense_mask(bool exact_k, dim3 grid, const SearchArgs &a)
     else hipLaunchKernelGGL((k_search_dense<MASK, false>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
 }
 
+// second pass of the (latency, energy) key: lowest energy among the candidates within a.lat_cap
+void launch_dense_latcap(bool exact_k, dim3 grid, const SearchArgs &a)
+{
+    if (a.mc.regroup) hipLaunchKernelGGL((k_search_dense<1, true, false, true, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
+    else if (exact_k) hipLaunchKernelGGL((k_search_dense<1, true, false, false, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
+    else hipLaunchKernelGGL((k_search_dense<1, false, false, false, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
+}
+
 void launch_dense_limited(bool exact_k, dim3 grid, const SearchArgs &a)
 {
     if (a.mc.regroup) hipLaunchKernelGGL((k_search_dense<4, true, true, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
@@ -417,6 +427,18 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
         a.e_limit = *e_limit;
         if (dense) launch_dense_limited(p.exact_k, grid, a);
         else launch_search_limited(p.exact_k, grid, a);
+    } else if (dense && mask == 4) {
+        // The (latency, energy) key over the full row set, as two passes that each cost what a
+        // single scalar key costs: the lowest latency first, then the lowest energy among the
+        // candidates that reach it (a candidate's latency is a maximum of a row part and a
+        // combination part, so the cap applies to the two separately).  The second pass's energy
+        // record lands in the slot of this key.
+        SearchArgs first = a, second = a;
+        first.final_key_dev = S.key_dev;
+        launch_dense_mask<2>(p.exact_k, grid, first);
+        second.lat_cap = S.key_dev + 1;
+        second.final_out = a.final_out + 2;
+        launch_dense_latcap(p.exact_k, grid, second);
     } else if (dense)
     switch (mask) {
     case 1: launch_dense_mask<1>(p.exact_k, grid, a); break;
@@ -824,7 +846,7 @@ void mmee_shutdown(void)
 {
     std::lock_guard<std::mutex> guard(g_lock);
     if (S.ready || S.btab || S.partials) (void)hipStreamSynchronize(S.stream);
-    (void)hipFree(S.enc); (void)hipFree(S.sig); (void)hipFree(S.flags); (void)hipFree(S.cls_dev);
+    (void)hipFree(S.enc); (void)hipFree(S.sig); (void)hipFree(S.flags); (void)hipFree(S.cls_dev); (void)hipFree(S.key_dev);
     (void)hipFree(S.rows[0]); (void)hipFree(S.rows[1]); (void)hipFree(S.counts_dev);
     (void)hipFree(S.row_enc[0]); (void)hipFree(S.row_enc[1]);
     (void)hipFree(S.btab); (void)hipFree(S.ctab_s); (void)hipFree(S.ctab_e);
