@@ -1202,7 +1202,7 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
     __shared__ uint32_t is_last;
     __shared__ uint32_t s_item;
 
-    constexpr bool LAZY = !(MASK & 4) && !LIMIT;
+    constexpr bool LAZY = !(MASK & 4);             // the energy bound of LIMIT masks values, which the lazy argmin handles too
     const double inf = pos_inf();
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1266,7 +1266,7 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
         double too_slow[9];                                   // 0, or +inf for a combination beyond the cap
 #pragma unroll
         for (int c = 0; c < 9; ++c) {
-            too_slow[c] = LATCAP && !(latc[c] <= lat_cap) ? inf : 0.0;
+            too_slow[c] = LATCAP && !(latc[c] <= lat_cap && lat_cap < inf) ? inf : 0.0;   // no cap found: nothing qualifies
             if constexpr (LATCAP && REGROUP) gb[c] = fmax(gb[c], too_slow[c]);
         }
         const double *col = tab + tl;                         // entry e of this tiling: col[e * LDS_ENT]
@@ -1447,7 +1447,12 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
                         en2 = en2 + e_mac_part;
                         if constexpr (LATCAP) en2 = fmax(en2, slow_u);
                     }
-                    const double lat2 = fmax(l2, latc_u);
+                    double lat2 = fmax(l2, latc_u);
+                    if constexpr (LIMIT) {
+                        const bool out_of_range = !(en2 < a.e_limit);
+                        en2 = out_of_range ? inf : en2;
+                        lat2 = out_of_range ? inf : lat2;
+                    }
                     const double val2 = o == 0 ? en2 : (o == 1 ? lat2 : en2 * lat2);
                     const unsigned long long hits = __ballot(val2 == wave_v);
                     if (!hits) continue;

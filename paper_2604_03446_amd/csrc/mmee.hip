@@ -332,11 +332,13 @@ void launch_dense_latcap(bool exact_k, dim3 grid, const SearchArgs &a)
     else hipLaunchKernelGGL((k_search_dense<1, false, false, false, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
 }
 
+// first pass of one step of the Pareto walk over the full row set: lowest latency among the candidates
+// with energy below a.e_limit (the second pass is launch_dense_latcap)
 void launch_dense_limited(bool exact_k, dim3 grid, const SearchArgs &a)
 {
-    if (a.mc.regroup) hipLaunchKernelGGL((k_search_dense<4, true, true, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
-    else if (exact_k) hipLaunchKernelGGL((k_search_dense<4, true, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
-    else hipLaunchKernelGGL((k_search_dense<4, false, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
+    if (a.mc.regroup) hipLaunchKernelGGL((k_search_dense<2, true, true, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
+    else if (exact_k) hipLaunchKernelGGL((k_search_dense<2, true, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
+    else hipLaunchKernelGGL((k_search_dense<2, false, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
 }
 
 // enqueue one pass (tables + search + readback of the final records) into slot `slot`
@@ -425,8 +427,17 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     } else if (e_limit) {
         if (mask != 4) return MMEE_EINVAL;
         a.e_limit = *e_limit;
-        if (dense) launch_dense_limited(p.exact_k, grid, a);
-        else launch_search_limited(p.exact_k, grid, a);
+        if (dense) {
+            // two scalar passes, as for the unbounded key below; the second needs no energy bound: the
+            // lowest energy among the candidates within the latency found is below it
+            SearchArgs first = a, second = a;
+            first.final_key_dev = S.key_dev;
+            launch_dense_limited(p.exact_k, grid, first);
+            second.lat_cap = S.key_dev + 1;
+            second.final_out = a.final_out + 2;
+            launch_dense_latcap(p.exact_k, grid, second);
+        } else
+            launch_search_limited(p.exact_k, grid, a);
     } else if (dense && mask == 4) {
         // The (latency, energy) key over the full row set, as two passes that each cost what a
         // single scalar key costs: the lowest latency first, then the lowest energy among the
