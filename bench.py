@@ -38,9 +38,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/*.md), scaled by what the
 # same counters read for a 1 GiB device-to-device copy (x2.0 and x1.0).  Valid only for the kernel
 # sources they were taken with: any change to the sources turns "traffic" into null.
-COUNTERS_TAKEN_WITH = "472280303649546b026304cfce1f5f8b9060f2994f6d847e783c3052b450e978"
-SEARCH_TRAFFIC_BYTES = 28578.1 * 1024 * 2.0 + 325.1 * 1024 * 1.0
-EVAL_TRAFFIC_BYTES = 22222.6 * 1024 * 2.0 + 4197393.5 * 1024 * 1.0
+COUNTERS_TAKEN_WITH = "413960388a97939a43d164612c5468e954f158e2ad829c1ed98afd65cb43fe02"
+SEARCH_TRAFFIC_BYTES = 28706.7 * 1024 * 2.0 + 325.1 * 1024 * 1.0
+EVAL_TRAFFIC_BYTES = 21929.7 * 1024 * 2.0 + 4197452.8 * 1024 * 1.0
 
 
 def kernel_sources_digest():
