@@ -4,7 +4,9 @@
 //   k_prune_rows     offline:  symbolic dominance test inside each group (Sec. VI-B)
 //   k_compact_rows   offline:  ballot + prefix compaction of surviving rows
 //   k_build_tilings  online:   tiling id -> boundaries -> per-tiling tables (the boundary-matrix side)
-//   k_search         online:   contraction, capacity mask, energy/latency, hierarchical argmin
+//   k_search         online:   contraction, capacity mask, energy/latency, hierarchical argmin (lane = row)
+//   k_search_dense   online:   the same for one key over the full row set (lane = tiling)
+//   k_front_step     online:   one point of the buffer-size / DRAM-access front
 //   k_eval_batch     online:   the same model, one 64-byte record per candidate
 //   k_decode         online:   index -> mapping
 #pragma once
@@ -638,7 +640,7 @@ struct SearchArgs {
     DivTable const *dv;          // device copy, for the final record's mapping
 };
 
-constexpr int BLOCKS_PER_CU = 2;       // what LDS (63 KB per block) lets a CU hold
+constexpr int BLOCKS_PER_CU = 2;       // what LDS (64 KB per block) lets a CU hold
 constexpr int TC = 64;                 // tilings per coarse item
 constexpr int TC_FINE = 32;            // tilings per fine item
 constexpr int SEARCH_THREADS = 512;
