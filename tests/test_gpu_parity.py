@@ -381,3 +381,91 @@ def test_search_widest_divisor_lists(M):
         assert rc == 0 and bi == full[obj].best.idx, (obj, bi)
     with pytest.raises(M.MmeeError):                      # one divisor too many for the tables
         M.mmee_space_size(dict(w, N=1441440), h)
+
+
+def random_small_cases(count, seed):
+    """Seeded small problems whose whole space the oracle enumerates in well under a second:
+    every mix of whole-number / fractional energies, power-of-two / other bandwidths and array
+    counts, tight and loose buffers."""
+    rng = SplitMix64(seed)
+
+    def divisors(x):
+        return sum(1 for a in range(1, x + 1) if x % a == 0)
+
+    cases = []
+    while len(cases) < count:
+        N, d = 1 + rng.next() % 40, 1 + rng.next() % 12
+        mode = rng.next() % 2
+        nd = (lambda x: sum(1 for a in range(x.bit_length()) if x % (1 << a) == 0)) if mode == 0 else divisors
+        if (nd(N) * nd(d)) ** 2 > 100:
+            continue
+        w = dict(B=1 + rng.next() % 2, H=1 + rng.next() % 3, N=N, d=d, word_bytes=(1, 2, 4)[rng.next() % 3],
+                 tiling_mode=mode, c_softmax=(0, 10, 3)[rng.next() % 3])
+        whole = rng.next() % 2 == 0
+        e = [float(1 + rng.next() % 300), float(1 + rng.next() % 20), float(rng.next() % 4), float(rng.next() % 3)]
+        if not whole:
+            e = [v + (rng.next() % 16) / 16.0 for v in e]
+        h = dict(pe_rows=1 << (rng.next() % 4), pe_cols=1 << (rng.next() % 4), n_arrays=(1, 2, 3, 4)[rng.next() % 4],
+                 rf_bytes=3 * w["word_bytes"] + rng.next() % 200, gb_bytes=w["word_bytes"] * (4 + rng.next() % (N * d * 6 + 8)),
+                 e_dram=e[0], e_gb=e[1], e_rf=e[2], e_mac=e[3],
+                 dram_bw=(0.0, 1.0, 2.0, 3.0, 0.5, 64.0, 6.0)[rng.next() % 7], gb_bw=(0.0, 4.0, 5.0, 128.0)[rng.next() % 4])
+        cases.append((w, h))
+    return cases
+
+
+def test_search_random_small_problems_against_oracle_enumeration(M):
+    """A hundred seeded problems through every search path: each key alone and all four in one pass, pruned
+    and exhaustive, the library's own choice of sum order and the term-by-term one."""
+    feasible = 0
+    for case, (w, h) in enumerate(random_small_cases(100, 0x5EA5C4)):
+        ow, oh = O.workload(w), O.hw(h)
+        rc, idx, cost, n_valid, _ = O.search_all(ow, oh)
+        assert rc == 0
+        for flags in (M.SEARCH_EXHAUSTIVE, M.SEARCH_PRUNED, M.SEARCH_EXHAUSTIVE | M.SEARCH_ORDERED_SUM):
+            singles = [M.mmee_search_ex(w, h, obj, flags, allow_infeasible=True) for obj in range(4)]
+            for obj in range(4):
+                code, res = singles[obj]
+                if n_valid == 0:
+                    assert code == M.ENOFEASIBLE, (case, flags, obj)
+                    continue
+                assert code == 0 and res.best.idx == idx[obj], (case, w, h, flags, obj)
+                assert res.cost.energy_pj == cost[obj].energy_pj and res.cost.latency_cycles == cost[obj].latency_cycles
+            if n_valid:
+                multi = M.mmee_search_multi(w, h, [0, 1, 2, 3], flags)
+                assert [r.best.idx for r in multi] == list(idx[:4]), (case, w, h, flags)
+        feasible += n_valid > 0
+    assert feasible >= 75
+
+
+def test_search_random_small_chains_against_oracle_enumeration(M):
+    """The same for free two-GEMM chains (four independent extents)."""
+    rng = SplitMix64(0xC4A125)
+    done = 0
+    while done < 40:
+        ext = [1 + rng.next() % 30 for _ in range(4)]
+        mode = rng.next() % 2
+        nd = (lambda x: sum(1 for a in range(x.bit_length()) if x % (1 << a) == 0)) if mode == 0 else \
+             (lambda x: sum(1 for a in range(1, x + 1) if x % a == 0))
+        T = nd(ext[0]) * nd(ext[1]) * nd(ext[2]) * nd(ext[3])
+        if T > 100:
+            continue
+        c = dict(batch=1 + rng.next() % 4, I=ext[0], K=ext[1], L=ext[2], J=ext[3], word_bytes=2, tiling_mode=mode,
+                 c_softmax=(0, 10)[rng.next() % 2])
+        h = dict(pe_rows=1 << (rng.next() % 4), pe_cols=1 << (rng.next() % 4), n_arrays=1 + rng.next() % 2,
+                 rf_bytes=8 + rng.next() % 120, gb_bytes=2 * (6 + rng.next() % (sum(ext) * 40)),
+                 e_dram=float(50 + rng.next() % 200), e_gb=float(1 + rng.next() % 9) + (rng.next() % 2) * 0.5,
+                 e_rf=1.0, e_mac=1.0, dram_bw=(1.0, 4.0, 60.0)[rng.next() % 3], gb_bw=(8.0, 0.0, 24.0)[rng.next() % 3])
+        oc, oh = O.workload(c), O.hw(h)
+        rc, idx, cost, n_valid, _ = O.search_all(oc, oh)
+        assert rc == 0
+        done += 1
+        if n_valid == 0:
+            continue
+        for flags in (M.SEARCH_EXHAUSTIVE, M.SEARCH_PRUNED):
+            multi = M.mmee_chain_search_multi(c, h, [0, 1, 2, 3], flags)
+            singles = [M.mmee_chain_search_multi(c, h, [obj], flags)[0] for obj in range(4)]
+            for obj in range(4):
+                for res in (multi[obj], singles[obj]):
+                    assert res.best.idx == idx[obj], (c, h, flags, obj)
+                    assert res.cost.energy_pj == cost[obj].energy_pj
+                    assert res.cost.latency_cycles == cost[obj].latency_cycles
