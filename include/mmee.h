@@ -126,8 +126,12 @@ enum {
     /* When the four energies per access are whole numbers and the largest possible total stays
      * below 2^53, every term of the energy is an exact integer and the search adds a (row, tiling)
      * part and a (tiling, stationary modes) part per candidate; the result has the same bits as
-     * the sum taken term by term in the order of Sec. V-D.  This flag (may be or-ed with the
-     * others) keeps the term-by-term order in every case. */
+     * the sum taken term by term in the order of Sec. V-D.  When only the size condition fails,
+     * the searches for the energy, the latency and the (latency, energy) key still start that way
+     * and keep the outcome if the optimal energy found is below 2^52 pJ: every candidate whose total
+     * reaches 2^53 computes to more than that in either order, all others are exact, so the optimum
+     * and its ties are those of the term-by-term sum; otherwise the search is repeated term by term.
+     * This flag (may be or-ed with the others) keeps the term-by-term order in every case. */
     MMEE_SEARCH_ORDERED_SUM = 2
 };
 
@@ -144,10 +148,10 @@ enum {
  * times 540000.  Pure host arithmetic. */
 int mmee_space_size(const mmee_workload *w, const mmee_hw *hw, uint64_t *out);
 
-/* *out = 1 when a search of (workload, hw) with these flags regroups the energy sum (see
- * MMEE_SEARCH_ORDERED_SUM): whole-number energies per access, total energy of any candidate
- * (Sec. V-D) below 2^53, and a power-of-two DRAM bandwidth and array count; else 0.  Pure host
- * arithmetic. */
+/* *out = 1 when the regrouped energy sum (see MMEE_SEARCH_ORDERED_SUM) is exact for every candidate
+ * of (workload, hw) and these flags allow it: whole-number energies per access, total energy of any
+ * candidate (Sec. V-D) below 2^53, and a power-of-two DRAM bandwidth and array count; else 0.  Pure
+ * host arithmetic. */
 int mmee_energy_regrouped(const mmee_workload *w, const mmee_hw *hw, uint32_t flags, int *out);
 
 /* On-device mixed-radix decode of n candidate indices (host arrays in and out). */

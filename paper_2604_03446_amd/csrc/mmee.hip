@@ -69,6 +69,7 @@ struct Plan {
     uint64_t space;
     bool exact_k;
     bool can_regroup;   // every term of the energy is an exact integer below 2^53
+    bool whole_energies; // the four energies per access are whole numbers (their size aside)
 };
 
 bool finite_nonneg(double v) { return std::isfinite(v) && v >= 0.0; }
@@ -145,8 +146,8 @@ int make_plan(const mmee_chain *w, const mmee_hw *hw, Plan &p)
         const long double P = (long double)w->batch * (long double)w->I * w->K * (long double)w->L * w->J;
         const long double worst = P * (8.0L * hw->e_dram + 14.0L * hw->e_gb + 6.0L * hw->e_rf +
                                        (2.0L + (long double)w->c_softmax) * hw->e_mac);
-        p.can_regroup = whole(hw->e_dram) && whole(hw->e_gb) && whole(hw->e_rf) && whole(hw->e_mac) &&
-                        worst < 9007199254740992.0L;
+        p.whole_energies = whole(hw->e_dram) && whole(hw->e_gb) && whole(hw->e_rf) && whole(hw->e_mac);
+        p.can_regroup = p.whole_energies && worst < 9007199254740992.0L;
     }
     mc.dram_bw = hw->dram_bw; mc.gb_bw = hw->gb_bw;
     // with a power-of-two bandwidth and array count, (B*H/n) * (words*word/bw) is the B*H-scaled
@@ -283,10 +284,21 @@ int ensure_slots(size_t n)
 
 // the model constants of one pass: whether the energy is regrouped is settled here, for the tables
 // and for the kernel alike
-ModelConst pass_constants(const Plan &p, uint32_t flags)
+//
+// Beyond the size bound the sum may still be regrouped for the scalar keys other than the
+// energy-delay product, subject to a check of the outcome (`*unproven` is set): all terms are
+// non-negative whole numbers, so a candidate whose true total is below 2^53 is exact in either
+// order, and any other candidate computes to more than 2^52 in either order.  An optimum below
+// 2^52 pJ therefore is the optimum of the term-by-term sum too, ties included; otherwise the
+// caller repeats the pass with MMEE_SEARCH_ORDERED_SUM.
+constexpr double REGROUP_PROOF_LIMIT = 4503599627370496.0;   // 2^52
+ModelConst pass_constants(const Plan &p, uint32_t flags, int mask = 8, bool *unproven = nullptr)
 {
     ModelConst mc = p.mc;
-    mc.regroup = (p.can_regroup && p.exact_k && !(flags & MMEE_SEARCH_ORDERED_SUM)) ? 1u : 0u;
+    const bool allowed = p.exact_k && !(flags & MMEE_SEARCH_ORDERED_SUM);
+    const bool on_trust = allowed && !p.can_regroup && p.whole_energies && !(mask & 8) && unproven;
+    mc.regroup = ((allowed && p.can_regroup) || on_trust) ? 1u : 0u;
+    if (unproven) *unproven = on_trust;
     return mc;
 }
 
@@ -343,10 +355,11 @@ void launch_dense_limited(bool exact_k, dim3 grid, const SearchArgs &a)
 
 // enqueue one pass (tables + search + readback of the final records) into slot `slot`
 int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_t *evaluated,
-                   const double *e_limit = nullptr, bool build_tables = true, bool bs_da_step = false)
+                   const double *e_limit = nullptr, bool build_tables = true, bool bs_da_step = false,
+                   bool *unproven = nullptr)
 {
     if (slot >= S.slots) return MMEE_EINVAL;
-    const ModelConst mc = pass_constants(p, flags);
+    const ModelConst mc = pass_constants(p, flags, bs_da_step ? 8 : mask, unproven);
     int rc = build_tables ? launch_tilings(p, mc, S.dv_dev + slot) : MMEE_OK;
     if (rc) return rc;
     const int which = (flags & MMEE_SEARCH_EXHAUSTIVE) ? 0 : 1;
@@ -650,12 +663,12 @@ int mmee_chain_search_many(const mmee_chain *w, const mmee_hw *hw, const int *ob
     if (rc) return rc;
 
     // group neighbouring entries that describe the same problem into one pass
-    struct Pass { uint32_t first, n; int mask; Plan plan; int rc; uint64_t evaluated; };
+    struct Pass { uint32_t first, n; int mask; Plan plan; int rc; uint64_t evaluated; bool unproven; };
     std::vector<Pass> passes;
     std::vector<int> codes(count, MMEE_OK);
     for (uint32_t a = 0; a < count;) {
         Pass ps;
-        ps.first = a; ps.n = 0; ps.mask = 0; ps.evaluated = 0;
+        ps.first = a; ps.n = 0; ps.mask = 0; ps.evaluated = 0; ps.unproven = false;
         ps.rc = make_plan(w + a, hw + a, ps.plan);
         uint32_t b = a;
         while (b < count && same_problem(w[a], hw[a], w[b], hw[b])) {
@@ -673,9 +686,36 @@ int mmee_chain_search_many(const mmee_chain *w, const mmee_hw *hw, const int *ob
     if (rc) return rc;
     for (size_t s = 0; s < passes.size(); ++s) {
         Pass &ps = passes[s];
-        if (ps.rc == MMEE_OK) ps.rc = enqueue_search(ps.plan, ps.mask, flags, s, &ps.evaluated);
+        if (ps.rc == MMEE_OK)
+            ps.rc = enqueue_search(ps.plan, ps.mask, flags, s, &ps.evaluated, nullptr, true, false, &ps.unproven);
     }
     HIP_TRY(hipStreamSynchronize(S.stream));
+    // a regrouped sum taken on trust (pass_constants) stands only if the energies found prove it
+    {
+        bool again = false;
+        for (size_t s = 0; s < passes.size(); ++s) {
+            Pass &ps = passes[s];
+            if (ps.rc != MMEE_OK || !ps.unproven) continue;
+            bool proven = true;
+            for (int o : {MMEE_OBJ_ENERGY, MMEE_OBJ_LATENCY_THEN_ENERGY}) {
+                if (!(ps.mask & (1 << o))) continue;
+                const FinalRecord &fr = S.final_host[N_OBJ * s + o];
+                double energy;
+                std::memcpy(&energy, &fr.cost[5], sizeof(double));          // mmee_cost::energy_pj
+                if (fr.key.p < INFINITY && !(energy < REGROUP_PROOF_LIMIT)) proven = false;
+            }
+            ps.unproven = !proven;
+            again = again || !proven;
+        }
+        if (again) {
+            for (size_t s = 0; s < passes.size(); ++s) {
+                Pass &ps = passes[s];
+                if (ps.rc != MMEE_OK || !ps.unproven) continue;
+                ps.rc = enqueue_search(ps.plan, ps.mask, flags | MMEE_SEARCH_ORDERED_SUM, s, &ps.evaluated);
+            }
+            HIP_TRY(hipStreamSynchronize(S.stream));
+        }
+    }
     const double seconds = now_seconds() - t_start;
     int first_bad = MMEE_OK;
     for (size_t s = 0; s < passes.size(); ++s) {
@@ -732,7 +772,8 @@ static int walk_front(const mmee_chain *w, const mmee_hw *hw, bool bs_da, uint32
     uint64_t evaluated = 0;
     for (uint32_t k = 0;; ++k) {
         uint64_t ev = 0;
-        rc = enqueue_search(p, bs_da ? 1 : 4, flags, 0, &ev, &limit, k == 0, bs_da);
+        bool unproven = false;
+        rc = enqueue_search(p, bs_da ? 1 : 4, flags, 0, &ev, &limit, k == 0, bs_da, &unproven);
         if (rc) return rc;
         HIP_TRY(hipStreamSynchronize(S.stream));
         float ms = 0.f;
@@ -742,6 +783,15 @@ static int walk_front(const mmee_chain *w, const mmee_hw *hw, bool bs_da, uint32
         mmee_result r;
         rc = unpack_result(p, 0, bs_da ? 0 : MMEE_OBJ_LATENCY_THEN_ENERGY, 0, 0.0, 0.0, &r);
         if (rc == MMEE_ENOFEASIBLE) break;          // nothing below the bound is left: the front is complete
+        if (unproven && !(r.cost.energy_pj < REGROUP_PROOF_LIMIT)) {
+            // the regrouped sum was taken on trust and this point does not prove it (energies fall
+            // along the front, so only its first point can): start again, term by term
+            flags |= MMEE_SEARCH_ORDERED_SUM;
+            limit = INFINITY;
+            *n_points = 0;
+            k = (uint32_t)-1;
+            continue;
+        }
         if (k == capacity) return MMEE_EOVERFLOW;   // out holds the first `capacity` points
         out[k] = r;
         *n_points = k + 1;

@@ -469,3 +469,29 @@ def test_search_random_small_chains_against_oracle_enumeration(M):
                     assert res.best.idx == idx[obj], (c, h, flags, obj)
                     assert res.cost.energy_pj == cost[obj].energy_pj
                     assert res.cost.latency_cycles == cost[obj].latency_cycles
+
+
+def test_regrouped_sum_on_trust_and_its_fallback(M):
+    """Whole-number energies beyond the size bound: the searches start regrouped and keep the result
+    only if the optimal energy is below 2^52 pJ.  Energies so large that it is not (the fallback to
+    the term-by-term sum must kick in) and energies where it is, against the oracle's enumeration."""
+    w, h0 = SMALL[0]
+    ow = O.workload(w)
+    for e_dram, e_mac, proven in ((3.0e12, 1.0, True), (3.0e12, 7.0e13, False)):
+        h = dict(h0, e_dram=e_dram, e_mac=e_mac)
+        assert not M.mmee_energy_regrouped(w, h, M.SEARCH_EXHAUSTIVE)      # not provable beforehand
+        oh = O.hw(h)
+        rc, idx, cost, n_valid, _ = O.search_all(ow, oh)
+        assert rc == 0 and n_valid > 0
+        assert (cost[0].energy_pj < 2.0 ** 52) == proven
+        for flags in (M.SEARCH_EXHAUSTIVE, M.SEARCH_PRUNED, M.SEARCH_EXHAUSTIVE | M.SEARCH_ORDERED_SUM):
+            singles = [M.mmee_search_ex(w, h, obj, flags) for obj in range(4)]
+            multi = M.mmee_search_multi(w, h, [0, 1, 2], flags)
+            for obj in range(4):
+                for res in [singles[obj]] + ([multi[obj]] if obj < 3 else []):
+                    assert res.best.idx == idx[obj], (e_mac, flags, obj)
+                    assert res.cost.energy_pj == cost[obj].energy_pj
+                    assert res.cost.latency_cycles == cost[obj].latency_cycles
+            code, front = M.mmee_pareto(w, h, flags)
+            ocode, oidx, _ = O.pareto(ow, oh)
+            assert code == 0 and [p.best.idx for p in front] == list(oidx), (e_mac, flags)
