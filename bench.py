@@ -38,9 +38,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/*.md), scaled by what the
 # same counters read for a 1 GiB device-to-device copy (x2.0 and x1.0).  Valid only for the kernel
 # sources they were taken with: any change to the sources turns "traffic" into null.
-COUNTERS_TAKEN_WITH = "3aa8af7e4045a790e565a4e48034f8c8ebddc9db8ddf9842349f06499c923459"
-SEARCH_TRAFFIC_BYTES = 27823.1 * 1024 * 2.0 + 325.1 * 1024 * 1.0
-EVAL_TRAFFIC_BYTES = 22119.5 * 1024 * 2.0 + 4197422.4 * 1024 * 1.0
+COUNTERS_TAKEN_WITH = "b0b8c5fa694cfc05fb8c67ef961c34def2104c105b0c8ee023167c3e0c6ea0f6"
+SEARCH_TRAFFIC_BYTES = 28572.4 * 1024 * 2.0 + 325.1 * 1024 * 1.0
+EVAL_TRAFFIC_BYTES = 22346.9 * 1024 * 2.0 + 4197505.2 * 1024 * 1.0
 
 
 def kernel_sources_digest():
