@@ -20,8 +20,10 @@
  * Fig. 11 example (buffer-size and DRAM-access estimation), the MAC and softmax counts of Sec. V-D, the compute-bound
  * latencies of Table II, the single-tile special case, and a stage-by-stage
  * loop-nest simulator (sim.c).  The GB<->RF traffic term and the unfused
- * variant are pinned by brute force only (the paper prints no formula for
- * them): parity unpinned against the paper for those two.
+ * variant are pinned by brute force (fold-by-fold enumeration of a tile matmul on
+ * the PE array; the simulator's DRAM counts with C staged through DRAM).  The
+ * paper prints neither a formula nor a value for these two, so what they are
+ * pinned to is this build's reading of its description, not a number of the paper.
  */
 #include <math.h>
 #include <stdint.h>
