@@ -60,6 +60,27 @@ struct State {
     uint32_t resident_blocks = 512;
 } S;
 
+// The device buffers one search pass works in.  The allocating entry points fill this from the
+// cached State; the entry point that allocates nothing fills it from the static scratch array.
+struct Bufs {
+    const uint4 *enc = nullptr;
+    const uint32_t *rows[2] = {nullptr, nullptr};
+    const uint4 *row_enc[2] = {nullptr, nullptr};
+    uint32_t counts[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+    const uint32_t *cls_dev = nullptr;          // null: no class list, the dense kernel is not used
+    uint32_t n_cls = 0;
+    double *btab = nullptr, *ctab_s = nullptr;
+    uint64_t *ctab_e = nullptr;
+    Key *partials = nullptr;
+    size_t partials_cap = 0;                    // blocks the partial records have room for
+    uint32_t *ticket = nullptr;                 // [0] finish ticket, [1] work counter
+    Key *key_dev = nullptr;
+    FinalRecord *final_dev = nullptr;           // device address of this pass's N_OBJ records
+    DivTable *dv_dev = nullptr;                 // this pass's copy of the divisor lists
+    hipEvent_t ev_begin = nullptr, ev_end = nullptr;   // null: the pass is not timed
+    uint32_t resident_blocks = 512;
+};
+
 // ---- argument checking and the per-call plan ---------------------------------
 
 struct Plan {
@@ -191,12 +212,14 @@ int ensure_ready()
     HIP_TRY(hipMalloc(&S.counts_dev, sizeof(uint32_t) * 8));
     HIP_TRY(hipMalloc(&S.key_dev, sizeof(Key) * N_OBJ));
     HIP_TRY(hipMalloc(&S.ticket, 2 * sizeof(uint32_t)));        // [0] finish ticket, [1] work counter
-    HIP_TRY(hipMemset(S.ticket, 0, 2 * sizeof(uint32_t)));
-    HIP_TRY(hipMemset(S.rows[0], 0, sizeof(uint32_t) * N_DFROWS));
-    HIP_TRY(hipMemset(S.rows[1], 0, sizeof(uint32_t) * N_DFROWS));
+    // on the library's stream, like the kernels that follow: a caller's non-blocking stream is not
+    // ordered against the null stream
+    HIP_TRY(hipMemsetAsync(S.ticket, 0, 2 * sizeof(uint32_t), S.stream));
+    HIP_TRY(hipMemsetAsync(S.rows[0], 0, sizeof(uint32_t) * N_DFROWS, S.stream));
+    HIP_TRY(hipMemsetAsync(S.rows[1], 0, sizeof(uint32_t) * N_DFROWS, S.stream));
     for (int w = 0; w < 2; ++w) {
         HIP_TRY(hipMalloc(&S.row_enc[w], sizeof(uint4) * N_DFROWS));
-        HIP_TRY(hipMemset(S.row_enc[w], 0, sizeof(uint4) * N_DFROWS));
+        HIP_TRY(hipMemsetAsync(S.row_enc[w], 0, sizeof(uint4) * N_DFROWS, S.stream));
     }
     // offline stage: encode every (order, levels, r, f) row, prune, compact
     hipLaunchKernelGGL(k_build_rows, dim3((N_DFROWS + 255) / 256), dim3(256), 0, S.stream, S.enc, S.sig);
@@ -302,13 +325,37 @@ ModelConst pass_constants(const Plan &p, uint32_t flags, int mask = 8, bool *unp
     return mc;
 }
 
-int launch_tilings(const Plan &p, const ModelConst &mc, DivTable *dv_copy = nullptr)
+// the tables of one problem into b's table buffers (which must hold mc.tpad tilings)
+int launch_tilings(const Plan &p, const ModelConst &mc, const Bufs &b, DivTable *dv_copy = nullptr)
 {
-    int rc = ensure_tilings(mc.tpad);
-    if (rc) return rc;
-    hipLaunchKernelGGL(k_build_tilings, dim3(mc.tpad / 64), dim3(64 * BUILD_PARTS), 0, S.stream, p.dv, mc, S.btab,
-                       S.ctab_s, S.ctab_e, dv_copy);
+    hipLaunchKernelGGL(k_build_tilings, dim3(mc.tpad / 64), dim3(64 * BUILD_PARTS), 0, S.stream, p.dv, mc, b.btab,
+                       b.ctab_s, b.ctab_e, dv_copy);
     HIP_TRY(hipGetLastError());
+    return MMEE_OK;
+}
+
+// the cached, growing buffers of the allocating entry points, for the pass in result slot `slot`
+int state_bufs(const Plan &p, size_t slot, Bufs &b)
+{
+    if (slot >= S.slots) return MMEE_EINVAL;
+    int rc = ensure_tilings(p.mc.tpad);
+    if (rc) return rc;
+    // persistent blocks: never more than the chip holds at once
+    rc = ensure_partials(S.resident_blocks);
+    if (rc) return rc;
+    b.enc = S.enc;
+    for (int w = 0; w < 2; ++w) {
+        b.rows[w] = S.rows[w]; b.row_enc[w] = S.row_enc[w];
+        for (int g = 0; g < 4; ++g) b.counts[w][g] = S.counts[w][g];
+    }
+    b.cls_dev = S.cls_dev; b.n_cls = S.n_cls;
+    b.btab = S.btab; b.ctab_s = S.ctab_s; b.ctab_e = S.ctab_e;
+    b.partials = S.partials; b.partials_cap = S.partials_cap;
+    b.ticket = S.ticket; b.key_dev = S.key_dev;
+    b.final_dev = S.final_map + N_OBJ * slot;
+    b.dv_dev = S.dv_dev + slot;
+    b.ev_begin = S.events[2 * slot]; b.ev_end = S.events[2 * slot + 1];
+    b.resident_blocks = S.resident_blocks;
     return MMEE_OK;
 }
 
@@ -353,19 +400,18 @@ void launch_dense_limited(bool exact_k, dim3 grid, const SearchArgs &a)
     else hipLaunchKernelGGL((k_search_dense<2, false, true>), grid, dim3(DENSE_THREADS), 0, S.stream, a);
 }
 
-// enqueue one pass (tables + search + readback of the final records) into slot `slot`
-int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_t *evaluated,
-                   const double *e_limit = nullptr, bool build_tables = true, bool bs_da_step = false,
-                   bool *unproven = nullptr)
+// enqueue one pass (tables + search; the final records land in b.final_dev) in the buffers b
+int enqueue_search_in(const Bufs &B, const Plan &p, int mask, uint32_t flags, uint64_t *evaluated,
+                      const double *e_limit = nullptr, bool build_tables = true, bool bs_da_step = false,
+                      bool *unproven = nullptr)
 {
-    if (slot >= S.slots) return MMEE_EINVAL;
     const ModelConst mc = pass_constants(p, flags, bs_da_step ? 8 : mask, unproven);
-    int rc = build_tables ? launch_tilings(p, mc, S.dv_dev + slot) : MMEE_OK;
+    int rc = build_tables ? launch_tilings(p, mc, B, B.dv_dev) : MMEE_OK;
     if (rc) return rc;
     const int which = (flags & MMEE_SEARCH_EXHAUSTIVE) ? 0 : 1;
     SearchArgs a;
     std::memset(&a, 0, sizeof(a));
-    a.enc = S.enc; a.rows = S.rows[which]; a.row_enc = S.row_enc[which];
+    a.enc = B.enc; a.rows = B.rows[which]; a.row_enc = B.row_enc[which];
     // rows: one slot numbering per recomputation class r, over the lists of (r, f=0) and (r, f=1)
     uint32_t rb = 0;
     uint64_t nrows = 0;
@@ -374,8 +420,8 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
         for (uint32_t f = 0; f < 2; ++f) {
             const uint32_t g = r + 2 * f;
             a.cls_off[r][f] = g * ROWS_PER_GROUP;
-            a.cls_cnt[r][f] = S.counts[which][g];
-            in_class += S.counts[which][g];
+            a.cls_cnt[r][f] = B.counts[which][g];
+            in_class += B.counts[which][g];
         }
         if (r == 0) a.rb_split = (in_class + SEARCH_THREADS - 1) / SEARCH_THREADS;
         rb += (in_class + SEARCH_THREADS - 1) / SEARCH_THREADS;
@@ -393,26 +439,26 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
         // (short lists split an item's tilings over the waves instead: short chunks only while one
         // round of blocks takes them all)
         const uint64_t all_fine = (p.T + TC_FINE - 1) / TC_FINE;
-        const uint64_t fine_chunks_wanted = short_lists ? (rb * all_fine <= S.resident_blocks ? all_fine : 0)
-                                                        : (4ull * S.resident_blocks + rb - 1) / rb;
+        const uint64_t fine_chunks_wanted = short_lists ? (rb * all_fine <= B.resident_blocks ? all_fine : 0)
+                                                        : (4ull * B.resident_blocks + rb - 1) / rb;
         const uint64_t fine_tilings = std::min<uint64_t>(p.T, fine_chunks_wanted * TC_FINE);
         a.n_cc = (uint32_t)((p.T - fine_tilings) / TC);
         a.n_fc = (uint32_t)((p.T - (uint64_t)a.n_cc * TC + TC_FINE - 1) / TC_FINE);
     }
-    a.btab = S.btab; a.ctab_s = S.ctab_s; a.ctab_e = S.ctab_e;
+    a.btab = B.btab; a.ctab_s = B.ctab_s; a.ctab_e = B.ctab_e;
     a.mc = mc;
     // One key over the full row set goes through the dense kernel (lane = tiling, wave = 125 rows of
     // a class).  With several keys its accumulators no longer fit four waves per SIMD, and the
     // row-per-lane kernel is the faster one.
-    const bool dense = which == 0 && !bs_da_step && (mask & (mask - 1)) == 0;
+    const bool dense = which == 0 && !bs_da_step && (mask & (mask - 1)) == 0 && B.cls_dev;
     uint64_t n_items;
     if (dense) {
-        a.cls = S.cls_dev; a.n_cls = S.n_cls;
+        a.cls = B.cls_dev; a.n_cls = B.n_cls;
         const uint32_t n_chunks = (uint32_t)((p.T + TC - 1) / TC);
-        a.d_gc = (S.n_cls * 5 + DENSE_WAVES - 1) / DENSE_WAVES;
-        a.d_gf = (S.n_cls * 25 + DENSE_WAVES - 1) / DENSE_WAVES;
+        a.d_gc = (B.n_cls * 5 + DENSE_WAVES - 1) / DENSE_WAVES;
+        a.d_gf = (B.n_cls * 25 + DENSE_WAVES - 1) / DENSE_WAVES;
         // fifths of tasks for the last chunks: about one whole-task item per resident block
-        const uint32_t dense_blocks = S.resident_blocks / BLOCKS_PER_CU * DENSE_BLOCKS_PER_CU;
+        const uint32_t dense_blocks = B.resident_blocks / BLOCKS_PER_CU * DENSE_BLOCKS_PER_CU;
         const uint32_t fine_chunks = std::min<uint32_t>(n_chunks, (dense_blocks + a.d_gc - 1) / a.d_gc);
         a.d_ncc = n_chunks - fine_chunks;
         a.n_coarse_items = a.d_ncc * a.d_gc;
@@ -425,13 +471,12 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     a.n_items = (uint32_t)n_items;
     // persistent blocks: as many as the chip holds at once (LDS allows two per CU)
     const uint64_t nblocks = std::min<uint64_t>(
-        n_items, dense ? (uint64_t)S.resident_blocks / BLOCKS_PER_CU * DENSE_BLOCKS_PER_CU : (uint64_t)S.resident_blocks);
-    rc = ensure_partials(nblocks);
-    if (rc) return rc;
-    a.partials = S.partials; a.ticket = S.ticket; a.work_counter = S.ticket + 1;
-    a.final_out = S.final_map + N_OBJ * slot;
-    a.dv = S.dv_dev + slot;
-    HIP_TRY(hipEventRecord(S.events[2 * slot], S.stream));
+        n_items, dense ? (uint64_t)B.resident_blocks / BLOCKS_PER_CU * DENSE_BLOCKS_PER_CU : (uint64_t)B.resident_blocks);
+    if (nblocks > B.partials_cap) return MMEE_EINVAL;
+    a.partials = B.partials; a.ticket = B.ticket; a.work_counter = B.ticket + 1;
+    a.final_out = B.final_dev;
+    a.dv = B.dv_dev;
+    if (B.ev_begin) HIP_TRY(hipEventRecord(B.ev_begin, S.stream));
     dim3 grid((uint32_t)nblocks);
     if (bs_da_step) {
         if (!e_limit) return MMEE_EINVAL;
@@ -444,9 +489,9 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
             // two scalar passes, as for the unbounded key below; the second needs no energy bound: the
             // lowest energy among the candidates within the latency found is below it
             SearchArgs first = a, second = a;
-            first.final_key_dev = S.key_dev;
+            first.final_key_dev = B.key_dev;
             launch_dense_limited(p.exact_k, grid, first);
-            second.lat_cap = S.key_dev + 1;
+            second.lat_cap = B.key_dev + 1;
             second.final_out = a.final_out + 2;
             launch_dense_latcap(p.exact_k, grid, second);
         } else
@@ -458,9 +503,9 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
         // combination part, so the cap applies to the two separately).  The second pass's energy
         // record lands in the slot of this key.
         SearchArgs first = a, second = a;
-        first.final_key_dev = S.key_dev;
+        first.final_key_dev = B.key_dev;
         launch_dense_mask<2>(p.exact_k, grid, first);
-        second.lat_cap = S.key_dev + 1;
+        second.lat_cap = B.key_dev + 1;
         second.final_out = a.final_out + 2;
         launch_dense_latcap(p.exact_k, grid, second);
     } else if (dense)
@@ -491,9 +536,20 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     default: return MMEE_EINVAL;
     }
     HIP_TRY(hipGetLastError());
-    HIP_TRY(hipEventRecord(S.events[2 * slot + 1], S.stream));
+    if (B.ev_end) HIP_TRY(hipEventRecord(B.ev_end, S.stream));
     *evaluated = nrows * p.T * (bs_da_step ? 1ull : 9ull);
     return MMEE_OK;
+}
+
+// the same in the cached buffers of the allocating entry points, result slot `slot`
+int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_t *evaluated,
+                   const double *e_limit = nullptr, bool build_tables = true, bool bs_da_step = false,
+                   bool *unproven = nullptr)
+{
+    Bufs b;
+    int rc = state_bufs(p, slot, b);
+    if (rc) return rc;
+    return enqueue_search_in(b, p, mask, flags, evaluated, e_limit, build_tables, bs_da_step, unproven);
 }
 
 int unpack_result(const Plan &p, size_t slot, int objective, uint64_t evaluated, double seconds, double ksec,
@@ -523,7 +579,6 @@ double now_seconds()
 {
     return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
 }
-
 }  // namespace
 }  // namespace mmee
 
@@ -607,7 +662,11 @@ int mmee_chain_eval_batch(const mmee_chain *w, const mmee_hw *hw, uint64_t first
     std::lock_guard<std::mutex> guard(g_lock);
     rc = ensure_ready();
     if (rc) return rc;
-    rc = launch_tilings(p, p.mc);
+    rc = ensure_tilings(p.mc.tpad);
+    if (rc) return rc;
+    Bufs tables;
+    tables.btab = S.btab; tables.ctab_s = S.ctab_s; tables.ctab_e = S.ctab_e;
+    rc = launch_tilings(p, p.mc, tables);
     if (rc) return rc;
 
     hipPointerAttribute_t attr;
@@ -673,12 +732,13 @@ int mmee_chain_search_many(const mmee_chain *w, const mmee_hw *hw, const int *ob
         uint32_t b = a;
         while (b < count && same_problem(w[a], hw[a], w[b], hw[b])) {
             int o = objectives[b];
-            if (o < 0 || o >= N_OBJ) { if (!ps.rc) ps.rc = MMEE_EINVAL; }
+            if (o < 0 || o >= N_OBJ) codes[b] = MMEE_EINVAL;     // this entry only; its neighbours still run
             else if (ps.mask & (1 << o)) break;      // same objective twice: start a new pass
             else ps.mask |= 1 << o;
             ++b; ++ps.n;
         }
         if (ps.n == 0) { ps.n = 1; b = a + 1; }
+        if (ps.mask == 0 && !ps.rc) ps.rc = MMEE_EINVAL;         // no valid objective in the group
         passes.push_back(ps);
         a = b;
     }
@@ -723,7 +783,7 @@ int mmee_chain_search_many(const mmee_chain *w, const mmee_hw *hw, const int *ob
         float ms = 0.f;
         if (ps.rc == MMEE_OK) (void)hipEventElapsedTime(&ms, S.events[2 * s], S.events[2 * s + 1]);
         for (uint32_t a = ps.first; a < ps.first + ps.n; ++a) {
-            int code = ps.rc;
+            int code = codes[a] ? codes[a] : ps.rc;
             if (code == MMEE_OK)
                 code = unpack_result(ps.plan, s, objectives[a], ps.evaluated, seconds, ms * 1e-3, out + a);
             else
