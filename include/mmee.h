@@ -141,7 +141,8 @@ enum {
     MMEE_ERANGE = -2,       /* index range outside [0, space)                                 */
     MMEE_ENOFEASIBLE = -3,  /* every candidate is masked; out->cost.valid = 0                 */
     MMEE_EDEVICE = -4,      /* HIP error or no device                                         */
-    MMEE_EOVERFLOW = -5     /* mmee_pareto: more front points than `capacity`                 */
+    MMEE_EOVERFLOW = -5,    /* mmee_pareto: more front points than `capacity`                 */
+    MMEE_ETOOBIG = -6       /* mmee_search_noalloc: the problem exceeds its fixed scratch     */
 };
 
 /* Number of candidates of (workload, hw): #tilings (integer factorisations, Sec. VI-A)
@@ -214,6 +215,28 @@ int mmee_chain_pareto(const mmee_chain *c, const mmee_hw *hw, uint32_t flags, mm
                       uint32_t capacity, uint32_t *n_points);
 int mmee_chain_front_bs_da(const mmee_chain *c, const mmee_hw *hw, uint32_t flags, mmee_result *out,
                            uint32_t capacity, uint32_t *n_points);
+
+/* mmee_search_ex for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  This call allocates and frees nothing, on the host
+ * side of HIP or on the device, and does not synchronise: it enqueues a handful of kernels on the
+ * library's stream (mmee_set_stream) and returns.  All its working memory (row encodings, the
+ * per-tiling tables, partial records) is one fixed array of at most 40 MiB that every GPU the
+ * library is loaded on holds until the process ends; problems with more than 16384 tilings do not
+ * fit and return MMEE_ETOOBIG (mmee_strerror says by how much) with nothing enqueued.
+ *   out_dev   DEVICE pointer (current device) to one mmee_result, written by the last kernel;
+ *             valid once the stream has been synchronised by the caller.  `seconds` and
+ *             `kernel_seconds` are 0.  When no candidate is feasible the call still returns
+ *             MMEE_OK and the record carries cost.valid = 0 (nothing is read back to tell).
+ *   flags     as for mmee_search_ex; the regrouped energy sum is used only where it is exact
+ *             beforehand (mmee_energy_regrouped), never on trust.
+ * The first call on a device runs the offline stage into the array and reads eight counters back
+ * (one synchronisation, still no allocation): make it outside any capture.  All calls on one GPU
+ * share that GPU's array, which keeps the last call's contents; what must start at zero is cleared
+ * by a kernel at the start of each call.  Calls that overlap on one GPU (different streams, or
+ * the same stream replayed while an earlier launch still runs) race; so does this call against
+ * any other search in flight on a different stream. */
+int mmee_search_noalloc(const mmee_workload *w, const mmee_hw *hw, int objective, uint32_t flags,
+                        mmee_result *out_dev);
 
 /* Runs the offline stage if needed (row encoding + symbolic pruning, once per process) and
  * reports its counts. */

@@ -16,7 +16,7 @@ LIB_PATH = os.environ.get("MMEE_LIB") or os.path.join(_HERE, "libmmee.so")
 
 OBJ_ENERGY, OBJ_LATENCY, OBJ_LATENCY_THEN_ENERGY, OBJ_EDP = 0, 1, 2, 3
 SEARCH_PRUNED, SEARCH_EXHAUSTIVE, SEARCH_ORDERED_SUM = 0, 1, 2
-OK, EINVAL, ERANGE, ENOFEASIBLE, EDEVICE, EOVERFLOW = 0, -1, -2, -3, -4, -5
+OK, EINVAL, ERANGE, ENOFEASIBLE, EDEVICE, EOVERFLOW, ETOOBIG = 0, -1, -2, -3, -4, -5, -6
 
 
 class MmeeError(RuntimeError):
@@ -102,6 +102,7 @@ def _load() -> C.CDLL:
     L.mmee_chain_pareto.argtypes = [P(Chain), P(Hw), C.c_uint32, P(Result), C.c_uint32, P(C.c_uint32)]
     L.mmee_front_bs_da.argtypes = [P(Workload), P(Hw), C.c_uint32, P(Result), C.c_uint32, P(C.c_uint32)]
     L.mmee_chain_front_bs_da.argtypes = [P(Chain), P(Hw), C.c_uint32, P(Result), C.c_uint32, P(C.c_uint32)]
+    L.mmee_search_noalloc.argtypes = [P(Workload), P(Hw), C.c_int, C.c_uint32, C.c_void_p]
     L.mmee_offline_stats.argtypes = [P(RowStats)]
     L.mmee_set_stream.argtypes = [C.c_void_p]
     L.mmee_shutdown.argtypes = []
@@ -109,7 +110,7 @@ def _load() -> C.CDLL:
     L.mmee_strerror.argtypes = [C.c_int]
     L.mmee_strerror.restype = C.c_char_p
     for name in ("mmee_space_size", "mmee_decode", "mmee_eval_batch", "mmee_search", "mmee_search_ex",
-                 "mmee_search_multi", "mmee_search_many", "mmee_offline_stats", "mmee_set_stream",
+                 "mmee_search_multi", "mmee_search_many", "mmee_search_noalloc", "mmee_offline_stats", "mmee_set_stream",
                  "mmee_chain_space_size", "mmee_chain_decode", "mmee_chain_eval_batch",
                  "mmee_chain_search_multi", "mmee_chain_search_many", "mmee_pareto", "mmee_chain_pareto",
                  "mmee_front_bs_da", "mmee_chain_front_bs_da"):
@@ -203,6 +204,13 @@ def mmee_search_ex(w, h, objective: int, flags: int = SEARCH_PRUNED, allow_infea
     code = _check(_lib.mmee_search_ex(C.byref(workload(w)), C.byref(hw(h)), objective, flags, C.byref(r)),
                   "mmee_search_ex", allow=(ENOFEASIBLE,) if allow_infeasible else ())
     return (code, r) if allow_infeasible else r
+
+
+def mmee_search_noalloc(w, h, objective: int, flags: int, out_dev: int) -> None:
+    """Enqueue one search that allocates nothing; out_dev is a device pointer to one Result record,
+    valid after the caller has synchronised the library's stream."""
+    _check(_lib.mmee_search_noalloc(C.byref(workload(w)), C.byref(hw(h)), objective, flags,
+                                    C.c_void_p(int(out_dev))), "mmee_search_noalloc")
 
 
 def mmee_search_multi(w, h, objectives, flags: int = SEARCH_PRUNED):

@@ -1574,4 +1574,30 @@ __global__ __launch_bounds__(SEARCH_THREADS, 4) void k_front_step(SearchArgs a)
     finish_grid<1>(a, wave_best, &is_last);
 }
 
+// ---------------------------------------------------------------------------
+// helpers of the entry point that allocates nothing
+
+// words[0 .. n) = 0 (a fill kernel rather than a memset node, so that a caller may capture the launch)
+__global__ void k_clear_words(uint32_t *words, uint32_t n)
+{
+    const uint32_t a = blockIdx.x * blockDim.x + threadIdx.x;
+    if (a < n) words[a] = 0;
+}
+
+// the search's final record -> an mmee_result in the caller's device buffer
+__global__ void k_pack_result(const FinalRecord *fr, uint64_t space, uint64_t evaluated, mmee_result *out)
+{
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    mmee_result r;
+    __builtin_memset(&r, 0, sizeof(r));
+    __builtin_memcpy(&r.cost, fr->cost, sizeof(mmee_cost));
+    __builtin_memcpy(&r.best, fr->map, sizeof(mmee_mapping));
+    r.space = space;
+    r.evaluated = evaluated;
+    r.seconds = 0.0;
+    r.kernel_seconds = 0.0;
+    if (!(fr->key.p < pos_inf())) r.cost.valid = 0;
+    *out = r;
+}
+
 }  // namespace mmee

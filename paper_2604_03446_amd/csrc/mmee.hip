@@ -13,6 +13,38 @@
 
 #include "kernels.h"
 
+// ---- fixed scratch of the entry point that allocates nothing (mmee_search_noalloc) ------------
+// One array per GPU, held from the moment the library is loaded until the process ends.  In host
+// code the array's name is only a stand-in: its device address comes from hipGetSymbolAddress,
+// once per device, and that pointer is what kernels, fills and copies are given.
+namespace mmee {
+namespace noalloc {
+constexpr size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+constexpr uint32_t MAX_TPAD = 16384;        // tilings a problem may have (rounded up to 64)
+constexpr uint32_t MAX_BLOCKS = 1024;       // persistent blocks the partial records have room for
+constexpr size_t OFF_ENC = 0;
+constexpr size_t OFF_SIG = OFF_ENC + up256(sizeof(uint4) * N_DFROWS);
+constexpr size_t OFF_FLAGS = OFF_SIG + up256(sizeof(uint32_t) * N_DFROWS);
+constexpr size_t OFF_ROWS0 = OFF_FLAGS + up256(N_DFROWS);
+constexpr size_t OFF_ROWS1 = OFF_ROWS0 + up256(sizeof(uint32_t) * N_DFROWS);
+constexpr size_t OFF_RENC0 = OFF_ROWS1 + up256(sizeof(uint32_t) * N_DFROWS);
+constexpr size_t OFF_RENC1 = OFF_RENC0 + up256(sizeof(uint4) * N_DFROWS);
+constexpr size_t OFF_COUNTS = OFF_RENC1 + up256(sizeof(uint4) * N_DFROWS);
+constexpr size_t OFF_TICKET = OFF_COUNTS + up256(sizeof(uint32_t) * 8);
+constexpr size_t OFF_KEYS = OFF_TICKET + up256(sizeof(uint32_t) * 2);
+constexpr size_t OFF_PARTIALS = OFF_KEYS + up256(sizeof(Key) * N_OBJ);
+constexpr size_t OFF_FINAL = OFF_PARTIALS + up256(sizeof(Key) * N_OBJ * MAX_BLOCKS);
+constexpr size_t OFF_DV = OFF_FINAL + up256(sizeof(FinalRecord) * N_OBJ);
+constexpr size_t OFF_BTAB = OFF_DV + up256(sizeof(DivTable));
+constexpr size_t OFF_CTAB_S = OFF_BTAB + up256(sizeof(double) * NENT_ALL * MAX_TPAD);
+constexpr size_t OFF_CTAB_E = OFF_CTAB_S + up256(sizeof(double) * 2 * NCS * MAX_TPAD);
+constexpr size_t BYTES = OFF_CTAB_E + up256(sizeof(uint64_t) * 2 * NCE * MAX_TPAD);
+static_assert(BYTES <= (40u << 20), "the fixed scratch is documented as at most 40 MiB");
+}  // namespace noalloc
+}  // namespace mmee
+
+static __device__ __align__(256) unsigned char scratch[mmee::noalloc::BYTES];
+
 namespace mmee {
 namespace {
 
@@ -579,6 +611,61 @@ double now_seconds()
 {
     return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
 }
+
+// ---- the entry point that allocates nothing: per-device set-up of the fixed scratch -----------
+
+constexpr int NOALLOC_MAX_DEVICES = 64;
+struct NoAllocDevice {
+    unsigned char *ptr = nullptr;        // this device's copy of `scratch`
+    bool built = false;                  // offline stage done in it
+    uint32_t counts[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+    uint32_t resident_blocks = 0;
+} g_noalloc[NOALLOC_MAX_DEVICES];
+
+// First call on a device: the address of that device's array, then the offline stage (row encoding,
+// pruning, compaction) into it and its eight counts back to the host.  Nothing is allocated.
+int noalloc_setup(int dev, NoAllocDevice *&out)
+{
+    if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) return MMEE_EINVAL;
+    NoAllocDevice &d = g_noalloc[dev];
+    out = &d;
+    if (d.built) return MMEE_OK;
+    if (!d.ptr) {
+        unsigned char *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch)));
+        if (!ptr) {
+            std::snprintf(g_last_error, sizeof(g_last_error), "hipGetSymbolAddress returned no address for the scratch array");
+            return MMEE_EDEVICE;
+        }
+        d.ptr = ptr;
+    }
+    int cus = 0;
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    d.resident_blocks = std::min<uint32_t>((uint32_t)std::max(cus, 1) * BLOCKS_PER_CU, noalloc::MAX_BLOCKS);
+    unsigned char *q = d.ptr;
+    uint4 *enc = reinterpret_cast<uint4 *>(q + noalloc::OFF_ENC);
+    uint32_t *sig = reinterpret_cast<uint32_t *>(q + noalloc::OFF_SIG);
+    uint8_t *flags = q + noalloc::OFF_FLAGS;
+    uint32_t *rows0 = reinterpret_cast<uint32_t *>(q + noalloc::OFF_ROWS0);
+    uint32_t *rows1 = reinterpret_cast<uint32_t *>(q + noalloc::OFF_ROWS1);
+    uint4 *renc0 = reinterpret_cast<uint4 *>(q + noalloc::OFF_RENC0);
+    uint4 *renc1 = reinterpret_cast<uint4 *>(q + noalloc::OFF_RENC1);
+    uint32_t *counts = reinterpret_cast<uint32_t *>(q + noalloc::OFF_COUNTS);
+    // the row lists must read as zero beyond their ends (lanes without a row read entry 0 of a list)
+    const uint32_t list_words = (uint32_t)((noalloc::OFF_COUNTS - noalloc::OFF_ROWS0) / 4);
+    hipLaunchKernelGGL(k_clear_words, dim3((list_words + 255) / 256), dim3(256), 0, S.stream, rows0, list_words);
+    hipLaunchKernelGGL(k_build_rows, dim3((N_DFROWS + 255) / 256), dim3(256), 0, S.stream, enc, sig);
+    hipLaunchKernelGGL(k_prune_rows, dim3((ROWS_PER_GROUP + 255) / 256, N_GROUPS), dim3(256), 0, S.stream, sig, flags);
+    hipLaunchKernelGGL(k_compact_rows, dim3(8), dim3(1024), 0, S.stream, flags, enc, rows0, rows1, renc0, renc1, counts);
+    HIP_TRY(hipGetLastError());
+    uint32_t h[8];
+    HIP_TRY(hipMemcpyAsync(h, counts, sizeof(h), hipMemcpyDeviceToHost, S.stream));
+    HIP_TRY(hipStreamSynchronize(S.stream));
+    for (int g = 0; g < 4; ++g) { d.counts[0][g] = h[g]; d.counts[1][g] = h[4 + g]; }
+    d.built = true;
+    return MMEE_OK;
+}
+
 }  // namespace
 }  // namespace mmee
 
@@ -963,6 +1050,64 @@ int mmee_search(const mmee_workload *w, const mmee_hw *hw, int objective, mmee_r
     return mmee_search_ex(w, hw, objective, MMEE_SEARCH_PRUNED, out);
 }
 
+int mmee_search_noalloc(const mmee_workload *w, const mmee_hw *hw, int objective, uint32_t flags,
+                        mmee_result *out_dev)
+{
+    if (!out_dev || objective < 0 || objective >= N_OBJ) return MMEE_EINVAL;
+    if (flags & ~(uint32_t)(MMEE_SEARCH_EXHAUSTIVE | MMEE_SEARCH_ORDERED_SUM)) return MMEE_EINVAL;
+    mmee_chain c;
+    int rc = chain_of(w, c);
+    if (rc) return rc;
+    Plan p;
+    rc = make_plan(&c, hw, p);
+    if (rc) return rc;
+    if (p.mc.tpad > noalloc::MAX_TPAD) {
+        std::snprintf(g_last_error, sizeof(g_last_error),
+                      "mmee_search_noalloc: %llu tilings, the fixed scratch holds %u; use mmee_search_ex",
+                      (unsigned long long)p.T, noalloc::MAX_TPAD);
+        return MMEE_ETOOBIG;
+    }
+    std::lock_guard<std::mutex> guard(g_lock);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        std::snprintf(g_last_error, sizeof(g_last_error), "no HIP device");
+        return MMEE_EDEVICE;
+    }
+    NoAllocDevice *d = nullptr;
+    rc = noalloc_setup(dev, d);
+    if (rc) return rc;
+    unsigned char *q = d->ptr;
+    Bufs b;
+    b.enc = reinterpret_cast<const uint4 *>(q + noalloc::OFF_ENC);
+    b.rows[0] = reinterpret_cast<const uint32_t *>(q + noalloc::OFF_ROWS0);
+    b.rows[1] = reinterpret_cast<const uint32_t *>(q + noalloc::OFF_ROWS1);
+    b.row_enc[0] = reinterpret_cast<const uint4 *>(q + noalloc::OFF_RENC0);
+    b.row_enc[1] = reinterpret_cast<const uint4 *>(q + noalloc::OFF_RENC1);
+    for (int k = 0; k < 2; ++k)
+        for (int g = 0; g < 4; ++g) b.counts[k][g] = d->counts[k][g];
+    b.cls_dev = nullptr;                       // row-per-lane kernel for every key
+    b.btab = reinterpret_cast<double *>(q + noalloc::OFF_BTAB);
+    b.ctab_s = reinterpret_cast<double *>(q + noalloc::OFF_CTAB_S);
+    b.ctab_e = reinterpret_cast<uint64_t *>(q + noalloc::OFF_CTAB_E);
+    b.partials = reinterpret_cast<Key *>(q + noalloc::OFF_PARTIALS);
+    b.partials_cap = noalloc::MAX_BLOCKS;
+    b.ticket = reinterpret_cast<uint32_t *>(q + noalloc::OFF_TICKET);
+    b.key_dev = reinterpret_cast<Key *>(q + noalloc::OFF_KEYS);
+    b.final_dev = reinterpret_cast<FinalRecord *>(q + noalloc::OFF_FINAL);
+    b.dv_dev = reinterpret_cast<DivTable *>(q + noalloc::OFF_DV);
+    b.resident_blocks = d->resident_blocks;
+    // the finish ticket and the work counter must start at zero whatever the last call left
+    hipLaunchKernelGGL(k_clear_words, dim3(1), dim3(64), 0, S.stream, b.ticket, 2u);
+    uint64_t evaluated = 0;
+    // the regrouped energy sum only where it is provably exact: nothing is read back to check it
+    rc = enqueue_search_in(b, p, 1 << objective, flags, &evaluated);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_pack_result, dim3(1), dim3(64), 0, S.stream, b.final_dev + objective, p.space, evaluated,
+                       out_dev);
+    HIP_TRY(hipGetLastError());
+    return MMEE_OK;
+}
+
 void mmee_shutdown(void)
 {
     std::lock_guard<std::mutex> guard(g_lock);
@@ -989,6 +1134,7 @@ const char *mmee_strerror(int code)
     case MMEE_ENOFEASIBLE: return "no feasible candidate";
     case MMEE_EDEVICE: return g_last_error[0] ? g_last_error : "HIP device error";
     case MMEE_EOVERFLOW: return "the Pareto front has more points than the caller made room for";
+    case MMEE_ETOOBIG: return g_last_error[0] ? g_last_error : "the problem exceeds the fixed scratch of mmee_search_noalloc";
     default: return "unknown error";
     }
 }
