@@ -71,6 +71,8 @@ class Detail(C.Structure):
 
 class SimResult(C.Structure):
     _fields_ = [("da", C.c_uint64 * 5), ("max_occupancy", C.c_uint64),
+                ("max_reserved", C.c_uint64), ("max_reserved_touch", C.c_uint64),
+                ("footprint", C.c_uint64 * 5), ("n_regions", C.c_uint64),
                 ("macs1", C.c_uint64), ("macs2", C.c_uint64), ("softmax_elems", C.c_uint64),
                 ("stages1", C.c_uint64), ("stages2", C.c_uint64), ("n_stages", C.c_uint64),
                 ("occ_trace", C.c_uint32 * 64),

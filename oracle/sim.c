@@ -15,6 +15,16 @@
  * Operands whose buffering level is the tile itself are released when the
  * other operator takes over; operands buffered at an inter-tile loop are
  * retained (Sec. III-D, Sec. IV-A "Buffering Level").
+ *
+ * Three occupancy counts come out.  `max_occupancy` counts the words really
+ * resident at each stage (blocks fill tile by tile, as in the chart of Fig. 10).
+ * The two reservation counts follow the rule of Sec. IV-A that an operand
+ * buffered at an inter-tile loop gets a space equal to its footprint, allocated
+ * and retained: the footprint of such an operand is MEASURED as the largest fill
+ * its block ever reaches during the run (no closed form), and that space counts
+ * in full either from the start to the end of the run (`max_reserved`, static
+ * allocation) or from the block's first use on (`max_reserved_touch`).  Operands
+ * at tile level and the intermediate C count as they are resident in all three.
  */
 #include <stdint.h>
 #include <string.h>
@@ -26,6 +36,10 @@ enum { SI = 0, SK = 1, SL = 2, SJ = 3 };
 typedef struct {
     uint64_t da[5];             /* words moved DRAM<->buffer for A,B,C,D,E */
     uint64_t max_occupancy;     /* peak words resident over all stages     */
+    uint64_t max_reserved;      /* peak with retained operands' measured footprints reserved throughout */
+    uint64_t max_reserved_touch;/* the same, each footprint reserved from its block's first use on      */
+    uint64_t footprint[5];      /* largest fill of each operand's block (A,B,C,D,E), words              */
+    uint64_t n_regions;         /* iterations of the loops shared by both operators                      */
     uint64_t macs1, macs2;      /* MACs executed by Op1 and Op2            */
     uint64_t softmax_elems;     /* elements of C sent through softmax      */
     uint64_t stages1, stages2;  /* tile-pair multiplications               */
@@ -44,6 +58,7 @@ typedef struct {
     uint8_t have[SIM_MAX_D][SIM_MAX_D];
     uint64_t tile_words;
     uint64_t occ;               /* words currently resident                */
+    uint64_t peak;              /* largest occ so far                      */
     uint64_t moved;             /* words moved over the DRAM boundary      */
 } sim_operand;
 
@@ -73,6 +88,7 @@ static void opd_touch(sim_operand *o, const int v[4])
         o->have[c0][c1] = 1;
         o->occ += o->tile_words;
         o->moved += o->tile_words;
+        if (o->occ > o->peak) o->peak = o->occ;
     }
 }
 
@@ -87,9 +103,11 @@ static int odo_next(const uint8_t *loops, int n, const uint32_t xD[4], int v[4])
     return 0;
 }
 
-int sim_run(const uint32_t xG[4], const uint32_t xD[4], const uint8_t order[4],
-            const uint8_t level[4] /* A,B,D,E */, int recompute, int fused,
-            sim_result *out)
+/* One execution of the stage program.  reserve = NULL: plain run.  Otherwise reserve[A,B,C,D,E]
+ * holds the footprints measured by an earlier run and the two reservation counts are taken. */
+static int sim_pass(const uint32_t xG[4], const uint32_t xD[4], const uint8_t order[4],
+                    const uint8_t level[4] /* A,B,D,E */, int recompute, int fused,
+                    const uint64_t *reserve, sim_result *out)
 {
     memset(out, 0, sizeof(*out));
     for (int q = 0; q < 4; ++q)
@@ -132,16 +150,30 @@ int sim_run(const uint32_t xG[4], const uint32_t xD[4], const uint8_t order[4],
     memset(done, 0, sizeof(done));
     uint64_t c_occ = 0;
 
-    uint64_t n_stage = 0, max_occ = 0;
+    uint64_t n_stage = 0, max_occ = 0, max_res = 0, max_touch = 0, c_peak = 0, n_regions = 0;
+    sim_operand *ext[4] = {&A, &B, &D, &E};
+    const int ext_slot[4] = {0, 1, 3, 4};
 #define RECORD_STAGE() do { \
         uint64_t occ_ = A.occ + B.occ + D.occ + E.occ + Cw.occ + Cr.occ + c_occ; \
         if (occ_ > max_occ) max_occ = occ_; \
+        if (c_occ > c_peak) c_peak = c_occ; \
         if (n_stage < SIM_TRACE) out->occ_trace[n_stage] = (uint32_t)occ_; \
+        if (reserve) { \
+            /* tile-level operands and C as they are resident; retained operands by footprint */ \
+            uint64_t dyn_ = Cw.occ + Cr.occ + c_occ, all_ = 0, touched_ = 0; \
+            for (int x_ = 0; x_ < 4; ++x_) { \
+                if (ext[x_]->level == 0) dyn_ += ext[x_]->occ; \
+                else { all_ += reserve[ext_slot[x_]]; if (ext[x_]->resident) touched_ += reserve[ext_slot[x_]]; } \
+            } \
+            if (all_ + dyn_ > max_res) max_res = all_ + dyn_; \
+            if (touched_ + dyn_ > max_touch) max_touch = touched_ + dyn_; \
+        } \
         ++n_stage; } while (0)
 
     int v[4] = {0, 0, 0, 0};
     int first_region = 1;
     do {    /* iterations of the shared leading loops */
+        ++n_regions;
         /* ---- the producer takes over ---- */
         if (!first_region) {
             if (level[2] == 0) opd_drop(&D);
@@ -206,7 +238,31 @@ int sim_run(const uint32_t xG[4], const uint32_t xD[4], const uint8_t order[4],
         out->da[2] = Cw.moved + Cr.moved + 2 * IL;
     }
     out->max_occupancy = max_occ;
+    out->max_reserved = max_res;
+    out->max_reserved_touch = max_touch;
+    out->footprint[0] = A.peak; out->footprint[1] = B.peak;
+    out->footprint[2] = fused ? c_peak : (Cw.peak > Cr.peak ? Cw.peak : Cr.peak);
+    out->footprint[3] = D.peak; out->footprint[4] = E.peak;
+    out->n_regions = n_regions;
     out->n_stages = n_stage;
+    return 0;
+}
+
+int sim_run(const uint32_t xG[4], const uint32_t xD[4], const uint8_t order[4],
+            const uint8_t level[4] /* A,B,D,E */, int recompute, int fused,
+            sim_result *out)
+{
+    /* first run: what happens, and how large each operand's block gets */
+    sim_result first;
+    int rc = sim_pass(xG, xD, order, level, recompute, fused, 0, &first);
+    if (rc) { memset(out, 0, sizeof(*out)); return rc; }
+    /* second run of the same program with those footprints reserved */
+    rc = sim_pass(xG, xD, order, level, recompute, fused, first.footprint, out);
+    if (rc) return rc;
+    /* the two runs are the same program: everything but the reservation counts agrees */
+    if (out->max_occupancy != first.max_occupancy || out->n_stages != first.n_stages) return -2;
+    for (int x = 0; x < 5; ++x)
+        if (out->da[x] != first.da[x] || out->footprint[x] != first.footprint[x]) return -2;
     return 0;
 }
 
