@@ -50,7 +50,7 @@ typedef struct mmee_workload {
     uint32_t reserved;      /* must be 0                                                   */
 } mmee_workload;
 
-/* Two chained matrix multiplications of free shape (Sec. VII-H, Table V: two GEMMs, or a
+/* Two chained matrix multiplications of free shape (Sec. VII-J, Table V: two GEMMs, or a
  * convolution chain turned into GEMMs by im2col): Op1 is I x K x L, Op2 is I x L x J, `batch`
  * independent instances.  An attention workload is the chain I = L = N, K = J = d, batch = B*H;
  * every mmee_* call on a workload is the mmee_chain_* call on that chain. */
@@ -117,7 +117,7 @@ enum {
     MMEE_OBJ_ENERGY = 0,                /* key (energy, idx)            */
     MMEE_OBJ_LATENCY = 1,               /* key (latency, idx)           */
     MMEE_OBJ_LATENCY_THEN_ENERGY = 2,   /* key (latency, energy, idx)   */
-    MMEE_OBJ_EDP = 3                    /* key (energy * latency, idx), the energy-delay product (Sec. VII-I) */
+    MMEE_OBJ_EDP = 3                    /* key (energy * latency, idx), the energy-delay product (Sec. VII-K) */
 };
 
 enum {
@@ -155,7 +155,9 @@ int mmee_space_size(const mmee_workload *w, const mmee_hw *hw, uint64_t *out);
  * host arithmetic. */
 int mmee_energy_regrouped(const mmee_workload *w, const mmee_hw *hw, uint32_t flags, int *out);
 
-/* On-device mixed-radix decode of n candidate indices (host arrays in and out). */
+/* On-device mixed-radix decode of n candidate indices (host arrays in and out): index -> loop
+ * boundaries, loop order, buffering levels and options, the components of a pseudo nested loop
+ * (Sec. IV-A).  A helper next to the three calls of the problem statement. */
 int mmee_decode(const mmee_workload *w, const mmee_hw *hw, const uint64_t *idx, uint64_t n,
                 mmee_mapping *out);
 
@@ -172,18 +174,19 @@ int mmee_search_ex(const mmee_workload *w, const mmee_hw *hw, int objective, uin
                    mmee_result *out);
 
 /* One pass over the space that reduces n_obj (1..4, distinct) objectives at once: all
- * metrics of a candidate are formed once and shared (Sec. VII-C).  out holds n_obj results. */
+ * metrics of a candidate are formed once and shared (Sec. VII-D).  out holds n_obj results. */
 int mmee_search_multi(const mmee_workload *w, const mmee_hw *hw, const int *objectives,
                       uint32_t n_obj, uint32_t flags, mmee_result *out);
 
-/* count independent searches (arrays of count workloads, hws, objectives, results) enqueued
+/* A helper for sweeps over hardware designs and sequence lengths (Sec. VII-I, Table IV; Sec. VII-H):
+ * count independent searches (arrays of count workloads, hws, objectives, results) enqueued
  * back to back on one stream with a single synchronisation at the end.  Neighbouring entries
  * with identical workload and hw share one pass.  Returns the first non-zero per-entry code
  * (per-entry codes are stored in rc[i] when rc is not null). */
 int mmee_search_many(const mmee_workload *w, const mmee_hw *hw, const int *objectives,
                      uint32_t count, uint32_t flags, mmee_result *out, int *rc);
 
-/* Energy-latency Pareto front (Sec. VI-A, Sec. VII-C): the feasible candidates that no other
+/* Energy-latency Pareto front (Sec. VI-A, Sec. VII-E): the feasible candidates that no other
  * candidate beats in both metrics; among candidates with identical (energy, latency) the lowest
  * index stands for all.  out receives at most `capacity` points by ascending latency (descending
  * energy), *n_points their number.  Each point costs one pass over the space.  Returns
@@ -191,7 +194,7 @@ int mmee_search_many(const mmee_workload *w, const mmee_hw *hw, const int *objec
 int mmee_pareto(const mmee_workload *w, const mmee_hw *hw, uint32_t flags, mmee_result *out,
                 uint32_t capacity, uint32_t *n_points);
 
-/* DRAM access versus buffer size requirement (Sec. VII-B): the dataflows that no other dataflow
+/* DRAM access versus buffer size requirement (Sec. VII-C): the dataflows that no other dataflow
  * beats in both Eq. (4) and Eq. (7), whatever the buffer capacity of hw (their cost records carry
  * valid = 0, reason = 2 where they exceed it).  Neither metric depends on the stationary modes;
  * the lowest index stands for equal pairs.  Points come by ascending buffer size (descending
@@ -199,7 +202,7 @@ int mmee_pareto(const mmee_workload *w, const mmee_hw *hw, uint32_t flags, mmee_
 int mmee_front_bs_da(const mmee_workload *w, const mmee_hw *hw, uint32_t flags, mmee_result *out,
                      uint32_t capacity, uint32_t *n_points);
 
-/* The same calls for a free chain shape (Sec. VII-H).  Semantics, layouts and error codes are
+/* The same calls for a free chain shape (Sec. VII-J).  Semantics, layouts and error codes are
  * those of the workload calls above. */
 int mmee_chain_space_size(const mmee_chain *c, const mmee_hw *hw, uint64_t *out);
 int mmee_chain_energy_regrouped(const mmee_chain *c, const mmee_hw *hw, uint32_t flags, int *out);
@@ -241,6 +244,13 @@ int mmee_search_noalloc(const mmee_workload *w, const mmee_hw *hw, int objective
 /* Runs the offline stage if needed (row encoding + symbolic pruning, once per process) and
  * reports its counts. */
 int mmee_offline_stats(mmee_row_stats *out);
+
+/* The offline stage's row lists (Sec. VI-A "enumerated offline", Sec. VI-B): the rows of group
+ * g = r + 2 f that denote a dataflow (which = 0) or that survive the symbolic pruning of Eq. (12)
+ * (which = 1), ascending, as row numbers inside the group: p_A + 5 p_B + 25 p_D + 125 p_E +
+ * 625 * order.  rows_out (host) receives at most `capacity` numbers, *n_rows the length of the
+ * list; MMEE_EOVERFLOW when the list is longer than `capacity`. */
+int mmee_offline_rows(uint32_t group, uint32_t which, uint32_t *rows_out, uint32_t capacity, uint32_t *n_rows);
 
 /* Use this HIP stream (a hipStream_t passed as void*) for all later launches; NULL = default. */
 int mmee_set_stream(void *hip_stream);

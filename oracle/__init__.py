@@ -11,7 +11,7 @@ import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liboracle.so")
-SOURCES = [os.path.join(_HERE, "oracle.c"), os.path.join(_HERE, "sim.c")]
+SOURCES = [os.path.join(_HERE, "oracle.c"), os.path.join(_HERE, "sim.c"), os.path.join(_HERE, "offline.c")]
 
 
 def build(force: bool = False) -> str:
@@ -112,6 +112,9 @@ def lib() -> C.CDLL:
         L.sim_tile_matmul.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_int,
                                       C.c_uint32, C.c_uint32, C.c_uint32,
                                       P(C.c_uint64), P(C.c_uint64), P(C.c_uint64)]
+        L.orc_offline_rows.argtypes = [C.c_int, C.c_int, P(C.c_uint32), P(C.c_uint32), P(C.c_uint32),
+                                       P(C.c_uint32), P(C.c_uint32)]
+        L.orc_offline_rows.restype = C.c_int
         for name in ("orc_from_attention", "orc_space_size", "orc_decode", "orc_eval", "orc_eval_mapping",
                      "orc_eval_batch", "orc_search_range", "orc_search", "orc_search_all", "orc_pareto", "orc_front", "sim_run",
                      "sim_tile_matmul"):
@@ -210,6 +213,17 @@ def front_bs_da(w: Chain, h: Hw, capacity: int = 1024, first_idx: int | None = N
     idx, cost, cnt = (C.c_uint64 * capacity)(), (Cost * capacity)(), C.c_uint32()
     rc = lib().orc_front(C.byref(w), C.byref(h), 1, first_idx, n, capacity, idx, cost, C.byref(cnt))
     return rc, list(idx[:cnt.value]), list(cost[:cnt.value])
+
+
+def offline_rows(r: int, f: int):
+    """Offline symbolic pruning of group (r, f): (rows that denote a dataflow, surviving rows,
+    dominator of every removed row or None), row numbers inside the group."""
+    valid, kept, dom = (C.c_uint32 * 15000)(), (C.c_uint32 * 15000)(), (C.c_uint32 * 15000)()
+    nv, nk = C.c_uint32(), C.c_uint32()
+    rc = lib().orc_offline_rows(r, f, valid, C.byref(nv), kept, C.byref(nk), dom)
+    if rc:
+        raise ValueError(f"orc_offline_rows rc={rc}")
+    return list(valid[:nv.value]), list(kept[:nk.value]), [None if d == 0xFFFFFFFF else d for d in dom]
 
 
 def simulate(xG, xD, order, level, recompute: int, fused: int) -> SimResult:

@@ -40,7 +40,7 @@ typedef struct {
     uint32_t reserved;
 } orc_workload;
 
-/* Two chained matrix multiplications of free shape (Sec. VII-H: two GEMMs, or a
+/* Two chained matrix multiplications of free shape (Sec. VII-J: two GEMMs, or a
  * convolution chain after im2col): Op1 is I x K x L, Op2 is I x L x J, `batch`
  * independent instances.  Attention is the case I = L = N, K = J = d, batch = B*H. */
 typedef struct {
@@ -462,7 +462,7 @@ static int better(int objective, const orc_cost *a, uint64_t ia, const orc_cost 
 {
     double pa, pb, sa = 0, sb = 0;
     if (objective == OBJ_ENERGY) { pa = a->energy_pj; pb = b->energy_pj; }
-    else if (objective == OBJ_EDP) {       /* energy-delay product (Sec. VII-I) */
+    else if (objective == OBJ_EDP) {       /* energy-delay product (Sec. VII-K) */
         pa = a->energy_pj * a->latency_cycles; pb = b->energy_pj * b->latency_cycles;
     }
     else { pa = a->latency_cycles; pb = b->latency_cycles; }
@@ -590,7 +590,7 @@ int orc_search_all(const orc_chain *w, const orc_hw *hw, uint64_t first_idx, uin
     return 0;
 }
 
-/* Energy-latency Pareto front (Sec. VI-A, Sec. VII-C): the feasible candidates that no other
+/* Energy-latency Pareto front (Sec. VI-A, Sec. VII-E): the feasible candidates that no other
  * candidate beats in both metrics.  Among candidates with identical (energy, latency) the lowest
  * index stands for all.  Points come out by ascending latency (so descending energy).
  * One plain pass: every candidate is checked against the current front.
@@ -618,7 +618,7 @@ static int front_insert(front_pt *f, int *n, int cap, double e, double l, uint64
 
 /* kind 0: (energy, latency) over the feasible candidates, listed by ascending latency.
  * kind 1: (DRAM access, buffer size requirement) over every candidate that denotes a dataflow,
- *         whatever the buffer capacity (the DRAM-access-versus-buffer-size curve of Sec. VII-B),
+ *         whatever the buffer capacity (the DRAM-access-versus-buffer-size curve of Sec. VII-C),
  *         listed by ascending buffer size. */
 int orc_front(const orc_chain *w, const orc_hw *hw, int kind, uint64_t first_idx, uint64_t n, uint32_t capacity,
               uint64_t *idx_out, orc_cost *cost_out, uint32_t *n_out)

@@ -104,13 +104,14 @@ def _load() -> C.CDLL:
     L.mmee_chain_front_bs_da.argtypes = [P(Chain), P(Hw), C.c_uint32, P(Result), C.c_uint32, P(C.c_uint32)]
     L.mmee_search_noalloc.argtypes = [P(Workload), P(Hw), C.c_int, C.c_uint32, C.c_void_p]
     L.mmee_offline_stats.argtypes = [P(RowStats)]
+    L.mmee_offline_rows.argtypes = [C.c_uint32, C.c_uint32, P(C.c_uint32), C.c_uint32, P(C.c_uint32)]
     L.mmee_set_stream.argtypes = [C.c_void_p]
     L.mmee_shutdown.argtypes = []
     L.mmee_shutdown.restype = None
     L.mmee_strerror.argtypes = [C.c_int]
     L.mmee_strerror.restype = C.c_char_p
     for name in ("mmee_space_size", "mmee_decode", "mmee_eval_batch", "mmee_search", "mmee_search_ex",
-                 "mmee_search_multi", "mmee_search_many", "mmee_search_noalloc", "mmee_offline_stats", "mmee_set_stream",
+                 "mmee_search_multi", "mmee_search_many", "mmee_search_noalloc", "mmee_offline_stats", "mmee_offline_rows", "mmee_set_stream",
                  "mmee_chain_space_size", "mmee_chain_decode", "mmee_chain_eval_batch",
                  "mmee_chain_search_multi", "mmee_chain_search_many", "mmee_pareto", "mmee_chain_pareto",
                  "mmee_front_bs_da", "mmee_chain_front_bs_da"):
@@ -310,6 +311,14 @@ def mmee_offline_stats() -> RowStats:
     s = RowStats()
     _check(_lib.mmee_offline_stats(C.byref(s)), "mmee_offline_stats")
     return s
+
+
+def mmee_offline_rows(group: int, which: int = 1):
+    """Row numbers (inside group g = r + 2 f) that denote a dataflow (which=0) or survive pruning (which=1)."""
+    out = (C.c_uint32 * 15000)()
+    n = C.c_uint32()
+    _check(_lib.mmee_offline_rows(group, which, out, 15000, C.byref(n)), "mmee_offline_rows")
+    return list(out[:n.value])
 
 
 def mmee_set_stream(stream_ptr: int | None):

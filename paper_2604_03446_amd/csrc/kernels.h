@@ -848,7 +848,7 @@ __device__ __forceinline__ void finish_grid(const SearchArgs &a, Key (*wave_best
     if (threadIdx.x == 0) { *a.ticket = 0; *a.work_counter = 0; }   // ready for the next launch on this stream
 }
 
-// MASK: bit0 energy, bit1 latency, bit2 latency-then-energy, bit3 energy-delay product (Sec. VII-I).
+// MASK: bit0 energy, bit1 latency, bit2 latency-then-energy, bit3 energy-delay product (Sec. VII-K).
 // FAST: DRAM bandwidth is 0 or a power of two and the array count is a power of two, so the
 // DRAM latency term is one exact multiply of the table value; otherwise it is divided out.
 //
@@ -1513,7 +1513,7 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
     finish_grid<MASK, DENSE_THREADS>(a, wave_best, &is_last);
 }
 
-// One step of the buffer-size / DRAM-access front (Sec. VII-B): the (buffer size, DRAM access,
+// One step of the buffer-size / DRAM-access front (Sec. VII-C): the (buffer size, DRAM access,
 // index)-smallest dataflow among those whose DRAM access is below a bound.  Neither metric depends
 // on the stationary modes, so a (row, tiling) pair stands for its nine combinations through the
 // lowest-index one, and the buffer capacity plays no part.  a.e_limit carries the bound in the

@@ -705,6 +705,24 @@ int mmee_offline_stats(mmee_row_stats *out)
     return MMEE_OK;
 }
 
+int mmee_offline_rows(uint32_t group, uint32_t which, uint32_t *rows_out, uint32_t capacity, uint32_t *n_rows)
+{
+    if (group >= N_GROUPS || which > 1 || !n_rows || (capacity && !rows_out)) return MMEE_EINVAL;
+    std::lock_guard<std::mutex> guard(g_lock);
+    int rc = ensure_ready();
+    if (rc) return rc;
+    const uint32_t n = S.counts[which][group];
+    *n_rows = n;
+    const uint32_t take = std::min(n, capacity);
+    if (take) {
+        HIP_TRY(hipMemcpyAsync(rows_out, S.rows[which] + (size_t)group * ROWS_PER_GROUP, sizeof(uint32_t) * take,
+                               hipMemcpyDeviceToHost, S.stream));
+        HIP_TRY(hipStreamSynchronize(S.stream));
+        for (uint32_t a = 0; a < take; ++a) rows_out[a] -= group * ROWS_PER_GROUP;   // number inside the group
+    }
+    return n > capacity ? MMEE_EOVERFLOW : MMEE_OK;
+}
+
 int mmee_chain_decode(const mmee_chain *w, const mmee_hw *hw, const uint64_t *idx, uint64_t n, mmee_mapping *out)
 {
     if (n && (!idx || !out)) return MMEE_EINVAL;
@@ -896,9 +914,9 @@ int mmee_chain_search_multi(const mmee_chain *w, const mmee_hw *hw, const int *o
     return mmee_chain_search_many(ws, hs, objectives, n_obj, flags, out, nullptr);
 }
 
-// Walk along a front.  Energy-latency (Sec. VII-C): by ascending latency, each step the
+// Walk along a front.  Energy-latency (Sec. VII-E): by ascending latency, each step the
 // latency-then-energy optimum among the candidates whose energy is strictly below the previous
-// point's.  Buffer size / DRAM access (Sec. VII-B): by ascending buffer size, each step the
+// point's.  Buffer size / DRAM access (Sec. VII-C): by ascending buffer size, each step the
 // (size, traffic)-smallest dataflow whose traffic is strictly below the previous point's.
 static int walk_front(const mmee_chain *w, const mmee_hw *hw, bool bs_da, uint32_t flags, mmee_result *out,
                uint32_t capacity, uint32_t *n_points)

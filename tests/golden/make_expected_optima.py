@@ -1,11 +1,15 @@
 """Writes tests/golden/expected_optima.json: the optimal mapping of every
-benchmark configuration, of a few hardware-sweep points and of the two-GEMM /
-convolution-chain shapes, for all four objectives, found by the CPU oracle's exhaustive search.
+benchmark configuration, of seed-chosen hardware-sweep points (every sequence length up to
+16384 included), of the two-GEMM / convolution-chain shapes and of a few logical PE-array
+shapes, for all four objectives, found by the CPU oracle's exhaustive search; plus the two
+Pareto fronts of the BERT-like configuration over its whole space.
 
 Calls only oracle/ and the shared input module.  Full enumeration: about
-3e10 candidate evaluations, tens of minutes on a few cores.
+2e11 candidate evaluations, around an hour on eight cores.  Entries already in the
+file whose workload and hardware are unchanged are kept (the oracle is deterministic);
+--force recomputes them.
 
-    python tests/golden/make_expected_optima.py [--only name,name] [--sweep-points 8]
+    python tests/golden/make_expected_optima.py [--only name,name] [--force]
 """
 import argparse
 import json
@@ -20,6 +24,13 @@ import oracle as O                                   # noqa: E402
 from inputs import CHAINS, CONFIGS, SplitMix64, sweep_hw, sweep_workloads   # noqa: E402
 
 OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "expected_optima.json")
+OBJ_NAMES = ("energy", "latency", "latency_then_energy", "edp")
+
+
+def cost_dict(idx, c):
+    return dict(idx=idx, energy_pj=float(c.energy_pj).hex(), latency_cycles=float(c.latency_cycles).hex(),
+                bs_words=c.bs_words, da_words=c.da_words, br_words=c.br_words,
+                mac_total=c.mac_total, comp_cycles=c.comp_cycles)
 
 
 def record(wcfg, hcfg):
@@ -28,37 +39,70 @@ def record(wcfg, hcfg):
     rc, idx, cost, n_valid, threads = O.search_all(w, h)
     rec = dict(workload=wcfg, hw=hcfg, space=O.space_size(w, h), n_valid=n_valid, rc=rc,
                oracle_seconds=round(time.time() - t, 2), oracle_threads=threads, best={})
-    for o, name in enumerate(("energy", "latency", "latency_then_energy", "edp")):
-        c = cost[o]
-        rec["best"][name] = dict(
-            idx=idx[o], energy_pj=float(c.energy_pj).hex(), latency_cycles=float(c.latency_cycles).hex(),
-            bs_words=c.bs_words, da_words=c.da_words, br_words=c.br_words,
-            mac_total=c.mac_total, comp_cycles=c.comp_cycles) if rc == 0 else None
+    for o, name in enumerate(OBJ_NAMES):
+        rec["best"][name] = cost_dict(idx[o], cost[o]) if rc == 0 else None
     return rec
 
 
-def sweep_choice(n_points, seed=0x5EED):
-    """Seed-chosen (workload, hw) pairs of the hardware sweep; the largest
-    sequence length is left to the GPU-side consistency tests."""
+def fronts_record(wcfg, hcfg):
+    """Both fronts over the whole space: energy-latency over the feasible candidates, DRAM access
+    versus buffer size over every dataflow."""
+    w, h = O.workload(wcfg), O.hw(hcfg)
+    t = time.time()
+    rc0, idx0, cost0 = O.pareto(w, h, 4096)
+    rc1, idx1, cost1 = O.front_bs_da(w, h, 4096)
+    assert rc0 == 0 and rc1 == 0
+    return dict(workload=wcfg, hw=hcfg, oracle_seconds=round(time.time() - t, 2),
+                energy_latency=[cost_dict(i, c) for i, c in zip(idx0, cost0)],
+                bs_da=[cost_dict(i, c) for i, c in zip(idx1, cost1)])
+
+
+SWEEP_POINTS = 32
+
+
+def sweep_choice(seed=0x5EED):
+    """Seed-chosen (workload, hw) pairs of the hardware sweep, 32 in all: eight among the
+    sequence lengths up to 4096, two accelerators for each of the two N = 16384 workloads, and
+    twenty more drawn over all eight workloads."""
     wls, hws = sweep_workloads(), sweep_hw()
     rng = SplitMix64(seed)
     picks = []
-    while len(picks) < n_points:
+    while len(picks) < 8:
         wi, hi = rng.next() % len(wls), rng.next() % len(hws)
         if wls[wi]["N"] > 4096 or (wi, hi) in picks:
             continue
         picks.append((wi, hi))
+    for wi, wl in enumerate(wls):
+        if wl["N"] != 16384:
+            continue
+        have = 0
+        while have < 2:
+            hi = rng.next() % len(hws)
+            if (wi, hi) not in picks:
+                picks.append((wi, hi))
+                have += 1
+    while len(picks) < SWEEP_POINTS:
+        wi, hi = rng.next() % len(wls), rng.next() % len(hws)
+        if (wi, hi) not in picks:
+            picks.append((wi, hi))
     return [(f"sweep_w{wi}_h{hi}", wls[wi], hws[hi]) for wi, hi in picks]
+
+
+# logical shapes of a 256-PE array (the BERT-like configuration has 16 x 16)
+ARRAY_SHAPES = [(4, 64), (8, 32), (32, 8), (64, 4)]
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--only", default="")
-    ap.add_argument("--sweep-points", type=int, default=8)
+    ap.add_argument("--force", action="store_true")
     args = ap.parse_args()
     todo = [(name, cfg["workload"], cfg["hw"]) for name, cfg in CONFIGS.items()]
-    todo += sweep_choice(args.sweep_points)
+    todo += sweep_choice()
     todo += [("chain_" + name, cfg["workload"], cfg["hw"]) for name, cfg in CHAINS.items()]
+    bert = CONFIGS["bert"]
+    todo += [(f"shape_bert_{r}x{c}", bert["workload"], dict(bert["hw"], pe_rows=r, pe_cols=c)) for r, c in ARRAY_SHAPES]
+    todo += [("fronts_bert", bert["workload"], bert["hw"])]
     if args.only:
         keep = set(args.only.split(","))
         todo = [t for t in todo if t[0] in keep]
@@ -67,8 +111,12 @@ def main():
         with open(OUT) as fh:
             result = json.load(fh)
     for name, wcfg, hcfg in todo:
-        result[name] = record(wcfg, hcfg)
-        print(name, result[name]["oracle_seconds"], "s", result[name]["best"]["energy"], flush=True)
+        old = result.get(name)
+        if old and not args.force and old["workload"] == wcfg and old["hw"] == hcfg:
+            print(name, "kept", flush=True)
+            continue
+        result[name] = fronts_record(wcfg, hcfg) if name.startswith("fronts_") else record(wcfg, hcfg)
+        print(name, result[name]["oracle_seconds"], "s", flush=True)
         with open(OUT, "w") as fh:
             json.dump(result, fh, indent=1, sort_keys=True)
 

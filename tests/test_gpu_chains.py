@@ -1,4 +1,4 @@
-"""GPU parity for free two-GEMM / convolution-chain shapes (Sec. VII-H, Table V):
+"""GPU parity for free two-GEMM / convolution-chain shapes (Sec. VII-J, Table V):
 the same kernels, four independent loop extents, non-power-of-two divisors."""
 import json
 import os

@@ -1,5 +1,5 @@
-"""GPU parity for the energy-delay-product objective (Sec. VII-I) and the energy-latency Pareto
-front (Sec. VI-A, Sec. VII-C) against the oracle."""
+"""GPU parity for the energy-delay-product objective (Sec. VII-K) and the energy-latency Pareto
+front (Sec. VI-A, Sec. VII-E) against the oracle."""
 import json
 import os
 
@@ -120,7 +120,7 @@ def test_pareto_full_configs_pruned_equals_exhaustive(M, name):
 
 @pytest.mark.parametrize("case", range(len(SMALL) + 1))
 def test_front_bs_da_small_spaces_against_oracle(M, case):
-    """DRAM access versus buffer size (Sec. VII-B) over every dataflow, against the oracle."""
+    """DRAM access versus buffer size (Sec. VII-C) over every dataflow, against the oracle."""
     w, h = (SMALL + [MULTI_POINT])[case]
     ow, oh = O.workload(w), O.hw(h)
     rc, idx, cost = O.front_bs_da(ow, oh)
@@ -164,7 +164,7 @@ def test_front_bs_da_chain_and_full_configs(M):
 
 
 def test_reconfigurable_array_shape_sweep_edp(M):
-    """Sec. VII-I: EDP-driven choice among logical PE-array shapes with at most 32x32 PEs (stationary
+    """Sec. VII-K: EDP-driven choice among logical PE-array shapes with at most 32x32 PEs (stationary
     modes are free in every search).  All shapes go through one launch stream; every per-shape
     optimum and the best shape must be the oracle's."""
     w, h = SMALL[0]
@@ -184,3 +184,54 @@ def test_reconfigurable_array_shape_sweep_edp(M):
             best_cpu = (o, r, c)
     assert best_gpu == best_cpu
     print("best shape", best_gpu, flush=True)
+
+
+def _load_expected():
+    with open(os.path.join(GOLDEN, "expected_optima.json")) as fh:
+        return json.load(fh)
+
+
+def test_fronts_of_bert_against_stored_oracle_fronts(M):
+    """Sec. VII-C and VII-E at full size: both fronts of the BERT-like configuration, point by point,
+    against the fronts one oracle pass over the whole space (2.6e9 candidates) wrote down."""
+    exp = _load_expected()["fronts_bert"]
+    cfg = CONFIGS["bert"]
+    w, h = cfg["workload"], cfg["hw"]
+    assert exp["workload"] == w and exp["hw"] == h
+    assert len(exp["energy_latency"]) >= 1 and len(exp["bs_da"]) >= 10
+    for flags in (M.SEARCH_PRUNED, M.SEARCH_EXHAUSTIVE):
+        for call, key in ((M.mmee_pareto, "energy_latency"), (M.mmee_front_bs_da, "bs_da")):
+            code, front = call(w, h, flags, capacity=4096)
+            want = exp[key]
+            assert code == 0 and [p.best.idx for p in front] == [e["idx"] for e in want], (key, flags)
+            for p, e in zip(front, want):
+                for fld in INT_FIELDS:
+                    assert getattr(p.cost, fld) == e[fld], (key, fld)
+                assert p.cost.energy_pj == float.fromhex(e["energy_pj"])
+                assert p.cost.latency_cycles == float.fromhex(e["latency_cycles"])
+
+
+def test_reconfigurable_array_shapes_on_bert_against_stored_oracle_optima(M):
+    """Sec. VII-K at full size: the EDP-driven optimum of the BERT-like workload on five logical shapes
+    of its 256-PE array, all through one launch stream; every optimum and the best shape are the
+    oracle's (full enumeration per shape)."""
+    exp = _load_expected()
+    cfg = CONFIGS["bert"]
+    shapes = [(4, 64), (8, 32), (16, 16), (32, 8), (64, 4)]
+    want = [exp["bert" if (r, c) == (16, 16) else f"shape_bert_{r}x{c}"] for r, c in shapes]
+    points = [(cfg["workload"], dict(cfg["hw"], pe_rows=r, pe_cols=c), M.OBJ_EDP) for r, c in shapes]
+    for rec, (_, hw_, _) in zip(want, points):
+        assert rec["hw"] == hw_
+    edp = lambda e, l: e * l
+    best_oracle = min(range(5), key=lambda k: (edp(float.fromhex(want[k]["best"]["edp"]["energy_pj"]),
+                                                   float.fromhex(want[k]["best"]["edp"]["latency_cycles"])), k))
+    for flags in (M.SEARCH_PRUNED, M.SEARCH_EXHAUSTIVE):
+        results, codes = M.mmee_search_many(points, flags)
+        for res, code, rec in zip(results, codes, want):
+            e = rec["best"]["edp"]
+            assert code == 0 and res.best.idx == e["idx"], (rec["hw"]["pe_rows"], flags)
+            assert res.cost.energy_pj == float.fromhex(e["energy_pj"])
+            assert res.cost.latency_cycles == float.fromhex(e["latency_cycles"])
+        best_gpu = min(range(5), key=lambda k: (edp(results[k].cost.energy_pj, results[k].cost.latency_cycles), k))
+        assert best_gpu == best_oracle
+    print("best shape on bert:", shapes[best_oracle], flush=True)

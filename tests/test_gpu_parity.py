@@ -233,10 +233,28 @@ def test_search_full_configs_against_stored_oracle_optima(M, name):
         assert res.best.idx == exp["best"][OBJ_NAMES[obj]]["idx"]
 
 
+def test_eval_batch_windows_on_sweep_workloads(M):
+    """Per-candidate records on hardware-sweep problems: fractional DRAM energies (the sum is taken
+    term by term), the longest sequence, both head dims."""
+    wls, hws = sweep_workloads(), sweep_hw()
+    picks = [(wls[6], hws[11]), (wls[7], hws[4]), (wls[3], hws[39])]     # N = 16384 d = 64 / 128, N = 1024 d = 128
+    for k, (w, h) in enumerate(picks):
+        assert h["e_dram"] != int(h["e_dram"])
+        ow, oh = O.workload(w), O.hw(h)
+        S = O.space_size(ow, oh)
+        T = S // 540000
+        for first, n in list(windows(S, 70 + k, [100003, 2 * T + 9, 300001])) + [(S - 50001, 50001)]:
+            assert_costs_equal(M.mmee_eval_batch(w, h, first, n), O.eval_batch(ow, oh, first, n), (k, first, n))
+
+
 def test_sweep_points_against_stored_oracle_optima(M):
+    """32 seed-chosen (workload, accelerator) pairs of the hardware sweep, every sequence length up
+    to 16384 and both head dims among them, against optima the oracle enumerated."""
     exp = load_expected()
     names = [k for k in exp if k.startswith("sweep_")]
-    assert len(names) >= 8
+    assert len(names) >= 32
+    longest = [exp[k]["workload"]["d"] for k in names if exp[k]["workload"]["N"] == 16384]
+    assert longest.count(64) >= 2 and longest.count(128) >= 2
     points = []
     for k in names:
         for obj in (0, 1):
@@ -285,14 +303,20 @@ def test_sweep_pruned_equals_exhaustive_everywhere(M):
                     assert (c.energy_pj if obj == 0 else c.latency_cycles) >= best
 
 
-def test_offline_stage_counts(M):
+def test_offline_stage_rows_against_the_plain_reference(M):
+    """Sec. VI-B: the device's row lists -- which rows denote a dataflow, which survive the symbolic
+    pruning of Eq. (12) -- against the oracle-side O(n^2) reference, row number by row number."""
     st = M.mmee_offline_stats()
     assert list(st.rows_total) == [15000] * 4
+    for g in range(4):
+        r, f = g & 1, g >> 1
+        valid, kept, _ = O.offline_rows(r, f)
+        assert M.mmee_offline_rows(g, 0) == valid, g
+        assert M.mmee_offline_rows(g, 1) == kept, g
+        assert (st.rows_valid[g], st.rows_kept[g]) == (len(valid), len(kept))
     # g = r + 2 f: recomputation needs a fused C and j outside k (half of the 24 orders)
     assert list(st.rows_valid) == [15000, 0, 15000, 7500]
-    kept = list(st.rows_kept)
-    assert kept[1] == 0 and all(0 < kept[g] < st.rows_valid[g] for g in (0, 2, 3))
-    print("rows kept per group", kept, flush=True)
+    print("rows kept per group", list(st.rows_kept), flush=True)
 
 
 def test_regrouped_energy_sum_near_its_exactness_bound(M):

@@ -1,5 +1,5 @@
 """Pins for the oracle's reductions beyond a single minimum: the energy-delay product
-objective (Sec. VII-I) and the energy-latency Pareto front (Sec. VI-A, Sec. VII-C), each against
+objective (Sec. VII-K) and the energy-latency Pareto front (Sec. VI-A, Sec. VII-E), each against
 its textbook definition evaluated with numpy on spaces small enough to hold in memory."""
 import numpy as np
 import pytest
@@ -97,7 +97,7 @@ def test_pareto_front_matches_the_definition(k):
 
 @pytest.mark.parametrize("k", range(len(CASES)))
 def test_dram_access_versus_buffer_size_front_matches_the_definition(k):
-    """Sec. VII-B plots minimum DRAM access against buffer size requirement: the non-dominated
+    """Sec. VII-C plots minimum DRAM access against buffer size requirement: the non-dominated
     (buffer size, DRAM access) pairs over every dataflow, whatever the buffer capacity."""
     case = CASES[k]
     w, h = O.workload(case["w"]), O.hw(case["h"])

@@ -280,7 +280,7 @@ def test_invariants_on_all_configs():
 
 
 def test_two_gemm_and_conv_chain_shapes():
-    """Sec. VII-H, Table V: two GEMMs [I,K,L,J] and convolution chains turned into GEMMs by im2col.
+    """Sec. VII-J, Table V: two GEMMs [I,K,L,J] and convolution chains turned into GEMMs by im2col.
     The model is the same; only the four loop extents are free."""
     from inputs import CHAINS
     assert [CHAINS["mlp"]["workload"][k] for k in "IKLJ"] == [768, 64, 384, 64]
