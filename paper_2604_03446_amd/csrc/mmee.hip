@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "kernels.h"
+#include "batch.h"
 
 // ---- fixed scratch of the entry point that allocates nothing (mmee_search_noalloc) ------------
 // One array per GPU, held from the moment the library is loaded until the process ends.  In host
@@ -90,6 +91,16 @@ struct State {
     void *eval_dev = nullptr;
     size_t eval_cap = 0;
     uint32_t resident_blocks = 512;
+    // batched search over the pruned rows: problem descriptors (pinned staging + device copy), one record
+    // per item and objective, one ticket and N_OBJ hints per problem; the split of the row lists over waves
+    unsigned char *batch_host = nullptr, *batch_dev = nullptr;
+    size_t batch_blob_cap = 0;
+    Key *item_keys = nullptr;
+    size_t item_cap = 0;
+    uint32_t *batch_tickets = nullptr;
+    unsigned long long *batch_hints = nullptr;
+    size_t batch_prob_cap = 0;
+    uint32_t task_off[BATCH_WAVES] = {}, task_cnt[BATCH_WAVES] = {}, task_g[BATCH_WAVES] = {};
 } S;
 
 // The device buffers one search pass works in.  The allocating entry points fill this from the
@@ -127,7 +138,28 @@ struct Plan {
 
 bool finite_nonneg(double v) { return std::isfinite(v) && v >= 0.0; }
 
+int list_divisors_uncached(uint32_t X, uint32_t mode, uint32_t *out);
+
+// the last few factorisations are kept: a sweep asks for the same extents over and over
 int list_divisors(uint32_t X, uint32_t mode, uint32_t *out)
+{
+    struct Entry { uint32_t X = 0, mode = 0; int n = 0; std::vector<uint32_t> div; };
+    static thread_local Entry cache[8];
+    static thread_local unsigned next = 0;
+    for (const Entry &e : cache)
+        if (e.X == X && e.mode == mode && e.n > 0) {
+            std::memcpy(out, e.div.data(), sizeof(uint32_t) * std::min(e.n, (int)MAXDIV));
+            return e.n;
+        }
+    Entry &e = cache[next++ % 8];
+    e.div.assign(MAXDIV, 0);
+    e.n = list_divisors_uncached(X, mode, e.div.data());
+    e.X = X; e.mode = mode;
+    std::memcpy(out, e.div.data(), sizeof(uint32_t) * std::min(std::max(e.n, 0), (int)MAXDIV));
+    return e.n;
+}
+
+int list_divisors_uncached(uint32_t X, uint32_t mode, uint32_t *out)
 {
     // trial division up to sqrt(X); ascending order
     std::vector<uint32_t> lo, hi;
@@ -289,6 +321,31 @@ int ensure_ready()
         HIP_TRY(hipMalloc(&S.cls_dev, sizeof(uint32_t) * 96));
         HIP_TRY(hipMemcpy(S.cls_dev, cls.data(), sizeof(uint32_t) * cls.size(), hipMemcpyHostToDevice));
         S.n_cls = (uint32_t)cls.size();
+    }
+    {
+        // batched search: share the surviving rows of each group out over the waves of a block, every
+        // wave a contiguous piece of one group's list (rows of one group share r and f)
+        uint32_t waves[N_GROUPS] = {0, 0, 0, 0}, used = 0;
+        for (uint32_t g = 0; g < N_GROUPS; ++g)
+            if (S.counts[1][g]) { waves[g] = 1; ++used; }
+        while (used < BATCH_WAVES) {
+            uint32_t worst = N_GROUPS, most = 0;
+            for (uint32_t g = 0; g < N_GROUPS; ++g) {
+                if (!waves[g]) continue;
+                const uint32_t per = (S.counts[1][g] + waves[g] - 1) / waves[g];
+                if (per > most) { most = per; worst = g; }
+            }
+            if (worst == N_GROUPS || most <= 1) break;
+            ++waves[worst]; ++used;
+        }
+        uint32_t wv = 0;
+        for (uint32_t g = 0; g < N_GROUPS; ++g)
+            for (uint32_t k = 0; k < waves[g]; ++k, ++wv) {
+                const uint32_t n = S.counts[1][g], lo = (uint32_t)((uint64_t)n * k / waves[g]),
+                               hi = (uint32_t)((uint64_t)n * (k + 1) / waves[g]);
+                S.task_off[wv] = g * ROWS_PER_GROUP + lo; S.task_cnt[wv] = hi - lo; S.task_g[wv] = g;
+            }
+        for (; wv < BATCH_WAVES; ++wv) { S.task_off[wv] = 0; S.task_cnt[wv] = 0; S.task_g[wv] = 0; }
     }
     S.ready = true;
     return MMEE_OK;
@@ -584,6 +641,149 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     return enqueue_search_in(b, p, mask, flags, evaluated, e_limit, build_tables, bs_da_step, unproven);
 }
 
+// ---- batched search over the pruned rows -----------------------------------------------------
+
+// masks the batched kernel is built for; other key sets take the per-problem kernels
+bool batch_mask(int mask) { return mask == 1 || mask == 2 || mask == 3 || mask == 4 || mask == 8; }
+
+int ensure_batch(size_t blob_bytes, size_t n_prob, size_t n_items)
+{
+    if (blob_bytes > S.batch_blob_cap) {
+        if (S.batch_host) { HIP_TRY(hipStreamSynchronize(S.stream)); (void)hipHostFree(S.batch_host); (void)hipFree(S.batch_dev); }
+        S.batch_host = nullptr; S.batch_dev = nullptr; S.batch_blob_cap = 0;
+        const size_t cap = std::max<size_t>(blob_bytes * 2, 1 << 16);
+        HIP_TRY(hipHostMalloc(&S.batch_host, cap, hipHostMallocDefault));
+        HIP_TRY(hipMalloc(&S.batch_dev, cap));
+        S.batch_blob_cap = cap;
+    }
+    if (n_items > S.item_cap) {
+        if (S.item_keys) { HIP_TRY(hipStreamSynchronize(S.stream)); (void)hipFree(S.item_keys); }
+        S.item_keys = nullptr; S.item_cap = 0;
+        const size_t cap = std::max<size_t>(n_items * 2, 4096);
+        HIP_TRY(hipMalloc(&S.item_keys, sizeof(Key) * N_OBJ * cap));
+        S.item_cap = cap;
+    }
+    if (n_prob > S.batch_prob_cap) {
+        if (S.batch_tickets) { HIP_TRY(hipStreamSynchronize(S.stream)); (void)hipFree(S.batch_tickets); (void)hipFree(S.batch_hints); }
+        S.batch_tickets = nullptr; S.batch_hints = nullptr; S.batch_prob_cap = 0;
+        const size_t cap = std::max<size_t>(n_prob * 2, 64);
+        HIP_TRY(hipMalloc(&S.batch_tickets, sizeof(uint32_t) * cap));
+        HIP_TRY(hipMalloc(&S.batch_hints, sizeof(unsigned long long) * N_OBJ * cap));
+        S.batch_prob_cap = cap;
+    }
+    return MMEE_OK;
+}
+
+template <int MASK>
+void launch_batch_mask(bool fast, bool regroup, dim3 grid, const BatchArgs &a)
+{
+    if (regroup) hipLaunchKernelGGL((k_search_batch<MASK, true, true>), grid, dim3(BATCH_THREADS), 0, S.stream, a);
+    else if (fast) hipLaunchKernelGGL((k_search_batch<MASK, true, false>), grid, dim3(BATCH_THREADS), 0, S.stream, a);
+    else hipLaunchKernelGGL((k_search_batch<MASK, false, false>), grid, dim3(BATCH_THREADS), 0, S.stream, a);
+}
+
+// One problem of a batched launch, as the host sees it.
+struct BatchEntry {
+    const Plan *plan;
+    int mask;
+    size_t slot;            // result slot: its N_OBJ final records
+    ModelConst mc;          // with the regrouping decision taken
+    bool unproven;          // regrouped on trust (pass_constants)
+    uint64_t evaluated;
+};
+
+// Enqueue the entries (all pruned searches) as few launches as their kernel variants allow: one per
+// (key set, exact DRAM constant, regrouped) combination present.  Events of slot `ev_slot` bracket it all.
+int enqueue_batches(std::vector<BatchEntry> &entries, uint32_t flags, size_t ev_slot)
+{
+    if (entries.empty()) return MMEE_OK;
+    struct Variant { int mask; bool fast, regroup; std::vector<size_t> members; uint64_t items = 0; };
+    std::vector<Variant> variants;
+    uint64_t kept_rows = 0;
+    for (int g = 0; g < 4; ++g) kept_rows += S.counts[1][g];
+    uint64_t total_items = 0;
+    for (size_t k = 0; k < entries.size(); ++k) {
+        BatchEntry &e = entries[k];
+        e.mc = pass_constants(*e.plan, flags, e.mask, &e.unproven);
+        e.evaluated = kept_rows * e.plan->T * 9ull;
+        const bool fast = e.plan->exact_k, regroup = e.mc.regroup != 0;
+        Variant *v = nullptr;
+        for (Variant &c : variants)
+            if (c.mask == e.mask && c.fast == fast && c.regroup == regroup) v = &c;
+        if (!v) { variants.push_back(Variant{e.mask, fast, regroup, {}, 0}); v = &variants.back(); }
+        v->members.push_back(k);
+        v->items += (e.plan->T + BATCH_TC - 1) / BATCH_TC;
+        total_items += (e.plan->T + BATCH_TC - 1) / BATCH_TC;
+    }
+    if (total_items > 0x7fffffffull) return MMEE_EINVAL;
+    // blob: per variant its problem descriptors, then its first-item table
+    size_t blob = 0;
+    for (const Variant &v : variants) blob += sizeof(BatchProblem) * v.members.size() + sizeof(uint32_t) * ((v.members.size() + 1 + 3) & ~(size_t)3);
+    int rc = ensure_batch(blob, entries.size(), total_items);
+    if (rc) return rc;
+    size_t off = 0, prob0 = 0;
+    uint64_t item0 = 0;
+    struct Launch { size_t desc_off, firsts_off, n_prob, prob0; uint64_t item0, n_items; };
+    std::vector<Launch> launches;
+    for (const Variant &v : variants) {
+        Launch L;
+        L.desc_off = off; L.n_prob = v.members.size(); L.prob0 = prob0; L.item0 = item0; L.n_items = v.items;
+        BatchProblem *bp = reinterpret_cast<BatchProblem *>(S.batch_host + off);
+        off += sizeof(BatchProblem) * v.members.size();
+        L.firsts_off = off;
+        uint32_t *firsts = reinterpret_cast<uint32_t *>(S.batch_host + off);
+        off += sizeof(uint32_t) * ((v.members.size() + 1 + 3) & ~(size_t)3);
+        uint32_t item = 0;
+        for (size_t k = 0; k < v.members.size(); ++k) {
+            const BatchEntry &e = entries[v.members[k]];
+            bp[k].dv = e.plan->dv;
+            bp[k].mc = e.mc;
+            bp[k].first_item = item;
+            bp[k].n_chunks = (uint32_t)((e.plan->T + BATCH_TC - 1) / BATCH_TC);
+            bp[k].slot = (uint32_t)e.slot;
+            bp[k].pad_ = 0;
+            firsts[k] = item;
+            item += bp[k].n_chunks;
+        }
+        firsts[v.members.size()] = item;
+        prob0 += v.members.size();
+        item0 += v.items;
+        launches.push_back(L);
+    }
+    HIP_TRY(hipMemcpyAsync(S.batch_dev, S.batch_host, off, hipMemcpyHostToDevice, S.stream));
+    const uint32_t n_init = (uint32_t)entries.size() * N_OBJ;
+    hipLaunchKernelGGL(k_batch_init, dim3((n_init + 255) / 256), dim3(256), 0, S.stream, S.batch_tickets, S.batch_hints,
+                       (uint32_t)entries.size());
+    HIP_TRY(hipEventRecord(S.events[2 * ev_slot], S.stream));
+    for (size_t k = 0; k < variants.size(); ++k) {
+        const Variant &v = variants[k];
+        const Launch &L = launches[k];
+        BatchArgs a;
+        std::memset(&a, 0, sizeof(a));
+        a.prob = reinterpret_cast<const BatchProblem *>(S.batch_dev + L.desc_off);
+        a.first_items = reinterpret_cast<const uint32_t *>(S.batch_dev + L.firsts_off);
+        a.n_prob = (uint32_t)L.n_prob; a.n_items = (uint32_t)L.n_items;
+        a.enc = S.enc; a.row_enc = S.row_enc[1];
+        for (int wv = 0; wv < BATCH_WAVES; ++wv) { a.task_off[wv] = S.task_off[wv]; a.task_cnt[wv] = S.task_cnt[wv]; a.task_g[wv] = S.task_g[wv]; }
+        a.item_keys = S.item_keys + N_OBJ * L.item0;
+        a.tickets = S.batch_tickets + L.prob0;
+        a.hints = S.batch_hints + N_OBJ * L.prob0;
+        a.final_out = S.final_map;
+        dim3 grid((uint32_t)L.n_items);
+        switch (v.mask) {
+        case 1: launch_batch_mask<1>(v.fast, v.regroup, grid, a); break;
+        case 2: launch_batch_mask<2>(v.fast, v.regroup, grid, a); break;
+        case 3: launch_batch_mask<3>(v.fast, v.regroup, grid, a); break;
+        case 4: launch_batch_mask<4>(v.fast, v.regroup, grid, a); break;
+        case 8: launch_batch_mask<8>(v.fast, v.regroup, grid, a); break;
+        default: return MMEE_EINVAL;
+        }
+    }
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(S.events[2 * ev_slot + 1], S.stream));
+    return MMEE_OK;
+}
+
 int unpack_result(const Plan &p, size_t slot, int objective, uint64_t evaluated, double seconds, double ksec,
                   mmee_result *out)
 {
@@ -827,7 +1027,10 @@ int mmee_chain_search_many(const mmee_chain *w, const mmee_hw *hw, const int *ob
     if (rc) return rc;
 
     // group neighbouring entries that describe the same problem into one pass
-    struct Pass { uint32_t first, n; int mask; Plan plan; int rc; uint64_t evaluated; bool unproven; };
+    struct Pass {
+        uint32_t first, n; int mask; Plan plan; int rc; uint64_t evaluated; bool unproven;
+        bool batched = false; size_t ev_slot = 0;
+    };
     std::vector<Pass> passes;
     std::vector<int> codes(count, MMEE_OK);
     for (uint32_t a = 0; a < count;) {
@@ -849,12 +1052,43 @@ int mmee_chain_search_many(const mmee_chain *w, const mmee_hw *hw, const int *ob
     }
     rc = ensure_slots(passes.size());
     if (rc) return rc;
-    for (size_t s = 0; s < passes.size(); ++s) {
-        Pass &ps = passes[s];
-        if (ps.rc == MMEE_OK)
-            ps.rc = enqueue_search(ps.plan, ps.mask, flags, s, &ps.evaluated, nullptr, true, false, &ps.unproven);
-    }
-    HIP_TRY(hipStreamSynchronize(S.stream));
+    // Pruned searches whose key set the batched kernel is built for share launches; everything else
+    // (the full row set, other key sets) goes problem by problem.  `round_flags` adds
+    // MMEE_SEARCH_ORDERED_SUM on the second round, which repeats what the first could not prove.
+    auto run_round = [&](uint32_t round_flags, bool only_unproven) -> int {
+        std::vector<BatchEntry> batch;
+        std::vector<size_t> batch_pass;
+        for (size_t s = 0; s < passes.size(); ++s) {
+            Pass &ps = passes[s];
+            if (ps.rc != MMEE_OK || (only_unproven && !ps.unproven)) continue;
+            ps.batched = !(round_flags & MMEE_SEARCH_EXHAUSTIVE) && batch_mask(ps.mask);
+            if (ps.batched) {
+                BatchEntry e;
+                e.plan = &ps.plan; e.mask = ps.mask; e.slot = s; e.unproven = false; e.evaluated = 0;
+                batch.push_back(e);
+                batch_pass.push_back(s);
+            } else {
+                bool unproven = false;
+                ps.rc = enqueue_search(ps.plan, ps.mask, round_flags, s, &ps.evaluated, nullptr, true, false,
+                                       only_unproven ? nullptr : &unproven);
+                ps.unproven = unproven;
+            }
+        }
+        if (!batch.empty()) {
+            int brc = enqueue_batches(batch, round_flags, batch_pass[0]);
+            for (size_t k = 0; k < batch.size(); ++k) {
+                Pass &ps = passes[batch_pass[k]];
+                ps.rc = brc;
+                ps.evaluated = batch[k].evaluated;
+                ps.unproven = !only_unproven && batch[k].unproven;
+                ps.ev_slot = batch_pass[0];
+            }
+        }
+        HIP_TRY(hipStreamSynchronize(S.stream));
+        return MMEE_OK;
+    };
+    rc = run_round(flags, false);
+    if (rc) return rc;
     // a regrouped sum taken on trust (pass_constants) stands only if the energies found prove it
     {
         bool again = false;
@@ -873,12 +1107,8 @@ int mmee_chain_search_many(const mmee_chain *w, const mmee_hw *hw, const int *ob
             again = again || !proven;
         }
         if (again) {
-            for (size_t s = 0; s < passes.size(); ++s) {
-                Pass &ps = passes[s];
-                if (ps.rc != MMEE_OK || !ps.unproven) continue;
-                ps.rc = enqueue_search(ps.plan, ps.mask, flags | MMEE_SEARCH_ORDERED_SUM, s, &ps.evaluated);
-            }
-            HIP_TRY(hipStreamSynchronize(S.stream));
+            rc = run_round(flags | MMEE_SEARCH_ORDERED_SUM, true);
+            if (rc) return rc;
         }
     }
     const double seconds = now_seconds() - t_start;
@@ -886,7 +1116,9 @@ int mmee_chain_search_many(const mmee_chain *w, const mmee_hw *hw, const int *ob
     for (size_t s = 0; s < passes.size(); ++s) {
         Pass &ps = passes[s];
         float ms = 0.f;
-        if (ps.rc == MMEE_OK) (void)hipEventElapsedTime(&ms, S.events[2 * s], S.events[2 * s + 1]);
+        // a batched pass reports the device time of the launches it shared
+        const size_t ev = ps.batched ? ps.ev_slot : s;
+        if (ps.rc == MMEE_OK) (void)hipEventElapsedTime(&ms, S.events[2 * ev], S.events[2 * ev + 1]);
         for (uint32_t a = ps.first; a < ps.first + ps.n; ++a) {
             int code = codes[a] ? codes[a] : ps.rc;
             if (code == MMEE_OK)
@@ -1137,6 +1369,8 @@ void mmee_shutdown(void)
     (void)hipFree(S.partials); (void)hipFree(S.ticket);
     (void)hipFree(S.dv_dev); (void)hipFree(S.eval_dev);
     if (S.final_host) (void)hipHostFree(S.final_host);
+    if (S.batch_host) (void)hipHostFree(S.batch_host);
+    (void)hipFree(S.batch_dev); (void)hipFree(S.item_keys); (void)hipFree(S.batch_tickets); (void)hipFree(S.batch_hints);
     for (hipEvent_t e : S.events) (void)hipEventDestroy(e);
     hipStream_t keep = S.stream;
     S = State();
