@@ -17,10 +17,12 @@
 
 namespace mmee {
 
-constexpr int BATCH_THREADS = 1024;
+constexpr int BATCH_THREADS = 512;           // two blocks per CU, four waves per SIMD
 constexpr int BATCH_WAVES = BATCH_THREADS / 64;
 constexpr int BATCH_TC = 64;                 // tilings per item = lanes of a wave
 constexpr int BATCH_NCS = 20;                // constants per (tiling, r), as in layout.h
+constexpr int BATCH_MAX_USED = 80;           // table entries the row lists may refer to (the pruned rows use 77)
+constexpr int BATCH_MAX_ROWS = 288;          // rows the lists may hold (the pruned lists hold 270)
 
 struct BatchProblem {                        // one problem, in device memory
     DivTable dv;
@@ -36,12 +38,16 @@ struct BatchArgs {
     const uint32_t *first_items;             // [n_prob + 1] ascending, for the item -> problem search
     uint32_t n_prob, n_items;
     const uint4 *enc;                        // every encoded row (for the winner's record)
-    const uint4 *row_enc;                    // the compacted lists, row id in .w
-    uint32_t task_off[BATCH_WAVES];          // per wave: where its share of a list starts in row_enc,
-    uint32_t task_cnt[BATCH_WAVES];          //           how many rows it holds,
+    // the row lists, one after the other (group by group, ascending row number inside a group)
+    const uint32_t *row_off;                 // [n_rows][8] byte offsets of a row's eight table values in the staged table
+    const uint32_t *row_df;                  // [n_rows] the rows' numbers (levels/order + 15000 * (r + 2 f))
+    const uint32_t *cmap;                    // [NENT] table entry -> its place in the staged table, 0xFFFF when no row refers to it
+    uint32_t n_rows, n_used;
+    uint32_t task_lo[BATCH_WAVES];           // per wave: its first row in the lists,
+    uint32_t task_cnt[BATCH_WAVES];          //           how many rows it takes,
     uint32_t task_g[BATCH_WAVES];            //           and the group g = r + 2 f they belong to
-    Key *item_keys;                          // [n_items][N_OBJ]
-    uint32_t *tickets;                       // [n_prob] items finished
+    Key *item_keys;                          // [n_items][N_OBJ]; written at the first item of every (block, problem) stretch
+    uint32_t per_block;                      // items per block of the search launch (the finish kernel needs it)
     unsigned long long *hints;               // [n_prob][N_OBJ] lowest value seen so far (bits of a non-negative fp64)
     FinalRecord *final_out;                  // [result slot][N_OBJ]
 };
@@ -54,18 +60,21 @@ struct TilingF {                             // boundary vector of one tiling (E
     double G[4], D[4];
 };
 
+// digit q of tiling t: the intra-tile size x_G and the inter-tile count x_D of dimension q
+__device__ __forceinline__ void tiling_dim(const DivTable &dv, uint32_t t, int q, double &G, double &D)
+{
+    uint32_t radix = 1;
+    for (int k = 0; k < q; ++k) radix *= dv.ndiv[k];
+    const uint32_t g = dv.div[q][(t / radix) % dv.ndiv[q]];
+    G = (double)g;
+    D = (double)(dv.X[q] / g);
+}
+
 __device__ __forceinline__ TilingF tiling_of(const DivTable &dv, uint32_t t)
 {
     TilingF v;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const uint32_t n = dv.ndiv[q];
-        const uint32_t digit = t % n;
-        t /= n;
-        const uint32_t g = dv.div[q][digit];
-        v.G[q] = (double)g;
-        v.D[q] = (double)(dv.X[q] / g);
-    }
+    for (int q = 0; q < 4; ++q) tiling_dim(dv, t, q, v.G[q], v.D[q]);
     return v;
 }
 
@@ -135,13 +144,11 @@ struct ComboTerms {
     double e_rf_part, e_mac_part;
 };
 
-__device__ __forceinline__ ComboTerms combo_terms(const TilingF &v, const double X[4], const ModelConst &mc, uint32_t r,
-                                                  uint32_t s1, uint32_t s2)
+// ... from the two operators' tile costs (words and cycles of one tile matmul each)
+__device__ __forceinline__ ComboTerms combo_terms_from(const TilingF &v, const double X[4], const ModelConst &mc, uint32_t r,
+                                                       double br1, double cy1, double br2, double cy2)
 {
     ComboTerms o;
-    double br1, cy1, br2, cy2;
-    tile_cost_f64((uint32_t)v.G[DI], (uint32_t)v.G[DK], (uint32_t)v.G[DL], s1, mc, br1, cy1);
-    tile_cost_f64((uint32_t)v.G[DI], (uint32_t)v.G[DL], (uint32_t)v.G[DJ], s2, mc, br2, cy2);
     const double rho = r ? v.D[DJ] : 1.0;                    // producer repeated per j tile (Sec. V-D)
     const double st1 = rho * v.D[DI] * v.D[DK] * v.D[DL], st2 = v.D[DI] * v.D[DL] * v.D[DJ];
     o.br = st1 * br1 + st2 * br2;
@@ -153,6 +160,15 @@ __device__ __forceinline__ ComboTerms combo_terms(const TilingF &v, const double
     o.e_rf_part = mc.e_rf * (mc.BH * 3.0 * o.mac);
     o.e_mac_part = mc.e_mac * (mc.BH * (o.mac + (double)mc.c_softmax * o.sm));
     return o;
+}
+
+__device__ __forceinline__ ComboTerms combo_terms(const TilingF &v, const double X[4], const ModelConst &mc, uint32_t r,
+                                                  uint32_t s1, uint32_t s2)
+{
+    double br1, cy1, br2, cy2;
+    tile_cost_f64((uint32_t)v.G[DI], (uint32_t)v.G[DK], (uint32_t)v.G[DL], s1, mc, br1, cy1);
+    tile_cost_f64((uint32_t)v.G[DI], (uint32_t)v.G[DL], (uint32_t)v.G[DJ], s2, mc, br2, cy2);
+    return combo_terms_from(v, X, mc, r, br1, cy1, br2, cy2);
 }
 
 // One candidate, complete, from the problem description alone: the winner's cost record (Sec. V-D's
@@ -200,276 +216,430 @@ __device__ __forceinline__ void eval_candidate_direct(const uint4 *enc, const Di
     c.valid = 1; c.reason = 0;
 }
 
-// hints start at +inf, tickets at zero
-__global__ void k_batch_init(uint32_t *tickets, unsigned long long *hints, uint32_t n_prob)
+// hints start at +inf
+__global__ void k_batch_init(unsigned long long *hints, uint32_t n_prob)
 {
     const uint32_t a = blockIdx.x * blockDim.x + threadIdx.x;
-    if (a < n_prob) tickets[a] = 0;
     if (a < n_prob * N_OBJ) hints[a] = 0x7ff0000000000000ull;
 }
 
-// MASK, FAST, REGROUP as in k_search.  One block per work item.
-template <int MASK, bool FAST, bool REGROUP>
-__global__ __launch_bounds__(BATCH_THREADS) void k_search_batch(BatchArgs a)
+// The table entries of one kind, for this lane's tiling, into the staged table: x[a] + y[b] for every
+// option pair (na x nb of them, entry number first + a + na * b), each at the place cmap gives it.
+template <int NA, int NB>
+__device__ __forceinline__ void stage_pair_sums(double *tab_lane, const uint16_t *cmap, int first, const double (&x)[5],
+                                                const double (&y)[5])
 {
-    __shared__ double tab[NENT * BATCH_TC];                  // entry-major, lane = tiling: conflict-free as it is
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int a = 0; a < NA; ++a) {
+            const uint32_t at = cmap[first + a + NA * b];
+            if (at != 0xFFFFu) tab_lane[at * BATCH_TC] = x[a] + y[b];
+        }
+}
+
+// footprints of one operand under its five options (4 = takes no space)
+__device__ __forceinline__ void footprints(double (&o)[5], double tile, double d0, double d1)
+{
+    o[0] = tile; o[1] = tile * d0; o[2] = tile * d1; o[3] = tile * d0 * d1; o[4] = 0.0;
+}
+
+// MASK, FAST, REGROUP as in k_search.  Every block takes a contiguous range of the work items, so
+// that it stays with one problem for many items: a wave keeps its running best (value, index) per key
+// across the items of a problem and recovers a position only where it can matter; one record per
+// (block, problem) leaves the block, at the slot of the first item of that stretch.
+template <int MASK, bool FAST, bool REGROUP>
+__global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
+{
+    __shared__ double tab[BATCH_MAX_USED * BATCH_TC];        // entry-major, lane = tiling: conflict-free as it is
     __shared__ double cst[2 * BATCH_NCS * BATCH_TC];         // [r][constant][tiling]
+    __shared__ double gd[8 * BATCH_TC];                      // the chunk's boundary vectors: G[0..3], D[0..3] per tiling
+    __shared__ double tc[6 * 2 * BATCH_TC];                  // tile costs: [op * 3 + mode][words, cycles][tiling]
+    __shared__ uint16_t row_lds[BATCH_MAX_ROWS * 8];         // the rows' table offsets (below 64 KiB: 80 entries x 512 B)
+    __shared__ uint32_t div_lds[4 * MAXDIV];                 // the current problem's divisor lists
+    __shared__ uint16_t cmap_lds[NENT + 1];
     __shared__ Key wave_best[N_OBJ][BATCH_WAVES];
-    __shared__ uint32_t is_last;
 
     const double inf = pos_inf();
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t item = blockIdx.x;
+    for (uint32_t k = threadIdx.x; k < a.n_rows * 8; k += BATCH_THREADS) row_lds[k] = (uint16_t)a.row_off[k];
+    if (threadIdx.x < NENT) cmap_lds[threadIdx.x] = (uint16_t)a.cmap[threadIdx.x];
 
-    // which problem: the last p with first_items[p] <= item
+    const uint32_t per_block = (a.n_items + gridDim.x - 1) / gridDim.x;
+    const uint32_t item_lo = blockIdx.x * per_block, item_hi = min(item_lo + per_block, a.n_items);
+    if (item_lo >= item_hi) return;
+    // the first item's problem: the last p with first_items[p] <= item; later items move p on
     ConstPtr<uint32_t> firsts = as_constant(a.first_items);
-    uint32_t lo = 0, hi = a.n_prob;
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (firsts[mid] <= item) lo = mid; else hi = mid;
-    }
-    const uint32_t p = lo;
-    const BatchProblem *pr = a.prob + p;
-    // the descriptors are read-only while the kernel runs: wave-uniform fields through scalar loads
-    ModelConst mc;
+    uint32_t p;
     {
-        ConstPtr<uint32_t> words = as_constant(reinterpret_cast<const uint32_t *>(&pr->mc));
-        uint32_t buf[sizeof(ModelConst) / 4];
-#pragma unroll
-        for (uint32_t k = 0; k < sizeof(ModelConst) / 4; ++k) buf[k] = words[k];
-        __builtin_memcpy(&mc, buf, sizeof(ModelConst));
-    }
-    ConstPtr<uint32_t> tail = as_constant(&pr->first_item);      // first_item, n_chunks, slot
-    const uint32_t n_chunks = tail[1], slot = tail[2];
-    const uint32_t t0 = (item - firsts[p]) * BATCH_TC;
-    const uint32_t T = mc.T;
-    const uint32_t nt = min((uint32_t)BATCH_TC, T - t0);
-
-    // ---- build: this lane's tiling (beyond the chunk: its last tiling once more, masked out below)
-    {
-        const TilingF v = tiling_of(pr->dv, t0 + min(lane, nt - 1));
-        const double X[4] = {(double)pr->dv.X[0], (double)pr->dv.X[1], (double)pr->dv.X[2], (double)pr->dv.X[3]};
-        if (wave < 9) {
-            // one stationary combination per wave, both recomputation choices
-            const uint32_t s1 = wave % 3, s2 = wave / 3;
-#pragma unroll
-            for (uint32_t r = 0; r < 2; ++r) {
-                const ComboTerms ct = combo_terms(v, X, mc, r, s1, s2);
-                double *cs = cst + r * BATCH_NCS * BATCH_TC + lane;
-                cs[wave * BATCH_TC] = REGROUP ? (mc.e_gb * (mc.BH * ct.br) + ct.e_rf_part) + ct.e_mac_part : mc.BH * ct.br;
-                cs[(9 + wave) * BATCH_TC] = ct.lat_part;
-                if (wave == 0) { cs[18 * BATCH_TC] = ct.e_rf_part; cs[19 * BATCH_TC] = ct.e_mac_part; }
-            }
-        } else {
-            // the 123 table entries, shared out over the other seven waves
-            constexpr uint32_t PER = (NENT + (BATCH_WAVES - 9) - 1) / (BATCH_WAVES - 9);
-            const uint32_t e0 = (wave - 9) * PER, e1 = min(e0 + PER, (uint32_t)NENT);
-            for (uint32_t ent = e0; ent < e1; ++ent) tab[ent * BATCH_TC + lane] = table_entry(ent, v, X, mc.BH);
+        uint32_t lo = 0, hi = a.n_prob;
+        while (hi - lo > 1) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (firsts[mid] <= item_lo) lo = mid; else hi = mid;
         }
+        p = lo;
     }
-    __syncthreads();
+    // this wave's share of one group's rows
+    const uint32_t n_rows = a.task_cnt[wave], row_lo = a.task_lo[wave], r = a.task_g[wave] & 1;
+    ConstPtr<uint32_t> row_df = as_constant(a.row_df);
+    const uint32_t first_index_row = n_rows ? index_row_base(row_df[row_lo]) : 0u;
+    const char *tab_bytes = reinterpret_cast<const char *>(tab) + lane * 8;
 
-    // ---- cost: this wave's share of one group's rows against the chunk
-    const uint32_t n_rows = a.task_cnt[wave], g = a.task_g[wave], r = g & 1;
-    ConstPtr<uint32_t> rows32 = as_constant(reinterpret_cast<const uint32_t *>(a.row_enc + a.task_off[wave]));
-    auto load_row = [&](uint32_t i) {
-        uint4 e;
-        e.x = rows32[4 * i]; e.y = rows32[4 * i + 1]; e.z = rows32[4 * i + 2]; e.w = rows32[4 * i + 3];
-        return e;
+    // the wave's running best over the items of the current problem
+    double run_p[N_OBJ];
+    uint64_t run_idx[N_OBJ];
+    uint32_t run_c[N_OBJ], run_i[N_OBJ], run_t0[N_OBJ];      // its combination, its row (place in this wave's share), its chunk
+    Key run_le;
+    auto reset_running = [&]() {
+#pragma unroll
+        for (int o = 0; o < N_OBJ; ++o) { run_p[o] = inf; run_idx[o] = ~0ull; run_c[o] = run_i[o] = run_t0[o] = 0; }
+        run_le.p = inf; run_le.s = 0.0; run_le.idx = ~0ull;
     };
-    const double cap = lane < nt ? mc.cap_words : -1.0;      // a lane beyond the chunk never passes the capacity test
-    double gb[9], latc[9];
-    {
-        const double *cs = cst + r * BATCH_NCS * BATCH_TC + lane;
-#pragma unroll
-        for (int c = 0; c < 9; ++c) { gb[c] = cs[c * BATCH_TC]; latc[c] = cs[(9 + c) * BATCH_TC]; }
-    }
-    const double e_rf_part = REGROUP ? 0.0 : cst[(r * BATCH_NCS + 18) * BATCH_TC + lane];
-    const double e_mac_part = REGROUP ? 0.0 : cst[(r * BATCH_NCS + 19) * BATCH_TC + lane];
-    const double *col = tab + lane;
+    reset_running();
+    uint32_t staged_p = 0xFFFFFFFFu;
 
-    double bestE[9], bestL[9], bestP[9], bestLE_l[9], bestLE_e[9];
-    uint32_t codeLE[9];
+    // one stretch = the block's items of one problem
+    for (uint32_t seg_first = item_lo; seg_first < item_hi;) {
+      while (firsts[p + 1] <= seg_first) ++p;
+      const uint32_t seg_end = min(item_hi, firsts[p + 1]), seg_len = seg_end - seg_first;
+      // The items of a stretch are visited with a stride of about 0.618 of its length (coprime to it):
+      // costs tend to move steadily along the tiling index, and in such an order the running minimum
+      // improves a logarithmic number of times instead of at every item, so positions are rarely recovered.
+      uint32_t stride = max(1u, (uint32_t)(((uint64_t)seg_len * 40503u) >> 16));
+      {
+          auto gcd = [](uint32_t x, uint32_t y) { while (y) { const uint32_t z = x % y; x = y; y = z; } return x; };
+          while (stride < seg_len && gcd(stride, seg_len) != 1) ++stride;
+          if (stride >= seg_len) stride = 1;
+      }
+      for (uint32_t visit = 0; visit < seg_len; ++visit) {
+        const uint32_t item = seg_first + (uint32_t)(((uint64_t)visit * stride) % seg_len);
+        const BatchProblem *pr = a.prob + p;
+        // the descriptors are read-only while the kernel runs: wave-uniform fields through scalar loads
+        ModelConst mc;
+        {
+            ConstPtr<uint32_t> words = as_constant(reinterpret_cast<const uint32_t *>(&pr->mc));
+            uint32_t buf[sizeof(ModelConst) / 4];
 #pragma unroll
-    for (int c9 = 0; c9 < 9; ++c9) { bestE[c9] = bestL[c9] = bestP[c9] = bestLE_l[c9] = bestLE_e[c9] = inf; codeLE[c9] = 0; }
-
-    // the row part of one (row, tiling): Eq. (1), (2), (4), capacity mask, B*H * Eq. (7)
-    auto row_part = [&](const uint4 &e, double &dram_words, double &e_part, double &l_dram) {
-        double w[NSEL];
-#pragma unroll
-        for (int k = 0; k < NSEL; ++k) w[k] = col[sel_of(e, k) * BATCH_TC];
-        const bool ok = fmax(w[0] + w[2] + w[1], w[3] + w[2] + w[4]) <= cap;
-        dram_words = w[5] + w[6] + w[7];
-        e_part = (REGROUP ? mc.e_sum : mc.e_dram) * dram_words;
-        if constexpr (FAST) l_dram = dram_words * mc.dram_k;
-        else l_dram = mc.dram_bw > 0.0 ? mc.c_lat * (((dram_words / mc.BH) * mc.word) / mc.dram_bw) : 0.0;
-        const double over = __hiloint2double(ok ? 0 : 0x7ff00000, 0);
-        e_part = fmax(e_part, over);
-        l_dram = fmax(l_dram, over);
-        pin(e_part);
-        pin(l_dram);
-    };
-    auto combo_cost = [&](double dram_words, double e_part, double l_dram, double gb_c, double latc_c, double &en, double &lat) {
-        if constexpr (REGROUP) {
-            en = e_part + gb_c;
-        } else {
-            const double gb_words = dram_words + gb_c;
-            en = e_part + mc.e_gb * gb_words;
-            en = en + e_rf_part;
-            en = en + e_mac_part;
+            for (uint32_t k = 0; k < sizeof(ModelConst) / 4; ++k) buf[k] = words[k];
+            __builtin_memcpy(&mc, buf, sizeof(ModelConst));
         }
-        lat = fmax(l_dram, latc_c);
-    };
-
-    for (uint32_t i = 0; i < n_rows; ++i) {
-        const uint4 e = load_row(i);
-        double dram_words, e_part, l_dram;
-        row_part(e, dram_words, e_part, l_dram);
-#pragma unroll
-        for (int c9 = 0; c9 < 9; ++c9) {
-            double en, lat;
-            combo_cost(dram_words, e_part, l_dram, gb[c9], latc[c9], en, lat);
-            if constexpr (MASK & 1) bestE[c9] = fmin(bestE[c9], en);
-            if constexpr (MASK & 2) bestL[c9] = fmin(bestL[c9], lat);
-            if constexpr (MASK & 8) bestP[c9] = fmin(bestP[c9], en * lat);
-            if constexpr (MASK & 4) {
-                // rows come in index order: a strict < keeps the lowest index on ties
-                const bool lt = (lat < bestLE_l[c9]) | ((lat == bestLE_l[c9]) & (en < bestLE_e[c9]));
-                bestLE_l[c9] = lt ? lat : bestLE_l[c9];
-                bestLE_e[c9] = lt ? en : bestLE_e[c9];
-                codeLE[c9] = lt ? i : codeLE[c9];
-            }
-        }
-    }
-
-    // ---- this wave's record per key
-    Key mine[N_OBJ];
-#pragma unroll
-    for (int o = 0; o < N_OBJ; ++o) { mine[o].p = inf; mine[o].s = 0.0; mine[o].idx = ~0ull; }
-    if (n_rows) {
-#pragma unroll
-        for (int o = 0; o < N_OBJ; ++o) {
-            if (!((MASK >> o) & 1) || o == 2) continue;
-            // scalar keys: only minima were kept; the position is recovered where it can matter
-            const double *best = o == 0 ? bestE : (o == 1 ? bestL : bestP);
-            double mine_v = best[0];
-#pragma unroll
-            for (int c9 = 1; c9 < 9; ++c9) mine_v = fmin(mine_v, best[c9]);
-            const double wave_v = uniform_f64(wave_min_f64(mine_v));
-            if (!(wave_v < inf)) continue;
-            // a value some other item has already reached or beaten strictly cannot win
-            unsigned long long *hint = a.hints + (uint64_t)p * N_OBJ + o;
-            const double seen = __longlong_as_double((long long)__hip_atomic_load(hint, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            if (wave_v > seen) continue;
-            // the lowest combination in which some tiling reaches the minimum
-            uint32_t cstar = 9;
-#pragma unroll
-            for (int c9 = 8; c9 >= 0; --c9) cstar = best[c9] == wave_v ? (uint32_t)c9 : cstar;
-            const uint32_t c_u = __builtin_amdgcn_readfirstlane(wave_min_u32(cstar));
-            double gb_u = gb[0], latc_u = latc[0];
-#pragma unroll
-            for (int c9 = 1; c9 < 9; ++c9) {
-                gb_u = c_u == (uint32_t)c9 ? gb[c9] : gb_u;
-                latc_u = c_u == (uint32_t)c9 ? latc[c9] : latc_u;
-            }
-            // the first row (index order) in which a tiling reaches it, at its lowest such tiling
-            for (uint32_t i = 0; i < n_rows; ++i) {
-                const uint4 e = load_row(i);
-                double dram_words, e_part, l_dram, en, lat;
-                row_part(e, dram_words, e_part, l_dram);
-                combo_cost(dram_words, e_part, l_dram, gb_u, latc_u, en, lat);
-                const double val = o == 0 ? en : (o == 1 ? lat : en * lat);
-                const unsigned long long hits = __ballot(val == wave_v);
-                if (!hits) continue;
-                const uint32_t index_row = index_row_base(e.w) + 30000u * (c_u % 3) + 90000u * (c_u / 3);
-                mine[o].p = wave_v;
-                mine[o].idx = (uint64_t)t0 + ((uint32_t)__ffsll((long long)hits) - 1u) + (uint64_t)T * index_row;
-                break;
-            }
-            // (only a value that this wave's record really carries may turn other waves away)
-            if (lane == 0 && mine[o].p == wave_v)
-                __hip_atomic_fetch_min(hint, (unsigned long long)__double_as_longlong(wave_v), __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if constexpr (MASK & 4) {
-            Key k;
-            k.p = inf; k.s = 0.0; k.idx = ~0ull;
-#pragma unroll
-            for (int c9 = 0; c9 < 9; ++c9) {
-                // ascending combination = ascending index
-                if (bestLE_l[c9] < k.p || (bestLE_l[c9] == k.p && bestLE_e[c9] < k.s)) {
-                    const uint32_t dfrow = rows32[4 * codeLE[c9] + 3];
-                    k.p = bestLE_l[c9];
-                    k.s = bestLE_e[c9];
-                    k.idx = (uint64_t)(t0 + lane) + (uint64_t)T * (index_row_base(dfrow) + 30000u * (c9 % 3) + 90000u * (c9 / 3));
-                }
-            }
-            if (!(k.p < inf)) { k.s = 0.0; k.idx = ~0ull; }
-            mine[2] = wave_min(k);
-        }
-    }
-    if (lane == 0) {
+        ConstPtr<uint32_t> tail = as_constant(&pr->first_item);
+        const uint32_t t0 = (item - tail[0]) * BATCH_TC;
+        const uint32_t T = mc.T;
+        const uint32_t nt = min((uint32_t)BATCH_TC, T - t0);
+        ConstPtr<uint32_t> dvw = as_constant(reinterpret_cast<const uint32_t *>(&pr->dv));   // X[4], ndiv[4], div[4][MAXDIV]
+        const uint32_t nd0 = dvw[4], nd1 = dvw[5], nd2 = dvw[6], nd3 = dvw[7];
+        // what other items of this problem have reached so far (read early, used after the cost loop)
+        double seen[N_OBJ];
 #pragma unroll
         for (int o = 0; o < N_OBJ; ++o)
-            if ((MASK >> o) & 1) wave_best[o][wave] = mine[o];
-    }
-    __syncthreads();
+            seen[o] = ((MASK >> o) & 1) && o != 2
+                          ? __longlong_as_double((long long)__hip_atomic_load(a.hints + (uint64_t)p * N_OBJ + o, __ATOMIC_RELAXED,
+                                                                              __HIP_MEMORY_SCOPE_AGENT))
+                          : inf;
 
-    // ---- the item's record, then the problem's ticket
-    if (threadIdx.x == 0) {
-#pragma unroll
-        for (int o = 0; o < N_OBJ; ++o) {
-            if (!((MASK >> o) & 1)) continue;
-            Key k = wave_best[o][0];
-            for (int wv = 1; wv < BATCH_WAVES; ++wv)
-                if (key_less(wave_best[o][wv], k)) k = wave_best[o][wv];
-            Key *dst = a.item_keys + (uint64_t)item * N_OBJ + o;
-            __hip_atomic_store(&dst->idx, k.idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(reinterpret_cast<uint64_t *>(&dst->p), (uint64_t)__double_as_longlong(k.p), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(reinterpret_cast<uint64_t *>(&dst->s), (uint64_t)__double_as_longlong(k.s), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
+        if (staged_p != p) {
+            // a new problem: its divisor lists into LDS (the previous item's barriers have passed)
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(&pr->dv) + 8;
+            for (uint32_t k = threadIdx.x; k < 4 * MAXDIV; k += BATCH_THREADS) div_lds[k] = src[k];
+            staged_p = p;
+            __syncthreads();
         }
-        __threadfence();
-        const uint32_t ticket = __hip_atomic_fetch_add(a.tickets + p, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        is_last = ticket == n_chunks - 1;
-    }
-    __syncthreads();
-    if (!is_last) return;
 
-    // ---- the block that finished the problem's last item reduces the problem's records
-    __threadfence();
-    const uint32_t item0 = firsts[p];
+        // ---- decode: dimension q of every tiling of the chunk by wave q (beyond the chunk: its last
+        // tiling once more, masked out below)
+        if (wave < 4) {
+            const uint32_t t = t0 + min(lane, nt - 1);
+            const uint32_t radix = wave == 0 ? 1u : (wave == 1 ? nd0 : (wave == 2 ? nd0 * nd1 : nd0 * nd1 * nd2));
+            const uint32_t nq = wave == 0 ? nd0 : (wave == 1 ? nd1 : (wave == 2 ? nd2 : nd3));
+            const uint32_t g = div_lds[wave * MAXDIV + (t / radix) % nq];
+            gd[wave * BATCH_TC + lane] = (double)g;
+            gd[(4 + wave) * BATCH_TC + lane] = (double)(dvw[wave] / g);
+        }
+        __syncthreads();
+
+        // ---- build, first half: the six tile costs (one per wave) and the table entries the rows refer to
+        TilingF v;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { v.G[q] = gd[q * BATCH_TC + lane]; v.D[q] = gd[(4 + q) * BATCH_TC + lane]; }
+        const double X[4] = {(double)dvw[0], (double)dvw[1], (double)dvw[2], (double)dvw[3]};
+        if (wave < 6) {
+            double words, cycles;
+            if (wave < 3) tile_cost_f64((uint32_t)v.G[DI], (uint32_t)v.G[DK], (uint32_t)v.G[DL], wave, mc, words, cycles);
+            else tile_cost_f64((uint32_t)v.G[DI], (uint32_t)v.G[DL], (uint32_t)v.G[DJ], wave - 3, mc, words, cycles);
+            tc[(wave * 2) * BATCH_TC + lane] = words;
+            tc[(wave * 2 + 1) * BATCH_TC + lane] = cycles;
+        }
+        {
+            // one kind of table entry per wave (layout.h); the two waves without a tile cost take the 25-entry kinds
+            double *tab_lane = tab + lane;
+            double x[5], y[5];
+            switch (wave) {
+            case 0:                                           // BS_A[a] + BS_B[b]
+                footprints(x, v.G[DI] * v.G[DK], v.D[DI], v.D[DK]);
+                footprints(y, v.G[DK] * v.G[DL], v.D[DK], v.D[DL]);
+                stage_pair_sums<4, 4>(tab_lane, cmap_lds, ENT_BS_AB, x, y);
+                break;
+            case 1:                                           // BS_D[a] + BS_E[b]
+                footprints(x, v.G[DL] * v.G[DJ], v.D[DL], v.D[DJ]);
+                footprints(y, v.G[DI] * v.G[DJ], v.D[DI], v.D[DJ]);
+                stage_pair_sums<4, 4>(tab_lane, cmap_lds, ENT_BS_DE, x, y);
+                break;
+            case 6:                                           // tau_D BS_D[a] + tau_E BS_E[b]
+                footprints(x, v.G[DL] * v.G[DJ], v.D[DL], v.D[DJ]);
+                footprints(y, v.G[DI] * v.G[DJ], v.D[DI], v.D[DJ]);
+                stage_pair_sums<5, 5>(tab_lane, cmap_lds, ENT_RET_DE, x, y);
+                break;
+            case 7:                                           // tau_A BS_A[a] + tau_B BS_B[b]
+                footprints(x, v.G[DI] * v.G[DK], v.D[DI], v.D[DK]);
+                footprints(y, v.G[DK] * v.G[DL], v.D[DK], v.D[DL]);
+                stage_pair_sums<5, 5>(tab_lane, cmap_lds, ENT_RET_AB, x, y);
+                break;
+            case 2: {                                         // BS_C[c]; B*H * DA_C[c]
+                footprints(x, v.G[DI] * v.G[DL], v.D[DI], v.D[DL]);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint32_t at = cmap_lds[ENT_BS_C + c];
+                    if (at != 0xFFFFu) tab_lane[at * BATCH_TC] = x[c];
+                }
+#pragma unroll
+                for (int c = 0; c < 5; ++c) {
+                    // unfused C: spilled by Op1, fetched by Op2, one softmax pass over S and P; option 4: fused
+                    const double spill = (c & 1) ? v.D[DK] : 1.0, fetch = (c & 2) ? v.D[DJ] : 1.0;
+                    const uint32_t at = cmap_lds[ENT_DA_C + c];
+                    if (at != 0xFFFFu) tab_lane[at * BATCH_TC] = c >= 4 ? 0.0 : mc.BH * (X[DI] * X[DL]) * (spill + fetch + 2.0);
+                }
+                break;
+            }
+            case 3:                                           // B*H * (|A| {1, l_D, j_D, l_D j_D} + |B| {1, i_D, j_D, i_D j_D})
+                footprints(x, mc.BH * (X[DI] * X[DK]), v.D[DL], v.D[DJ]);
+                footprints(y, mc.BH * (X[DK] * X[DL]), v.D[DI], v.D[DJ]);
+                stage_pair_sums<4, 4>(tab_lane, cmap_lds, ENT_DA_AB, x, y);
+                break;
+            case 4:                                           // B*H * (|D| {1, i_D, k_D, i_D k_D} + |E| {1, k_D, l_D, k_D l_D})
+                footprints(x, mc.BH * (X[DL] * X[DJ]), v.D[DI], v.D[DK]);
+                footprints(y, mc.BH * (X[DI] * X[DJ]), v.D[DK], v.D[DL]);
+                stage_pair_sums<4, 4>(tab_lane, cmap_lds, ENT_DA_DE, x, y);
+                break;
+            default: break;
+            }
+        }
+        __syncthreads();
+        // ---- build, second half: the 18 (recomputation, combination) constant pairs, shared out over the waves
+        for (uint32_t job = wave; job < 18; job += BATCH_WAVES) {
+            const uint32_t rr = job / 9, c9 = job % 9, s1 = c9 % 3, s2 = c9 / 3;
+            const ComboTerms ct = combo_terms_from(v, X, mc, rr, tc[(s1 * 2) * BATCH_TC + lane], tc[(s1 * 2 + 1) * BATCH_TC + lane],
+                                                   tc[((3 + s2) * 2) * BATCH_TC + lane], tc[((3 + s2) * 2 + 1) * BATCH_TC + lane]);
+            double *cs = cst + rr * BATCH_NCS * BATCH_TC + lane;
+            cs[c9 * BATCH_TC] = REGROUP ? (mc.e_gb * (mc.BH * ct.br) + ct.e_rf_part) + ct.e_mac_part : mc.BH * ct.br;
+            cs[(9 + c9) * BATCH_TC] = ct.lat_part;
+            if (c9 == 0) { cs[18 * BATCH_TC] = ct.e_rf_part; cs[19 * BATCH_TC] = ct.e_mac_part; }
+        }
+        __syncthreads();
+
+        // ---- cost: this wave's rows against the chunk
+        const double cap = lane < nt ? mc.cap_words : -1.0;  // a lane beyond the chunk never passes the capacity test
+        double gb[9], latc[9];
+        {
+            const double *cs = cst + r * BATCH_NCS * BATCH_TC + lane;
+#pragma unroll
+            for (int c = 0; c < 9; ++c) { gb[c] = cs[c * BATCH_TC]; latc[c] = cs[(9 + c) * BATCH_TC]; }
+        }
+        const double e_rf_part = REGROUP ? 0.0 : cst[(r * BATCH_NCS + 18) * BATCH_TC + lane];
+        const double e_mac_part = REGROUP ? 0.0 : cst[(r * BATCH_NCS + 19) * BATCH_TC + lane];
+
+        double bestE[9], bestL[9], bestP[9], bestLE_l[9], bestLE_e[9];
+        uint32_t codeLE[9];
+#pragma unroll
+        for (int c9 = 0; c9 < 9; ++c9) { bestE[c9] = bestL[c9] = bestP[c9] = bestLE_l[c9] = bestLE_e[c9] = inf; codeLE[c9] = 0; }
+
+        // the row part of one (row, tiling): Eq. (1), (2), (4), capacity mask, B*H * Eq. (7)
+        auto row_part = [&](uint32_t i, double &dram_words, double &e_part, double &l_dram) {
+            const uint16_t *off = row_lds + (row_lo + i) * 8;
+            double w[NSEL];
+#pragma unroll
+            for (int k = 0; k < NSEL; ++k) w[k] = *reinterpret_cast<const double *>(tab_bytes + off[k]);
+            const bool ok = fmax(w[0] + w[2] + w[1], w[3] + w[2] + w[4]) <= cap;
+            dram_words = w[5] + w[6] + w[7];
+            e_part = (REGROUP ? mc.e_sum : mc.e_dram) * dram_words;
+            if constexpr (FAST) l_dram = dram_words * mc.dram_k;
+            else l_dram = mc.dram_bw > 0.0 ? mc.c_lat * (((dram_words / mc.BH) * mc.word) / mc.dram_bw) : 0.0;
+            const double over = __hiloint2double(ok ? 0 : 0x7ff00000, 0);
+            e_part = fmax(e_part, over);
+            l_dram = fmax(l_dram, over);
+            pin(e_part);
+            pin(l_dram);
+        };
+        auto combo_cost = [&](double dram_words, double e_part, double l_dram, double gb_c, double latc_c, double &en, double &lat) {
+            if constexpr (REGROUP) {
+                en = e_part + gb_c;
+            } else {
+                const double gb_words = dram_words + gb_c;
+                en = e_part + mc.e_gb * gb_words;
+                en = en + e_rf_part;
+                en = en + e_mac_part;
+            }
+            lat = fmax(l_dram, latc_c);
+        };
+
+        for (uint32_t i = 0; i < n_rows; ++i) {
+            double dram_words, e_part, l_dram;
+            row_part(i, dram_words, e_part, l_dram);
+#pragma unroll
+            for (int c9 = 0; c9 < 9; ++c9) {
+                double en, lat;
+                combo_cost(dram_words, e_part, l_dram, gb[c9], latc[c9], en, lat);
+                if constexpr (MASK & 1) bestE[c9] = fmin(bestE[c9], en);
+                if constexpr (MASK & 2) bestL[c9] = fmin(bestL[c9], lat);
+                if constexpr (MASK & 8) bestP[c9] = fmin(bestP[c9], en * lat);
+                if constexpr (MASK & 4) {
+                    // rows come in index order: a strict < keeps the lowest index on ties
+                    const bool lt = (lat < bestLE_l[c9]) | ((lat == bestLE_l[c9]) & (en < bestLE_e[c9]));
+                    bestLE_l[c9] = lt ? lat : bestLE_l[c9];
+                    bestLE_e[c9] = lt ? en : bestLE_e[c9];
+                    codeLE[c9] = lt ? i : codeLE[c9];
+                }
+            }
+        }
+
+        // ---- fold the item into the wave's running best
+        if (n_rows) {
+#pragma unroll
+            for (int o = 0; o < N_OBJ; ++o) {
+                if (!((MASK >> o) & 1) || o == 2) continue;
+                // scalar keys: only minima were kept; the position is recovered where it can matter
+                const double *best = o == 0 ? bestE : (o == 1 ? bestL : bestP);
+                double mine_v = best[0];
+#pragma unroll
+                for (int c9 = 1; c9 < 9; ++c9) mine_v = fmin(mine_v, best[c9]);
+                const double wave_v = uniform_f64(wave_min_f64(mine_v));
+                // nothing feasible; or this wave, or another item of the problem, already holds a lower value
+                if (!(wave_v < inf) || wave_v > run_p[o] || wave_v > seen[o]) continue;
+                // the lowest combination in which some tiling reaches the minimum
+                uint32_t cstar = 9;
+#pragma unroll
+                for (int c9 = 8; c9 >= 0; --c9) cstar = best[c9] == wave_v ? (uint32_t)c9 : cstar;
+                const uint32_t c_u = __builtin_amdgcn_readfirstlane(wave_min_u32(cstar));
+                const uint32_t combo_rows = 30000u * (c_u % 3) + 90000u * (c_u / 3);
+                // Index order is (combination, row, tiling).  An equal value only matters where it can sit at a
+                // lower index than the running best: in a lower combination; or in the same one in an earlier
+                // row, or in the same row if this chunk comes before the running best's.
+                uint32_t scan = n_rows;
+                if (wave_v == run_p[o]) {
+                    if (c_u > run_c[o]) continue;
+                    if (c_u == run_c[o]) scan = t0 < run_t0[o] ? run_i[o] + 1 : run_i[o];
+                }
+                double gb_u = gb[0], latc_u = latc[0];
+#pragma unroll
+                for (int c9 = 1; c9 < 9; ++c9) {
+                    gb_u = c_u == (uint32_t)c9 ? gb[c9] : gb_u;
+                    latc_u = c_u == (uint32_t)c9 ? latc[c9] : latc_u;
+                }
+                // the first row (index order) in which a tiling reaches it, at its lowest such tiling
+                for (uint32_t i = 0; i < scan; ++i) {
+                    double dram_words, e_part, l_dram, en, lat;
+                    row_part(i, dram_words, e_part, l_dram);
+                    combo_cost(dram_words, e_part, l_dram, gb_u, latc_u, en, lat);
+                    const double val = o == 0 ? en : (o == 1 ? lat : en * lat);
+                    const unsigned long long hits = __ballot(val == wave_v);
+                    if (!hits) continue;
+                    const uint64_t idx = (uint64_t)t0 + ((uint32_t)__ffsll((long long)hits) - 1u) +
+                                         (uint64_t)T * (index_row_base(row_df[row_lo + i]) + combo_rows);
+                    if (wave_v < run_p[o] || idx < run_idx[o]) {
+                        run_p[o] = wave_v; run_idx[o] = idx; run_c[o] = c_u; run_i[o] = i; run_t0[o] = t0;
+                        // (only a value that this wave's record will carry may turn other waves away)
+                        if (lane == 0)
+                            __hip_atomic_fetch_min(a.hints + (uint64_t)p * N_OBJ + o, (unsigned long long)__double_as_longlong(wave_v),
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    break;
+                }
+            }
+            if constexpr (MASK & 4) {
+                Key k;
+                k.p = inf; k.s = 0.0; k.idx = ~0ull;
+#pragma unroll
+                for (int c9 = 0; c9 < 9; ++c9) {
+                    // ascending combination = ascending index
+                    if (bestLE_l[c9] < k.p || (bestLE_l[c9] == k.p && bestLE_e[c9] < k.s)) {
+                        const uint32_t dfrow = a.row_df[row_lo + codeLE[c9]];
+                        k.p = bestLE_l[c9];
+                        k.s = bestLE_e[c9];
+                        k.idx = (uint64_t)(t0 + lane) + (uint64_t)T * (index_row_base(dfrow) + 30000u * (c9 % 3) + 90000u * (c9 / 3));
+                    }
+                }
+                if (!(k.p < inf)) { k.s = 0.0; k.idx = ~0ull; }
+                k = wave_min(k);
+                k.p = uniform_f64(k.p); k.s = uniform_f64(k.s);
+                if (key_less(k, run_le)) run_le = k;
+            }
+        }
+
+        // ---- after the stretch's last item its record leaves the block
+        const bool flush = visit + 1 == seg_len;
+        if (!flush) {
+            __syncthreads();                                 // every wave is done with the staged tables
+            continue;
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int o = 0; o < N_OBJ; ++o) {
+                if (!((MASK >> o) & 1)) continue;
+                Key k;
+                if (o == 2) k = run_le;
+                else { k.p = run_p[o]; k.s = 0.0; k.idx = run_idx[o]; }
+                wave_best[o][wave] = k;
+            }
+        }
+        reset_running();
+        __syncthreads();
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int o = 0; o < N_OBJ; ++o) {
+                if (!((MASK >> o) & 1)) continue;
+                Key k = wave_best[o][0];
+                for (int wv = 1; wv < BATCH_WAVES; ++wv)
+                    if (key_less(wave_best[o][wv], k)) k = wave_best[o][wv];
+                a.item_keys[(uint64_t)seg_first * N_OBJ + o] = k;       // read by the finish kernel, after this one
+            }
+        }
+        __syncthreads();                                     // wave_best and the staged tables are free again
+      }
+      seg_first = seg_end;
+    }
+}
+
+
+// After the search: one block per problem reduces the problem's records -- one per (block, problem)
+// stretch of the search launch, at the problem's first item and at every block boundary inside the
+// problem -- and writes the winner's full cost record and mapping.
+template <int MASK>
+__global__ __launch_bounds__(64) void k_batch_finish(BatchArgs a)
+{
+    const double inf = pos_inf();
+    const uint32_t p = blockIdx.x, lane = threadIdx.x;
+    const BatchProblem *pr = a.prob + p;
+    const uint32_t item0 = pr->first_item, n_chunks = pr->n_chunks, T = pr->mc.T;
+    const uint32_t inner0 = item0 / a.per_block + 1;         // first block boundary after the problem's first item
 #pragma unroll
     for (int o = 0; o < N_OBJ; ++o) {
         if (!((MASK >> o) & 1)) continue;
         Key k; k.p = inf; k.s = 0.0; k.idx = ~0ull;
-        for (uint32_t b = threadIdx.x; b < n_chunks; b += BATCH_THREADS) {
-            Key *src = a.item_keys + (uint64_t)(item0 + b) * N_OBJ + o;
-            Key c;
-            c.idx = __hip_atomic_load(&src->idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            c.p = __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<uint64_t *>(&src->p), __ATOMIC_RELAXED,
-                                                                    __HIP_MEMORY_SCOPE_AGENT));
-            c.s = __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<uint64_t *>(&src->s), __ATOMIC_RELAXED,
-                                                                    __HIP_MEMORY_SCOPE_AGENT));
+        for (uint32_t b = lane;; b += 64) {
+            const uint64_t at = b == 0 ? (uint64_t)item0 : (uint64_t)(inner0 + b - 1) * a.per_block;
+            if (at >= (uint64_t)item0 + n_chunks) break;
+            const Key c = a.item_keys[at * N_OBJ + o];
             if (key_less(c, k)) k = c;
         }
         k = wave_min(k);
-        if (lane == 0) wave_best[o][wave] = k;
-    }
-    __syncthreads();
-    if (threadIdx.x < N_OBJ && ((MASK >> threadIdx.x) & 1)) {
-        const int o = threadIdx.x;
-        Key k = wave_best[o][0];
-        for (int wv = 1; wv < BATCH_WAVES; ++wv)
-            if (key_less(wave_best[o][wv], k)) k = wave_best[o][wv];
-        FinalRecord *fr = a.final_out + (uint64_t)slot * N_OBJ + o;
+        if (lane != (uint32_t)o) continue;                   // lane o evaluates key o's winner
+        FinalRecord *fr = a.final_out + (uint64_t)pr->slot * N_OBJ + o;
         fr->key = k;
         mmee_cost c;
         mmee_mapping m;
         if (k.p < inf) {
-            eval_candidate_direct(a.enc, pr->dv, mc, k.idx, c);
+            eval_candidate_direct(a.enc, pr->dv, pr->mc, k.idx, c);
             decode_candidate(pr->dv, T, k.idx, m);
         } else {
             c.bs_words = c.da_words = c.br_words = c.mac_total = c.comp_cycles = 0;

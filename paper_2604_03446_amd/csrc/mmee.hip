@@ -97,10 +97,12 @@ struct State {
     size_t batch_blob_cap = 0;
     Key *item_keys = nullptr;
     size_t item_cap = 0;
-    uint32_t *batch_tickets = nullptr;
     unsigned long long *batch_hints = nullptr;
     size_t batch_prob_cap = 0;
-    uint32_t task_off[BATCH_WAVES] = {}, task_cnt[BATCH_WAVES] = {}, task_g[BATCH_WAVES] = {};
+    uint32_t task_lo[BATCH_WAVES] = {}, task_cnt[BATCH_WAVES] = {}, task_g[BATCH_WAVES] = {};
+    uint32_t *batch_row_off = nullptr, *batch_row_df = nullptr, *batch_cmap = nullptr;
+    uint32_t batch_rows = 0, batch_n_used = 0;
+    bool batch_ok = false;      // the surviving rows fit the batched kernel's fixed LDS layout
 } S;
 
 // The device buffers one search pass works in.  The allocating entry points fill this from the
@@ -323,12 +325,51 @@ int ensure_ready()
         S.n_cls = (uint32_t)cls.size();
     }
     {
-        // batched search: share the surviving rows of each group out over the waves of a block, every
-        // wave a contiguous piece of one group's list (rows of one group share r and f)
-        uint32_t waves[N_GROUPS] = {0, 0, 0, 0}, used = 0;
+        // Batched search over the surviving rows.  The rows refer to a subset of the table entries only:
+        // the kernel stages just those, and a row becomes the eight byte offsets of its values in that
+        // compact table.  Lists follow each other group by group.
+        std::vector<uint4> rows;
+        std::vector<uint32_t> group_first(N_GROUPS + 1, 0);
+        for (uint32_t g = 0; g < N_GROUPS; ++g) {
+            const uint32_t n = S.counts[1][g];
+            group_first[g] = (uint32_t)rows.size();
+            if (!n) continue;
+            rows.resize(rows.size() + n);
+            HIP_TRY(hipMemcpy(rows.data() + group_first[g], S.row_enc[1] + (size_t)g * ROWS_PER_GROUP, sizeof(uint4) * n,
+                              hipMemcpyDeviceToHost));
+        }
+        group_first[N_GROUPS] = (uint32_t)rows.size();
+        auto sel_at = [](const uint4 &e, int k) { const uint32_t w = k < 4 ? e.x : e.y; return (w >> (8 * (k & 3))) & 0xFFu; };
+        std::vector<int> compact(NENT, -1);
+        std::vector<uint32_t> used;
+        for (const uint4 &e : rows)
+            for (int k = 0; k < NSEL; ++k) compact[sel_at(e, k)] = 0;
+        for (uint32_t ent = 0; ent < (uint32_t)NENT; ++ent)
+            if (compact[ent] == 0) { compact[ent] = (int)used.size(); used.push_back(ent); }
+        S.batch_rows = (uint32_t)rows.size();
+        S.batch_n_used = (uint32_t)used.size();
+        S.batch_ok = !rows.empty() && rows.size() <= BATCH_MAX_ROWS && used.size() <= BATCH_MAX_USED;
+        if (S.batch_ok) {
+            std::vector<uint32_t> off(rows.size() * 8), df(rows.size());
+            for (size_t i = 0; i < rows.size(); ++i) {
+                for (int k = 0; k < NSEL; ++k) off[i * 8 + k] = (uint32_t)compact[sel_at(rows[i], k)] * BATCH_TC * 8u;
+                df[i] = rows[i].w;
+            }
+            HIP_TRY(hipMalloc(&S.batch_row_off, sizeof(uint32_t) * off.size()));
+            HIP_TRY(hipMalloc(&S.batch_row_df, sizeof(uint32_t) * df.size()));
+            std::vector<uint32_t> cmap(NENT);
+            for (int ent = 0; ent < NENT; ++ent) cmap[ent] = compact[ent] < 0 ? 0xFFFFu : (uint32_t)compact[ent];
+            HIP_TRY(hipMalloc(&S.batch_cmap, sizeof(uint32_t) * NENT));
+            HIP_TRY(hipMemcpy(S.batch_row_off, off.data(), sizeof(uint32_t) * off.size(), hipMemcpyHostToDevice));
+            HIP_TRY(hipMemcpy(S.batch_row_df, df.data(), sizeof(uint32_t) * df.size(), hipMemcpyHostToDevice));
+            HIP_TRY(hipMemcpy(S.batch_cmap, cmap.data(), sizeof(uint32_t) * NENT, hipMemcpyHostToDevice));
+        }
+        // share the rows of each group out over the waves of a block, every wave a contiguous piece of
+        // one group's list (rows of one group share r and f)
+        uint32_t waves[N_GROUPS] = {0, 0, 0, 0}, taken = 0;
         for (uint32_t g = 0; g < N_GROUPS; ++g)
-            if (S.counts[1][g]) { waves[g] = 1; ++used; }
-        while (used < BATCH_WAVES) {
+            if (S.counts[1][g]) { waves[g] = 1; ++taken; }
+        while (taken < BATCH_WAVES) {
             uint32_t worst = N_GROUPS, most = 0;
             for (uint32_t g = 0; g < N_GROUPS; ++g) {
                 if (!waves[g]) continue;
@@ -336,16 +377,16 @@ int ensure_ready()
                 if (per > most) { most = per; worst = g; }
             }
             if (worst == N_GROUPS || most <= 1) break;
-            ++waves[worst]; ++used;
+            ++waves[worst]; ++taken;
         }
         uint32_t wv = 0;
         for (uint32_t g = 0; g < N_GROUPS; ++g)
             for (uint32_t k = 0; k < waves[g]; ++k, ++wv) {
                 const uint32_t n = S.counts[1][g], lo = (uint32_t)((uint64_t)n * k / waves[g]),
                                hi = (uint32_t)((uint64_t)n * (k + 1) / waves[g]);
-                S.task_off[wv] = g * ROWS_PER_GROUP + lo; S.task_cnt[wv] = hi - lo; S.task_g[wv] = g;
+                S.task_lo[wv] = group_first[g] + lo; S.task_cnt[wv] = hi - lo; S.task_g[wv] = g;
             }
-        for (; wv < BATCH_WAVES; ++wv) { S.task_off[wv] = 0; S.task_cnt[wv] = 0; S.task_g[wv] = 0; }
+        for (; wv < BATCH_WAVES; ++wv) { S.task_lo[wv] = 0; S.task_cnt[wv] = 0; S.task_g[wv] = 0; }
     }
     S.ready = true;
     return MMEE_OK;
@@ -664,10 +705,9 @@ int ensure_batch(size_t blob_bytes, size_t n_prob, size_t n_items)
         S.item_cap = cap;
     }
     if (n_prob > S.batch_prob_cap) {
-        if (S.batch_tickets) { HIP_TRY(hipStreamSynchronize(S.stream)); (void)hipFree(S.batch_tickets); (void)hipFree(S.batch_hints); }
-        S.batch_tickets = nullptr; S.batch_hints = nullptr; S.batch_prob_cap = 0;
+        if (S.batch_hints) { HIP_TRY(hipStreamSynchronize(S.stream)); (void)hipFree(S.batch_hints); }
+        S.batch_hints = nullptr; S.batch_prob_cap = 0;
         const size_t cap = std::max<size_t>(n_prob * 2, 64);
-        HIP_TRY(hipMalloc(&S.batch_tickets, sizeof(uint32_t) * cap));
         HIP_TRY(hipMalloc(&S.batch_hints, sizeof(unsigned long long) * N_OBJ * cap));
         S.batch_prob_cap = cap;
     }
@@ -680,6 +720,8 @@ void launch_batch_mask(bool fast, bool regroup, dim3 grid, const BatchArgs &a)
     if (regroup) hipLaunchKernelGGL((k_search_batch<MASK, true, true>), grid, dim3(BATCH_THREADS), 0, S.stream, a);
     else if (fast) hipLaunchKernelGGL((k_search_batch<MASK, true, false>), grid, dim3(BATCH_THREADS), 0, S.stream, a);
     else hipLaunchKernelGGL((k_search_batch<MASK, false, false>), grid, dim3(BATCH_THREADS), 0, S.stream, a);
+    // the problems' records are complete when the search kernel has ended: one block per problem finishes
+    hipLaunchKernelGGL((k_batch_finish<MASK>), dim3(a.n_prob), dim3(64), 0, S.stream, a);
 }
 
 // One problem of a batched launch, as the host sees it.
@@ -752,8 +794,7 @@ int enqueue_batches(std::vector<BatchEntry> &entries, uint32_t flags, size_t ev_
     }
     HIP_TRY(hipMemcpyAsync(S.batch_dev, S.batch_host, off, hipMemcpyHostToDevice, S.stream));
     const uint32_t n_init = (uint32_t)entries.size() * N_OBJ;
-    hipLaunchKernelGGL(k_batch_init, dim3((n_init + 255) / 256), dim3(256), 0, S.stream, S.batch_tickets, S.batch_hints,
-                       (uint32_t)entries.size());
+    hipLaunchKernelGGL(k_batch_init, dim3((n_init + 255) / 256), dim3(256), 0, S.stream, S.batch_hints, (uint32_t)entries.size());
     HIP_TRY(hipEventRecord(S.events[2 * ev_slot], S.stream));
     for (size_t k = 0; k < variants.size(); ++k) {
         const Variant &v = variants[k];
@@ -763,13 +804,16 @@ int enqueue_batches(std::vector<BatchEntry> &entries, uint32_t flags, size_t ev_
         a.prob = reinterpret_cast<const BatchProblem *>(S.batch_dev + L.desc_off);
         a.first_items = reinterpret_cast<const uint32_t *>(S.batch_dev + L.firsts_off);
         a.n_prob = (uint32_t)L.n_prob; a.n_items = (uint32_t)L.n_items;
-        a.enc = S.enc; a.row_enc = S.row_enc[1];
-        for (int wv = 0; wv < BATCH_WAVES; ++wv) { a.task_off[wv] = S.task_off[wv]; a.task_cnt[wv] = S.task_cnt[wv]; a.task_g[wv] = S.task_g[wv]; }
+        a.enc = S.enc;
+        a.row_off = S.batch_row_off; a.row_df = S.batch_row_df; a.cmap = S.batch_cmap;
+        a.n_rows = S.batch_rows; a.n_used = S.batch_n_used;
+        for (int wv = 0; wv < BATCH_WAVES; ++wv) { a.task_lo[wv] = S.task_lo[wv]; a.task_cnt[wv] = S.task_cnt[wv]; a.task_g[wv] = S.task_g[wv]; }
         a.item_keys = S.item_keys + N_OBJ * L.item0;
-        a.tickets = S.batch_tickets + L.prob0;
         a.hints = S.batch_hints + N_OBJ * L.prob0;
         a.final_out = S.final_map;
-        dim3 grid((uint32_t)L.n_items);
+        // persistent blocks, two per CU, each with a contiguous range of the items
+        dim3 grid((uint32_t)std::min<uint64_t>(L.n_items, (uint64_t)S.resident_blocks));
+        a.per_block = (uint32_t)((L.n_items + grid.x - 1) / grid.x);
         switch (v.mask) {
         case 1: launch_batch_mask<1>(v.fast, v.regroup, grid, a); break;
         case 2: launch_batch_mask<2>(v.fast, v.regroup, grid, a); break;
@@ -1061,7 +1105,7 @@ int mmee_chain_search_many(const mmee_chain *w, const mmee_hw *hw, const int *ob
         for (size_t s = 0; s < passes.size(); ++s) {
             Pass &ps = passes[s];
             if (ps.rc != MMEE_OK || (only_unproven && !ps.unproven)) continue;
-            ps.batched = !(round_flags & MMEE_SEARCH_EXHAUSTIVE) && batch_mask(ps.mask);
+            ps.batched = S.batch_ok && !(round_flags & MMEE_SEARCH_EXHAUSTIVE) && batch_mask(ps.mask);
             if (ps.batched) {
                 BatchEntry e;
                 e.plan = &ps.plan; e.mask = ps.mask; e.slot = s; e.unproven = false; e.evaluated = 0;
@@ -1370,7 +1414,8 @@ void mmee_shutdown(void)
     (void)hipFree(S.dv_dev); (void)hipFree(S.eval_dev);
     if (S.final_host) (void)hipHostFree(S.final_host);
     if (S.batch_host) (void)hipHostFree(S.batch_host);
-    (void)hipFree(S.batch_dev); (void)hipFree(S.item_keys); (void)hipFree(S.batch_tickets); (void)hipFree(S.batch_hints);
+    (void)hipFree(S.batch_dev); (void)hipFree(S.item_keys); (void)hipFree(S.batch_hints);
+    (void)hipFree(S.batch_row_off); (void)hipFree(S.batch_row_df); (void)hipFree(S.batch_cmap);
     for (hipEvent_t e : S.events) (void)hipEventDestroy(e);
     hipStream_t keep = S.stream;
     S = State();
