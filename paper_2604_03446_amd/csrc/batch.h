@@ -5,11 +5,13 @@
 // (Sec. VII-H, VII-I) is bound by launches and table traffic unless the problems share a launch.
 // Here one work item is (problem, chunk of 64 tilings) and a block builds the chunk's slice of the
 // boundary-side tables straight into LDS, from the problem's divisor lists: nothing per tiling ever
-// touches HBM.  Lane = tiling, wave = a contiguous share of one group's row list, so a row's
-// selectors are wave-uniform (scalar loads) and the per-tiling constants of the nine stationary
-// combinations sit in registers for the whole item.  Each item leaves one (key, index) record per
-// objective; the block that finishes a problem's last item reduces the problem's records and writes
-// the winner's full cost record and mapping.
+// touches HBM.  Lane = tiling, wave = a contiguous piece of one group's row list, so a row's table
+// offsets are wave-uniform and the per-tiling constants of the nine stationary combinations sit in
+// registers for the whole item.  Only the table entries that the rows refer to are staged (77 of 123
+// for the pruned rows), which lets two 512-thread blocks share a CU.  A block takes a contiguous range
+// of items, waves carry their best (value, index) across the items of a problem, and each (block,
+// problem) stretch leaves one record per key; k_batch_finish, launched behind the search, reduces a
+// problem's records and writes the winner's full cost record and mapping.
 //
 // Included once by mmee.hip, after kernels.h.
 #pragma once
@@ -23,12 +25,13 @@ constexpr int BATCH_TC = 64;                 // tilings per item = lanes of a wa
 constexpr int BATCH_NCS = 20;                // constants per (tiling, r), as in layout.h
 constexpr int BATCH_MAX_USED = 80;           // table entries the row lists may refer to (the pruned rows use 77)
 constexpr int BATCH_MAX_ROWS = 288;          // rows the lists may hold (the pruned lists hold 270)
+constexpr int BATCH_MAX_SPLIT = 4;           // blocks that may share the rows of one chunk (small launches)
 
 struct BatchProblem {                        // one problem, in device memory
     DivTable dv;
     ModelConst mc;
     uint32_t first_item;                     // its first work item in the launch
-    uint32_t n_chunks;                       // its work items
+    uint32_t n_work;                         // its work items: chunks of 64 tilings x row shares
     uint32_t slot;                           // where its N_OBJ final records go
     uint32_t pad_;
 };
@@ -43,12 +46,14 @@ struct BatchArgs {
     const uint32_t *row_df;                  // [n_rows] the rows' numbers (levels/order + 15000 * (r + 2 f))
     const uint32_t *cmap;                    // [NENT] table entry -> its place in the staged table, 0xFFFF when no row refers to it
     uint32_t n_rows, n_used;
-    uint32_t task_lo[BATCH_WAVES];           // per wave: its first row in the lists,
-    uint32_t task_cnt[BATCH_WAVES];          //           how many rows it takes,
-    uint32_t task_g[BATCH_WAVES];            //           and the group g = r + 2 f they belong to
+    // A chunk's rows are shared out over `split` work items (1 in a large launch; more when the launch
+    // would otherwise leave most of the chip idle), and inside a work item over the waves of the block.
+    uint32_t split;
+    uint32_t task_lo[BATCH_MAX_SPLIT * BATCH_WAVES];     // per (share, wave): its first row in the lists,
+    uint32_t task_cnt[BATCH_MAX_SPLIT * BATCH_WAVES];    //                    how many rows it takes,
+    uint32_t task_g[BATCH_MAX_SPLIT * BATCH_WAVES];      //                    and the group g = r + 2 f they belong to
     Key *item_keys;                          // [n_items][N_OBJ]; written at the first item of every (block, problem) stretch
     uint32_t per_block;                      // items per block of the search launch (the finish kernel needs it)
-    unsigned long long *hints;               // [n_prob][N_OBJ] lowest value seen so far (bits of a non-negative fp64)
     FinalRecord *final_out;                  // [result slot][N_OBJ]
 };
 
@@ -216,13 +221,6 @@ __device__ __forceinline__ void eval_candidate_direct(const uint4 *enc, const Di
     c.valid = 1; c.reason = 0;
 }
 
-// hints start at +inf
-__global__ void k_batch_init(unsigned long long *hints, uint32_t n_prob)
-{
-    const uint32_t a = blockIdx.x * blockDim.x + threadIdx.x;
-    if (a < n_prob * N_OBJ) hints[a] = 0x7ff0000000000000ull;
-}
-
 // The table entries of one kind, for this lane's tiling, into the staged table: x[a] + y[b] for every
 // option pair (na x nb of them, entry number first + a + na * b), each at the place cmap gives it.
 template <int NA, int NB>
@@ -280,16 +278,13 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
         }
         p = lo;
     }
-    // this wave's share of one group's rows
-    const uint32_t n_rows = a.task_cnt[wave], row_lo = a.task_lo[wave], r = a.task_g[wave] & 1;
     ConstPtr<uint32_t> row_df = as_constant(a.row_df);
-    const uint32_t first_index_row = n_rows ? index_row_base(row_df[row_lo]) : 0u;
     const char *tab_bytes = reinterpret_cast<const char *>(tab) + lane * 8;
 
     // the wave's running best over the items of the current problem
     double run_p[N_OBJ];
     uint64_t run_idx[N_OBJ];
-    uint32_t run_c[N_OBJ], run_i[N_OBJ], run_t0[N_OBJ];      // its combination, its row (place in this wave's share), its chunk
+    uint32_t run_c[N_OBJ], run_i[N_OBJ], run_t0[N_OBJ];      // its combination, its row (place in the row lists), its chunk
     Key run_le;
     auto reset_running = [&]() {
 #pragma unroll
@@ -325,20 +320,15 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
             __builtin_memcpy(&mc, buf, sizeof(ModelConst));
         }
         ConstPtr<uint32_t> tail = as_constant(&pr->first_item);
-        const uint32_t t0 = (item - tail[0]) * BATCH_TC;
+        const uint32_t work = item - tail[0];
+        const uint32_t t0 = work / a.split * BATCH_TC;
+        // this wave's piece of one group's rows, within the work item's share of the chunk's rows
+        const uint32_t task = (work % a.split) * BATCH_WAVES + wave;
+        const uint32_t n_rows = a.task_cnt[task], row_lo = a.task_lo[task], r = a.task_g[task] & 1;
         const uint32_t T = mc.T;
         const uint32_t nt = min((uint32_t)BATCH_TC, T - t0);
         ConstPtr<uint32_t> dvw = as_constant(reinterpret_cast<const uint32_t *>(&pr->dv));   // X[4], ndiv[4], div[4][MAXDIV]
         const uint32_t nd0 = dvw[4], nd1 = dvw[5], nd2 = dvw[6], nd3 = dvw[7];
-        // what other items of this problem have reached so far (read early, used after the cost loop)
-        double seen[N_OBJ];
-#pragma unroll
-        for (int o = 0; o < N_OBJ; ++o)
-            seen[o] = ((MASK >> o) & 1) && o != 2
-                          ? __longlong_as_double((long long)__hip_atomic_load(a.hints + (uint64_t)p * N_OBJ + o, __ATOMIC_RELAXED,
-                                                                              __HIP_MEMORY_SCOPE_AGENT))
-                          : inf;
-
         if (staged_p != p) {
             // a new problem: its divisor lists into LDS (the previous item's barriers have passed)
             const uint32_t *src = reinterpret_cast<const uint32_t *>(&pr->dv) + 8;
@@ -514,8 +504,8 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
 #pragma unroll
                 for (int c9 = 1; c9 < 9; ++c9) mine_v = fmin(mine_v, best[c9]);
                 const double wave_v = uniform_f64(wave_min_f64(mine_v));
-                // nothing feasible; or this wave, or another item of the problem, already holds a lower value
-                if (!(wave_v < inf) || wave_v > run_p[o] || wave_v > seen[o]) continue;
+                // nothing feasible, or this wave already holds a lower value
+                if (!(wave_v < inf) || wave_v > run_p[o]) continue;
                 // the lowest combination in which some tiling reaches the minimum
                 uint32_t cstar = 9;
 #pragma unroll
@@ -525,10 +515,14 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
                 // Index order is (combination, row, tiling).  An equal value only matters where it can sit at a
                 // lower index than the running best: in a lower combination; or in the same one in an earlier
                 // row, or in the same row if this chunk comes before the running best's.
+                // (A wave's pieces all lie in one group's list, whatever the share: list places compare like indices.)
                 uint32_t scan = n_rows;
                 if (wave_v == run_p[o]) {
                     if (c_u > run_c[o]) continue;
-                    if (c_u == run_c[o]) scan = t0 < run_t0[o] ? run_i[o] + 1 : run_i[o];
+                    if (c_u == run_c[o]) {
+                        const uint32_t upto = t0 < run_t0[o] ? run_i[o] + 1 : run_i[o];    // list places below this one matter
+                        scan = upto > row_lo ? min(upto - row_lo, n_rows) : 0u;
+                    }
                 }
                 double gb_u = gb[0], latc_u = latc[0];
 #pragma unroll
@@ -547,11 +541,7 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
                     const uint64_t idx = (uint64_t)t0 + ((uint32_t)__ffsll((long long)hits) - 1u) +
                                          (uint64_t)T * (index_row_base(row_df[row_lo + i]) + combo_rows);
                     if (wave_v < run_p[o] || idx < run_idx[o]) {
-                        run_p[o] = wave_v; run_idx[o] = idx; run_c[o] = c_u; run_i[o] = i; run_t0[o] = t0;
-                        // (only a value that this wave's record will carry may turn other waves away)
-                        if (lane == 0)
-                            __hip_atomic_fetch_min(a.hints + (uint64_t)p * N_OBJ + o, (unsigned long long)__double_as_longlong(wave_v),
-                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        run_p[o] = wave_v; run_idx[o] = idx; run_c[o] = c_u; run_i[o] = row_lo + i; run_t0[o] = t0;
                     }
                     break;
                 }
@@ -615,32 +605,46 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
 // stretch of the search launch, at the problem's first item and at every block boundary inside the
 // problem -- and writes the winner's full cost record and mapping.
 template <int MASK>
-__global__ __launch_bounds__(64) void k_batch_finish(BatchArgs a)
+__global__ __launch_bounds__(256) void k_batch_finish(BatchArgs a)
 {
+    __shared__ Key wave_best[N_OBJ][4];
+    __shared__ BatchProblem prob_s;                          // the problem's description, fetched while the records arrive
     const double inf = pos_inf();
-    const uint32_t p = blockIdx.x, lane = threadIdx.x;
+    const uint32_t p = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    {
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(a.prob + p);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(&prob_s);
+        for (uint32_t k = threadIdx.x; k < sizeof(BatchProblem) / 4; k += 256) dst[k] = src[k];
+    }
     const BatchProblem *pr = a.prob + p;
-    const uint32_t item0 = pr->first_item, n_chunks = pr->n_chunks, T = pr->mc.T;
+    const uint32_t item0 = pr->first_item, n_work = pr->n_work;
     const uint32_t inner0 = item0 / a.per_block + 1;         // first block boundary after the problem's first item
 #pragma unroll
     for (int o = 0; o < N_OBJ; ++o) {
         if (!((MASK >> o) & 1)) continue;
         Key k; k.p = inf; k.s = 0.0; k.idx = ~0ull;
-        for (uint32_t b = lane;; b += 64) {
+        for (uint32_t b = threadIdx.x;; b += 256) {
             const uint64_t at = b == 0 ? (uint64_t)item0 : (uint64_t)(inner0 + b - 1) * a.per_block;
-            if (at >= (uint64_t)item0 + n_chunks) break;
+            if (at >= (uint64_t)item0 + n_work) break;
             const Key c = a.item_keys[at * N_OBJ + o];
             if (key_less(c, k)) k = c;
         }
         k = wave_min(k);
-        if (lane != (uint32_t)o) continue;                   // lane o evaluates key o's winner
-        FinalRecord *fr = a.final_out + (uint64_t)pr->slot * N_OBJ + o;
+        if (lane == 0) wave_best[o][wave] = k;
+    }
+    __syncthreads();
+    if (threadIdx.x < N_OBJ && ((MASK >> threadIdx.x) & 1)) {
+        const int o = threadIdx.x;
+        Key k = wave_best[o][0];
+        for (int wv = 1; wv < 4; ++wv)
+            if (key_less(wave_best[o][wv], k)) k = wave_best[o][wv];
+        FinalRecord *fr = a.final_out + (uint64_t)prob_s.slot * N_OBJ + o;
         fr->key = k;
         mmee_cost c;
         mmee_mapping m;
         if (k.p < inf) {
-            eval_candidate_direct(a.enc, pr->dv, pr->mc, k.idx, c);
-            decode_candidate(pr->dv, T, k.idx, m);
+            eval_candidate_direct(a.enc, prob_s.dv, prob_s.mc, k.idx, c);
+            decode_candidate(prob_s.dv, prob_s.mc.T, k.idx, m);
         } else {
             c.bs_words = c.da_words = c.br_words = c.mac_total = c.comp_cycles = 0;
             c.energy_pj = inf; c.latency_cycles = inf; c.valid = 0; c.reason = 0;

@@ -92,13 +92,11 @@ struct State {
     size_t eval_cap = 0;
     uint32_t resident_blocks = 512;
     // batched search over the pruned rows: problem descriptors (pinned staging + device copy), one record
-    // per item and objective, one ticket and N_OBJ hints per problem; the split of the row lists over waves
+    // per work item and objective; the split of the row lists over the waves of a block
     unsigned char *batch_host = nullptr, *batch_dev = nullptr;
     size_t batch_blob_cap = 0;
     Key *item_keys = nullptr;
     size_t item_cap = 0;
-    unsigned long long *batch_hints = nullptr;
-    size_t batch_prob_cap = 0;
     uint32_t task_lo[BATCH_WAVES] = {}, task_cnt[BATCH_WAVES] = {}, task_g[BATCH_WAVES] = {};
     uint32_t *batch_row_off = nullptr, *batch_row_df = nullptr, *batch_cmap = nullptr;
     uint32_t batch_rows = 0, batch_n_used = 0;
@@ -687,7 +685,7 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
 // masks the batched kernel is built for; other key sets take the per-problem kernels
 bool batch_mask(int mask) { return mask == 1 || mask == 2 || mask == 3 || mask == 4 || mask == 8; }
 
-int ensure_batch(size_t blob_bytes, size_t n_prob, size_t n_items)
+int ensure_batch(size_t blob_bytes, size_t n_items)
 {
     if (blob_bytes > S.batch_blob_cap) {
         if (S.batch_host) { HIP_TRY(hipStreamSynchronize(S.stream)); (void)hipHostFree(S.batch_host); (void)hipFree(S.batch_dev); }
@@ -704,13 +702,6 @@ int ensure_batch(size_t blob_bytes, size_t n_prob, size_t n_items)
         HIP_TRY(hipMalloc(&S.item_keys, sizeof(Key) * N_OBJ * cap));
         S.item_cap = cap;
     }
-    if (n_prob > S.batch_prob_cap) {
-        if (S.batch_hints) { HIP_TRY(hipStreamSynchronize(S.stream)); (void)hipFree(S.batch_hints); }
-        S.batch_hints = nullptr; S.batch_prob_cap = 0;
-        const size_t cap = std::max<size_t>(n_prob * 2, 64);
-        HIP_TRY(hipMalloc(&S.batch_hints, sizeof(unsigned long long) * N_OBJ * cap));
-        S.batch_prob_cap = cap;
-    }
     return MMEE_OK;
 }
 
@@ -721,7 +712,7 @@ void launch_batch_mask(bool fast, bool regroup, dim3 grid, const BatchArgs &a)
     else if (fast) hipLaunchKernelGGL((k_search_batch<MASK, true, false>), grid, dim3(BATCH_THREADS), 0, S.stream, a);
     else hipLaunchKernelGGL((k_search_batch<MASK, false, false>), grid, dim3(BATCH_THREADS), 0, S.stream, a);
     // the problems' records are complete when the search kernel has ended: one block per problem finishes
-    hipLaunchKernelGGL((k_batch_finish<MASK>), dim3(a.n_prob), dim3(64), 0, S.stream, a);
+    hipLaunchKernelGGL((k_batch_finish<MASK>), dim3(a.n_prob), dim3(256), 0, S.stream, a);
 }
 
 // One problem of a batched launch, as the host sees it.
@@ -739,7 +730,7 @@ struct BatchEntry {
 int enqueue_batches(std::vector<BatchEntry> &entries, uint32_t flags, size_t ev_slot)
 {
     if (entries.empty()) return MMEE_OK;
-    struct Variant { int mask; bool fast, regroup; std::vector<size_t> members; uint64_t items = 0; };
+    struct Variant { int mask; bool fast, regroup; std::vector<size_t> members; uint64_t items = 0; uint32_t split = 1; };
     std::vector<Variant> variants;
     uint64_t kept_rows = 0;
     for (int g = 0; g < 4; ++g) kept_rows += S.counts[1][g];
@@ -752,16 +743,21 @@ int enqueue_batches(std::vector<BatchEntry> &entries, uint32_t flags, size_t ev_
         Variant *v = nullptr;
         for (Variant &c : variants)
             if (c.mask == e.mask && c.fast == fast && c.regroup == regroup) v = &c;
-        if (!v) { variants.push_back(Variant{e.mask, fast, regroup, {}, 0}); v = &variants.back(); }
+        if (!v) { variants.push_back(Variant{e.mask, fast, regroup, {}, 0, 1}); v = &variants.back(); }
         v->members.push_back(k);
         v->items += (e.plan->T + BATCH_TC - 1) / BATCH_TC;
-        total_items += (e.plan->T + BATCH_TC - 1) / BATCH_TC;
+    }
+    for (Variant &v : variants) {
+        // a launch with few chunks leaves most of the chip idle: let several blocks share a chunk's rows
+        while (v.split < BATCH_MAX_SPLIT && v.items * v.split * 2 <= S.resident_blocks) v.split *= 2;
+        v.items *= v.split;
+        total_items += v.items;
     }
     if (total_items > 0x7fffffffull) return MMEE_EINVAL;
     // blob: per variant its problem descriptors, then its first-item table
     size_t blob = 0;
     for (const Variant &v : variants) blob += sizeof(BatchProblem) * v.members.size() + sizeof(uint32_t) * ((v.members.size() + 1 + 3) & ~(size_t)3);
-    int rc = ensure_batch(blob, entries.size(), total_items);
+    int rc = ensure_batch(blob, total_items);
     if (rc) return rc;
     size_t off = 0, prob0 = 0;
     uint64_t item0 = 0;
@@ -781,11 +777,11 @@ int enqueue_batches(std::vector<BatchEntry> &entries, uint32_t flags, size_t ev_
             bp[k].dv = e.plan->dv;
             bp[k].mc = e.mc;
             bp[k].first_item = item;
-            bp[k].n_chunks = (uint32_t)((e.plan->T + BATCH_TC - 1) / BATCH_TC);
+            bp[k].n_work = (uint32_t)((e.plan->T + BATCH_TC - 1) / BATCH_TC) * v.split;
             bp[k].slot = (uint32_t)e.slot;
             bp[k].pad_ = 0;
             firsts[k] = item;
-            item += bp[k].n_chunks;
+            item += bp[k].n_work;
         }
         firsts[v.members.size()] = item;
         prob0 += v.members.size();
@@ -793,8 +789,6 @@ int enqueue_batches(std::vector<BatchEntry> &entries, uint32_t flags, size_t ev_
         launches.push_back(L);
     }
     HIP_TRY(hipMemcpyAsync(S.batch_dev, S.batch_host, off, hipMemcpyHostToDevice, S.stream));
-    const uint32_t n_init = (uint32_t)entries.size() * N_OBJ;
-    hipLaunchKernelGGL(k_batch_init, dim3((n_init + 255) / 256), dim3(256), 0, S.stream, S.batch_hints, (uint32_t)entries.size());
     HIP_TRY(hipEventRecord(S.events[2 * ev_slot], S.stream));
     for (size_t k = 0; k < variants.size(); ++k) {
         const Variant &v = variants[k];
@@ -807,9 +801,16 @@ int enqueue_batches(std::vector<BatchEntry> &entries, uint32_t flags, size_t ev_
         a.enc = S.enc;
         a.row_off = S.batch_row_off; a.row_df = S.batch_row_df; a.cmap = S.batch_cmap;
         a.n_rows = S.batch_rows; a.n_used = S.batch_n_used;
-        for (int wv = 0; wv < BATCH_WAVES; ++wv) { a.task_lo[wv] = S.task_lo[wv]; a.task_cnt[wv] = S.task_cnt[wv]; a.task_g[wv] = S.task_g[wv]; }
+        // every wave's piece of its group's list, cut once more into one sub-piece per row share
+        a.split = v.split;
+        for (uint32_t sh = 0; sh < v.split; ++sh)
+            for (int wv = 0; wv < BATCH_WAVES; ++wv) {
+                const uint32_t n = S.task_cnt[wv], lo = n * sh / v.split, hi = n * (sh + 1) / v.split;
+                a.task_lo[sh * BATCH_WAVES + wv] = S.task_lo[wv] + lo;
+                a.task_cnt[sh * BATCH_WAVES + wv] = hi - lo;
+                a.task_g[sh * BATCH_WAVES + wv] = S.task_g[wv];
+            }
         a.item_keys = S.item_keys + N_OBJ * L.item0;
-        a.hints = S.batch_hints + N_OBJ * L.prob0;
         a.final_out = S.final_map;
         // persistent blocks, two per CU, each with a contiguous range of the items
         dim3 grid((uint32_t)std::min<uint64_t>(L.n_items, (uint64_t)S.resident_blocks));
@@ -1414,7 +1415,7 @@ void mmee_shutdown(void)
     (void)hipFree(S.dv_dev); (void)hipFree(S.eval_dev);
     if (S.final_host) (void)hipHostFree(S.final_host);
     if (S.batch_host) (void)hipHostFree(S.batch_host);
-    (void)hipFree(S.batch_dev); (void)hipFree(S.item_keys); (void)hipFree(S.batch_hints);
+    (void)hipFree(S.batch_dev); (void)hipFree(S.item_keys);
     (void)hipFree(S.batch_row_off); (void)hipFree(S.batch_row_df); (void)hipFree(S.batch_cmap);
     for (hipEvent_t e : S.events) (void)hipEventDestroy(e);
     hipStream_t keep = S.stream;

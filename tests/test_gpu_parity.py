@@ -519,3 +519,30 @@ def test_regrouped_sum_on_trust_and_its_fallback(M):
             code, front = M.mmee_pareto(w, h, flags)
             ocode, oidx, _ = O.pareto(ow, oh)
             assert code == 0 and [p.best.idx for p in front] == list(oidx), (e_mac, flags)
+
+
+def test_search_many_mixed_small_problems_in_one_call(M):
+    """Two hundred seeded problems -- whole-number and fractional energies, power-of-two and other
+    bandwidths, infeasible ones, every single key and the key pairs -- through ONE mmee_search_many
+    call per flag set: the pruned passes share launches across kernel variants, their items span
+    several problems per block and small launches share a chunk's rows between blocks.  Every
+    entry against the oracle's full enumeration."""
+    cases = random_small_cases(200, 0xBA7C4ED)
+    keysets = ([0], [1], [2], [3], [0, 1], [1, 0], [0, 1, 2], [3, 0])
+    points, want = [], []
+    for k, (w, h) in enumerate(cases):
+        rc, idx, cost, n_valid, _ = O.search_all(O.workload(w), O.hw(h))
+        assert rc in (0, -3)
+        for obj in keysets[k % len(keysets)]:
+            points.append((w, h, obj))
+            want.append((idx[obj], cost[obj]) if n_valid else None)
+    for flags in (M.SEARCH_PRUNED, M.SEARCH_PRUNED | M.SEARCH_ORDERED_SUM, M.SEARCH_EXHAUSTIVE):
+        results, codes = M.mmee_search_many(points, flags)
+        for k, (res, code, exp) in enumerate(zip(results, codes, want)):
+            if exp is None:
+                assert code == M.ENOFEASIBLE, (k, flags)
+                continue
+            assert code == 0 and res.best.idx == exp[0], (k, points[k], flags)
+            assert res.cost.energy_pj == exp[1].energy_pj and res.cost.latency_cycles == exp[1].latency_cycles
+            for fld in INT_FIELDS:
+                assert getattr(res.cost, fld) == getattr(exp[1], fld)
