@@ -545,55 +545,55 @@ __global__ void k_decode(DivTable dv, uint32_t T, const uint64_t *__restrict__ i
     out[a] = m;
 }
 
-// One candidate per thread, a block = 256 consecutive tilings of one row.  Records leave through
-// LDS so that every store instruction of a wave writes one contiguous kilobyte; the stores are
-// streaming (nothing reads the records back on the device).
+// One candidate per thread; records leave through LDS so that every store instruction of a wave
+// writes one contiguous kilobyte; the stores are streaming (nothing reads the records back on the
+// device).
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
-
-// Work unit = 64 consecutive tilings of one index row, one wave each (4 units per block).  Unit
-// boundaries are shifted per row so that every unit starts at a multiple of EVAL_ALIGN records
-// (1 KiB) in the output buffer: each store instruction then covers whole, aligned kilobytes.
-constexpr uint32_t EVAL_ALIGN = 16;
-
-__global__ __launch_bounds__(256) void k_eval_batch(EvalArgs a, uint64_t first_idx, uint64_t n, uint32_t row_first,
-                                                    uint32_t units_per_row, uint32_t n_units, v4u *__restrict__ out)
+// Work unit = one 4 KiB page of the output: 64 consecutive candidates, one wave.  Almost every page
+// lies inside one index row (all its candidates share order, levels and options), so the row decode
+// is wave-uniform; a page that straddles rows takes them one after the other.
+// Pages are dealt so that all pages of a block are congruent to the block number modulo 8: blocks go
+// round the eight XCDs, and an XCD that keeps to every eighth page writes at a measurably higher rate
+// than one whose pages lie side by side (6.7 against 6.0 TB/s for plain 4 KiB stores).
+__global__ __launch_bounds__(256) void k_eval_batch(EvalArgs a, uint32_t row_first, uint32_t t_first, uint32_t n, uint32_t n_pages,
+                                                    v4u *__restrict__ out)
 {
+    // record 0 of this launch is candidate row_first * T + t_first; n < 2^31 records per launch keep
+    // every tiling offset below 2^32
     __shared__ v4u stage[4][256];                             // [wave][64 records x 4 pieces]
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform on purpose
-    const uint32_t unit = blockIdx.x * 4 + wave;
-    if (unit >= n_units) return;
-    const uint32_t row = row_first + unit / units_per_row;
-    // first tiling of the row sits at output record row*T - first_idx; back off to the alignment
-    const uint32_t shift = (uint32_t)(((uint64_t)row * a.mc.T - first_idx) % EVAL_ALIGN);
-    const uint32_t t = (unit % units_per_row) * 64 + lane - shift;           // wraps for the lanes before the row
-    const uint64_t T = a.mc.T;
-    const uint64_t idx = (uint64_t)row * T + t;
-    const bool on = t < T && idx >= first_idx && idx - first_idx < n;
-    if (on) {
-        mmee_cost c;
-        eval_candidate(a, row, t, c);
-        const v4u *src = reinterpret_cast<const v4u *>(&c);
+    const uint32_t page = 32u * (blockIdx.x / 8u) + 8u * wave + blockIdx.x % 8u;
+    if (page >= n_pages) return;
+    const uint32_t rec0 = page * 64u;
+    const bool on = rec0 + lane < n;
+    // the page's first candidate, then each lane's own row and tiling
+    const uint32_t T = a.mc.T;
+    const uint32_t off0 = t_first + rec0;                     // tilings from the start of row_first
+    const uint32_t row0 = row_first + off0 / T, x = off0 % T + lane;
+    uint32_t my_row, my_t;
+    if (T >= 64u) { const bool next = x >= T; my_row = row0 + next; my_t = next ? x - T : x; }
+    else { my_row = row0 + x / T; my_t = x % T; }
+    const uint32_t row_last = __builtin_amdgcn_readfirstlane(row0 + (off0 % T + 63u) / T);
+    for (uint32_t row = __builtin_amdgcn_readfirstlane(row0); row <= row_last; ++row) {
+        if (on && my_row == row) {
+            mmee_cost c;
+            eval_candidate(a, row, my_t, c);
+            const v4u *src = reinterpret_cast<const v4u *>(&c);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) stage[wave][lane * 4 + k] = src[k];
+            for (int k = 0; k < 4; ++k) stage[wave][lane * 4 + k] = src[k];
+        }
     }
     // only this wave touches stage[wave]: order its LDS writes before its LDS reads
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const unsigned long long mask = __ballot(on);
-    // the wave's 64 records are consecutive in the output; lane L moves piece (L & 3) of
-    // record 16 k + L / 4 on pass k
-    // index of lane 0's candidate (before the row's first tiling when the unit was backed off)
-    const uint64_t wave_first = (uint64_t)row * T + (uint64_t)(int64_t)(int32_t)(t - lane);
+    // lane L moves piece (L & 3) of record 16 k + L / 4 on pass k
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        uint32_t rec = 16 * k + (lane >> 2);
-        if ((mask >> rec) & 1ull) {
-            uint64_t o = wave_first + rec - first_idx;
-            __builtin_nontemporal_store(stage[wave][rec * 4 + (lane & 3)], &out[o * 4 + (lane & 3)]);
-        }
+        const uint32_t rec = 16 * k + (lane >> 2);
+        if (rec0 + rec < n) __builtin_nontemporal_store(stage[wave][rec * 4 + (lane & 3)], &out[(rec0 + rec) * 4 + (lane & 3)]);
     }
 }
 

@@ -1026,10 +1026,9 @@ int mmee_chain_eval_batch(const mmee_chain *w, const mmee_hw *hw, uint64_t first
 
     EvalArgs ea;
     ea.enc = S.enc; ea.btab = S.btab; ea.ctab_e = S.ctab_e; ea.mc = p.mc;
-    const uint32_t upr = (uint32_t)((p.T + EVAL_ALIGN - 1 + 63) / 64);      // 64-tiling units per index row
-    // records per launch: 1 GiB of staging for host output, one launch (grid limit) for device output
-    uint64_t CHUNK = on_device ? (1ull << 30) : (1ull << 24);
-    CHUNK = std::min<uint64_t>(CHUNK, std::max<uint64_t>(1, (1ull << 29) / upr) * p.T);   // grid size limit
+    // records per launch: 1 GiB of staging for host output, one launch (grid limit) for device output;
+    // whole 4 KiB pages of 64 records each
+    const uint64_t CHUNK = on_device ? (1ull << 30) : (1ull << 24);
     if (!on_device) {
         size_t need = (size_t)std::min<uint64_t>(n, CHUNK) * sizeof(mmee_cost);
         if (need > S.eval_cap) {
@@ -1041,14 +1040,14 @@ int mmee_chain_eval_batch(const mmee_chain *w, const mmee_hw *hw, uint64_t first
     }
     for (uint64_t done = 0; done < n; done += CHUNK) {
         const uint64_t cnt = std::min<uint64_t>(CHUNK, n - done);
-        const uint64_t first = first_idx + done;
-        const uint64_t row_first = first / p.T, row_last = (first + cnt - 1) / p.T;
-        const uint64_t n_units = (row_last - row_first + 1) * upr;
-        if (n_units > 0x7fffffffull) return MMEE_EINVAL;
-        const uint64_t nblocks = (n_units + 3) / 4;
+        const uint64_t n_pages = (cnt + 63) / 64;
+        // blocks come in groups of eight that share 32 neighbouring pages
+        const uint64_t nblocks = (n_pages + 31) / 32 * 8;
+        if (nblocks > 0x7fffffffull) return MMEE_EINVAL;
         v4u *dst = on_device ? reinterpret_cast<v4u *>(out_costs + done) : reinterpret_cast<v4u *>(S.eval_dev);
-        hipLaunchKernelGGL(k_eval_batch, dim3((uint32_t)nblocks), dim3(256), 0, S.stream, ea, first, cnt,
-                           (uint32_t)row_first, upr, (uint32_t)n_units, dst);
+        const uint64_t first = first_idx + done;
+        hipLaunchKernelGGL(k_eval_batch, dim3((uint32_t)nblocks), dim3(256), 0, S.stream, ea, (uint32_t)(first / p.T),
+                           (uint32_t)(first % p.T), (uint32_t)cnt, (uint32_t)n_pages, dst);
         HIP_TRY(hipGetLastError());
         if (!on_device) {
             HIP_TRY(hipMemcpyAsync(out_costs + done, S.eval_dev, cnt * sizeof(mmee_cost), hipMemcpyDeviceToHost,
