@@ -133,20 +133,25 @@ def main():
                 "ms_inside_library": results[0].seconds * 1e3, "candidates_costed": costed,
                 "candidates_per_s": costed / dt, "infeasible": sum(1 for c in codes if c != 0)}, results
 
-    if args.profile_only and args.profile_leg != "long":
-        if args.profile_leg == "bert":
+    if args.profile_only:
+        # the timed steps of one leg only, for rocprofv3, then a plain copy of known size (1 GiB read,
+        # 1 GiB written) as the reference reading of the FETCH_SIZE / WRITE_SIZE counters
+        if args.profile_leg == "long":
+            timed_search(CONFIGS["long"], [M.OBJ_ENERGY], M.SEARCH_EXHAUSTIVE, args.steps, args.warmup)
+        elif args.profile_leg == "bert":
             timed_search(CONFIGS["bert"], [M.OBJ_ENERGY, M.OBJ_LATENCY], M.SEARCH_EXHAUSTIVE, args.steps, args.warmup)
         elif args.profile_leg == "sweep":
             sweep_leg(M.SEARCH_PRUNED, max(1, args.steps), args.warmup)
-            sweep_leg(M.SEARCH_EXHAUSTIVE, 1, 0)
         else:
             cfg = CONFIGS["bert"]
             buf = torch.empty((1 << 26) * 8, dtype=torch.int64, device="cuda")
             for _ in range(args.warmup + args.steps):
                 M.mmee_eval_batch(cfg["workload"], cfg["hw"], 1_000_000_007, 1 << 26, out=buf.data_ptr())
-            src = torch.zeros(1 << 27, dtype=torch.int64, device="cuda")
-            buf[: src.numel()].copy_(src)         # 1 GiB read + 1 GiB written: the counters' reference reading
-            torch.cuda.synchronize()
+            del buf
+        src = torch.zeros(1 << 27, dtype=torch.int64, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
         print(json.dumps({"profile_leg": args.profile_leg}))
         return
 

@@ -8,7 +8,8 @@
 // touches HBM.  Lane = tiling, wave = a contiguous piece of one group's row list, so a row's table
 // offsets are wave-uniform and the per-tiling constants of the nine stationary combinations sit in
 // registers for the whole item.  Only the table entries that the rows refer to are staged (77 of 123
-// for the pruned rows), which lets two 512-thread blocks share a CU.  A block takes a contiguous range
+// for the pruned rows), which lets two 512-thread blocks share a CU; a row's offsets into the staged
+// table and the entries' places in it reach the waves as scalar loads.  A block takes a contiguous range
 // of items, waves carry their best (value, index) across the items of a problem, and each (block,
 // problem) stretch leaves one record per key; k_batch_finish, launched behind the search, reduces a
 // problem's records and writes the winner's full cost record and mapping.
@@ -224,9 +225,10 @@ __device__ __forceinline__ void eval_candidate_direct(const uint4 *enc, const Di
 // The table entries of one kind, for this lane's tiling, into the staged table: x[a] + y[b] for every
 // option pair (na x nb of them, entry number first + a + na * b), each at the place cmap gives it.
 template <int NA, int NB>
-__device__ __forceinline__ void stage_pair_sums(double *tab_lane, const uint16_t *cmap, int first, const double (&x)[5],
+__device__ __forceinline__ void stage_pair_sums(double *tab_lane, ConstPtr<uint32_t> cmap, int first, const double (&x)[5],
                                                 const double (&y)[5])
 {
+    // the places are wave-uniform (scalar loads): an entry no row refers to costs a branch, nothing more
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
@@ -253,16 +255,17 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
     __shared__ double cst[2 * BATCH_NCS * BATCH_TC];         // [r][constant][tiling]
     __shared__ double gd[8 * BATCH_TC];                      // the chunk's boundary vectors: G[0..3], D[0..3] per tiling
     __shared__ double tc[6 * 2 * BATCH_TC];                  // tile costs: [op * 3 + mode][words, cycles][tiling]
-    __shared__ uint16_t row_lds[BATCH_MAX_ROWS * 8];         // the rows' table offsets (below 64 KiB: 80 entries x 512 B)
     __shared__ uint32_t div_lds[4 * MAXDIV];                 // the current problem's divisor lists
-    __shared__ uint16_t cmap_lds[NENT + 1];
     __shared__ Key wave_best[N_OBJ][BATCH_WAVES];
 
     const double inf = pos_inf();
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    for (uint32_t k = threadIdx.x; k < a.n_rows * 8; k += BATCH_THREADS) row_lds[k] = (uint16_t)a.row_off[k];
-    if (threadIdx.x < NENT) cmap_lds[threadIdx.x] = (uint16_t)a.cmap[threadIdx.x];
+    // A wave's rows and the table's entry places are the same for all its lanes: both come through
+    // the constant address space (scalar loads), a row's eight offsets as one load, one row ahead of use.
+    typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+    ConstPtr<u32x8> row_offs = (ConstPtr<u32x8>)a.row_off;
+    ConstPtr<uint32_t> cmap_c = as_constant(a.cmap);
 
     const uint32_t per_block = (a.n_items + gridDim.x - 1) / gridDim.x;
     const uint32_t item_lo = blockIdx.x * per_block, item_hi = min(item_lo + per_block, a.n_items);
@@ -282,14 +285,12 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
     const char *tab_bytes = reinterpret_cast<const char *>(tab) + lane * 8;
 
     // the wave's running best over the items of the current problem
-    double run_p[N_OBJ];
+    double run_p[N_OBJ], run_s[N_OBJ];                       // (primary, secondary) as in Key; secondary 0 for scalar keys
     uint64_t run_idx[N_OBJ];
     uint32_t run_c[N_OBJ], run_i[N_OBJ], run_t0[N_OBJ];      // its combination, its row (place in the row lists), its chunk
-    Key run_le;
     auto reset_running = [&]() {
 #pragma unroll
-        for (int o = 0; o < N_OBJ; ++o) { run_p[o] = inf; run_idx[o] = ~0ull; run_c[o] = run_i[o] = run_t0[o] = 0; }
-        run_le.p = inf; run_le.s = 0.0; run_le.idx = ~0ull;
+        for (int o = 0; o < N_OBJ; ++o) { run_p[o] = inf; run_s[o] = 0.0; run_idx[o] = ~0ull; run_c[o] = run_i[o] = run_t0[o] = 0; }
     };
     reset_running();
     uint32_t staged_p = 0xFFFFFFFFu;
@@ -369,35 +370,35 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
             case 0:                                           // BS_A[a] + BS_B[b]
                 footprints(x, v.G[DI] * v.G[DK], v.D[DI], v.D[DK]);
                 footprints(y, v.G[DK] * v.G[DL], v.D[DK], v.D[DL]);
-                stage_pair_sums<4, 4>(tab_lane, cmap_lds, ENT_BS_AB, x, y);
+                stage_pair_sums<4, 4>(tab_lane, cmap_c, ENT_BS_AB, x, y);
                 break;
             case 1:                                           // BS_D[a] + BS_E[b]
                 footprints(x, v.G[DL] * v.G[DJ], v.D[DL], v.D[DJ]);
                 footprints(y, v.G[DI] * v.G[DJ], v.D[DI], v.D[DJ]);
-                stage_pair_sums<4, 4>(tab_lane, cmap_lds, ENT_BS_DE, x, y);
+                stage_pair_sums<4, 4>(tab_lane, cmap_c, ENT_BS_DE, x, y);
                 break;
             case 6:                                           // tau_D BS_D[a] + tau_E BS_E[b]
                 footprints(x, v.G[DL] * v.G[DJ], v.D[DL], v.D[DJ]);
                 footprints(y, v.G[DI] * v.G[DJ], v.D[DI], v.D[DJ]);
-                stage_pair_sums<5, 5>(tab_lane, cmap_lds, ENT_RET_DE, x, y);
+                stage_pair_sums<5, 5>(tab_lane, cmap_c, ENT_RET_DE, x, y);
                 break;
             case 7:                                           // tau_A BS_A[a] + tau_B BS_B[b]
                 footprints(x, v.G[DI] * v.G[DK], v.D[DI], v.D[DK]);
                 footprints(y, v.G[DK] * v.G[DL], v.D[DK], v.D[DL]);
-                stage_pair_sums<5, 5>(tab_lane, cmap_lds, ENT_RET_AB, x, y);
+                stage_pair_sums<5, 5>(tab_lane, cmap_c, ENT_RET_AB, x, y);
                 break;
             case 2: {                                         // BS_C[c]; B*H * DA_C[c]
                 footprints(x, v.G[DI] * v.G[DL], v.D[DI], v.D[DL]);
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    const uint32_t at = cmap_lds[ENT_BS_C + c];
+                    const uint32_t at = cmap_c[ENT_BS_C + c];
                     if (at != 0xFFFFu) tab_lane[at * BATCH_TC] = x[c];
                 }
 #pragma unroll
                 for (int c = 0; c < 5; ++c) {
                     // unfused C: spilled by Op1, fetched by Op2, one softmax pass over S and P; option 4: fused
                     const double spill = (c & 1) ? v.D[DK] : 1.0, fetch = (c & 2) ? v.D[DJ] : 1.0;
-                    const uint32_t at = cmap_lds[ENT_DA_C + c];
+                    const uint32_t at = cmap_c[ENT_DA_C + c];
                     if (at != 0xFFFFu) tab_lane[at * BATCH_TC] = c >= 4 ? 0.0 : mc.BH * (X[DI] * X[DL]) * (spill + fetch + 2.0);
                 }
                 break;
@@ -405,12 +406,12 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
             case 3:                                           // B*H * (|A| {1, l_D, j_D, l_D j_D} + |B| {1, i_D, j_D, i_D j_D})
                 footprints(x, mc.BH * (X[DI] * X[DK]), v.D[DL], v.D[DJ]);
                 footprints(y, mc.BH * (X[DK] * X[DL]), v.D[DI], v.D[DJ]);
-                stage_pair_sums<4, 4>(tab_lane, cmap_lds, ENT_DA_AB, x, y);
+                stage_pair_sums<4, 4>(tab_lane, cmap_c, ENT_DA_AB, x, y);
                 break;
             case 4:                                           // B*H * (|D| {1, i_D, k_D, i_D k_D} + |E| {1, k_D, l_D, k_D l_D})
                 footprints(x, mc.BH * (X[DL] * X[DJ]), v.D[DI], v.D[DK]);
                 footprints(y, mc.BH * (X[DI] * X[DJ]), v.D[DK], v.D[DL]);
-                stage_pair_sums<4, 4>(tab_lane, cmap_lds, ENT_DA_DE, x, y);
+                stage_pair_sums<4, 4>(tab_lane, cmap_c, ENT_DA_DE, x, y);
                 break;
             default: break;
             }
@@ -439,77 +440,89 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
         const double e_rf_part = REGROUP ? 0.0 : cst[(r * BATCH_NCS + 18) * BATCH_TC + lane];
         const double e_mac_part = REGROUP ? 0.0 : cst[(r * BATCH_NCS + 19) * BATCH_TC + lane];
 
-        double bestE[9], bestL[9], bestP[9], bestLE_l[9], bestLE_e[9];
-        uint32_t codeLE[9];
-#pragma unroll
-        for (int c9 = 0; c9 < 9; ++c9) { bestE[c9] = bestL[c9] = bestP[c9] = bestLE_l[c9] = bestLE_e[c9] = inf; codeLE[c9] = 0; }
-
-        // the row part of one (row, tiling): Eq. (1), (2), (4), capacity mask, B*H * Eq. (7)
-        auto row_part = [&](uint32_t i, double &dram_words, double &e_part, double &l_dram) {
-            const uint16_t *off = row_lds + (row_lo + i) * 8;
+        // Every key is a monotone function of a candidate's DRAM traffic once tiling, recomputation choice
+        // and stationary combination are fixed: DRAM energy and DRAM time grow with it, every rounded sum,
+        // product and maximum they pass through keeps the order, and the capacity test does not look at the
+        // combination.  All rows of a wave's piece share the recomputation choice.  Among the rows that fit,
+        // the one with the least traffic therefore has the least cost under every combination and every key
+        // -- bit for bit the value a row-by-row minimum gives -- and the loop over the rows only has to keep
+        // that least traffic per tiling.  (Rounding may give rows with more traffic the same cost: positions
+        // are recovered below by comparing costs, not traffic.)
+        auto row_words = [&](const u32x8 off) -> double {
             double w[NSEL];
 #pragma unroll
             for (int k = 0; k < NSEL; ++k) w[k] = *reinterpret_cast<const double *>(tab_bytes + off[k]);
-            const bool ok = fmax(w[0] + w[2] + w[1], w[3] + w[2] + w[4]) <= cap;
-            dram_words = w[5] + w[6] + w[7];
-            e_part = (REGROUP ? mc.e_sum : mc.e_dram) * dram_words;
-            if constexpr (FAST) l_dram = dram_words * mc.dram_k;
-            else l_dram = mc.dram_bw > 0.0 ? mc.c_lat * (((dram_words / mc.BH) * mc.word) / mc.dram_bw) : 0.0;
-            const double over = __hiloint2double(ok ? 0 : 0x7ff00000, 0);
-            e_part = fmax(e_part, over);
-            l_dram = fmax(l_dram, over);
-            pin(e_part);
-            pin(l_dram);
+            const bool ok = fmax(w[0] + w[2] + w[1], w[3] + w[2] + w[4]) <= cap;     // Eq. (1), (2), (4)
+            const double dram_words = w[5] + w[6] + w[7];                            // B*H * Eq. (7)
+            return ok ? dram_words : inf;
         };
-        auto combo_cost = [&](double dram_words, double e_part, double l_dram, double gb_c, double latc_c, double &en, double &lat) {
+        // energy and latency of the candidate (row with traffic dram_words, combination constants gb_c, latc_c)
+        auto costs_of = [&](double dram_words, double gb_c, double latc_c, double &en, double &lat) {
+            const bool feasible = dram_words < inf;
+            const double d = feasible ? dram_words : 0.0;
+            const double e_part = (REGROUP ? mc.e_sum : mc.e_dram) * d;
+            double l_dram;
+            if constexpr (FAST) l_dram = d * mc.dram_k;
+            else l_dram = mc.dram_bw > 0.0 ? mc.c_lat * (((d / mc.BH) * mc.word) / mc.dram_bw) : 0.0;
             if constexpr (REGROUP) {
                 en = e_part + gb_c;
             } else {
-                const double gb_words = dram_words + gb_c;
+                const double gb_words = d + gb_c;
                 en = e_part + mc.e_gb * gb_words;
                 en = en + e_rf_part;
                 en = en + e_mac_part;
             }
             lat = fmax(l_dram, latc_c);
+            en = feasible ? en : inf;
+            lat = feasible ? lat : inf;
+        };
+        // key o of a candidate as a (primary, secondary) pair; the secondary is 0 for the scalar keys
+        auto key_of = [&](int o, double en, double lat, double &kp, double &ks) {
+            kp = o == 0 ? en : (o == 3 ? en * lat : lat);
+            ks = o == 2 ? en : 0.0;
         };
 
-        for (uint32_t i = 0; i < n_rows; ++i) {
-            double dram_words, e_part, l_dram;
-            row_part(i, dram_words, e_part, l_dram);
-#pragma unroll
-            for (int c9 = 0; c9 < 9; ++c9) {
-                double en, lat;
-                combo_cost(dram_words, e_part, l_dram, gb[c9], latc[c9], en, lat);
-                if constexpr (MASK & 1) bestE[c9] = fmin(bestE[c9], en);
-                if constexpr (MASK & 2) bestL[c9] = fmin(bestL[c9], lat);
-                if constexpr (MASK & 8) bestP[c9] = fmin(bestP[c9], en * lat);
-                if constexpr (MASK & 4) {
-                    // rows come in index order: a strict < keeps the lowest index on ties
-                    const bool lt = (lat < bestLE_l[c9]) | ((lat == bestLE_l[c9]) & (en < bestLE_e[c9]));
-                    bestLE_l[c9] = lt ? lat : bestLE_l[c9];
-                    bestLE_e[c9] = lt ? en : bestLE_e[c9];
-                    codeLE[c9] = lt ? i : codeLE[c9];
-                }
+        double min_d = inf;
+        {
+            u32x8 off_next = row_offs[min(row_lo, a.n_rows - 1)];
+            for (uint32_t i = 0; i < n_rows; ++i) {
+                const u32x8 off_now = off_next;
+                off_next = row_offs[row_lo + min(i + 1, n_rows - 1)];
+                min_d = fmin(min_d, row_words(off_now));
             }
         }
 
         // ---- fold the item into the wave's running best
         if (n_rows) {
+            double en9[9], lat9[9];
+#pragma unroll
+            for (int c9 = 0; c9 < 9; ++c9) costs_of(min_d, gb[c9], latc[c9], en9[c9], lat9[c9]);
 #pragma unroll
             for (int o = 0; o < N_OBJ; ++o) {
-                if (!((MASK >> o) & 1) || o == 2) continue;
-                // scalar keys: only minima were kept; the position is recovered where it can matter
-                const double *best = o == 0 ? bestE : (o == 1 ? bestL : bestP);
-                double mine_v = best[0];
+                if (!((MASK >> o) & 1)) continue;
+                // only minima were kept; the position is recovered where it can matter
+                double mine_p = inf, mine_s = inf;
 #pragma unroll
-                for (int c9 = 1; c9 < 9; ++c9) mine_v = fmin(mine_v, best[c9]);
-                const double wave_v = uniform_f64(wave_min_f64(mine_v));
+                for (int c9 = 0; c9 < 9; ++c9) {
+                    double kp, ks;
+                    key_of(o, en9[c9], lat9[c9], kp, ks);
+                    const bool lt = (kp < mine_p) | ((kp == mine_p) & (ks < mine_s));
+                    mine_p = lt ? kp : mine_p;
+                    mine_s = lt ? ks : mine_s;
+                }
+                const double wave_p = uniform_f64(wave_min_f64(mine_p));
                 // nothing feasible, or this wave already holds a lower value
-                if (!(wave_v < inf) || wave_v > run_p[o]) continue;
+                if (!(wave_p < inf) || wave_p > run_p[o]) continue;
+                const double wave_s = o == 2 ? uniform_f64(wave_min_f64(mine_p == wave_p ? mine_s : inf)) : 0.0;
+                if (wave_p == run_p[o] && wave_s > run_s[o]) continue;
                 // the lowest combination in which some tiling reaches the minimum
                 uint32_t cstar = 9;
 #pragma unroll
-                for (int c9 = 8; c9 >= 0; --c9) cstar = best[c9] == wave_v ? (uint32_t)c9 : cstar;
+                for (int c9 = 8; c9 >= 0; --c9) {
+                    double kp, ks;
+                    key_of(o, en9[c9], lat9[c9], kp, ks);
+                    cstar = ((kp == wave_p) & (ks == wave_s)) ? (uint32_t)c9 : cstar;
+                }
                 const uint32_t c_u = __builtin_amdgcn_readfirstlane(wave_min_u32(cstar));
                 const uint32_t combo_rows = 30000u * (c_u % 3) + 90000u * (c_u / 3);
                 // Index order is (combination, row, tiling).  An equal value only matters where it can sit at a
@@ -517,7 +530,7 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
                 // row, or in the same row if this chunk comes before the running best's.
                 // (A wave's pieces all lie in one group's list, whatever the share: list places compare like indices.)
                 uint32_t scan = n_rows;
-                if (wave_v == run_p[o]) {
+                if (wave_p == run_p[o] && wave_s == run_s[o]) {
                     if (c_u > run_c[o]) continue;
                     if (c_u == run_c[o]) {
                         const uint32_t upto = t0 < run_t0[o] ? run_i[o] + 1 : run_i[o];    // list places below this one matter
@@ -532,37 +545,18 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
                 }
                 // the first row (index order) in which a tiling reaches it, at its lowest such tiling
                 for (uint32_t i = 0; i < scan; ++i) {
-                    double dram_words, e_part, l_dram, en, lat;
-                    row_part(i, dram_words, e_part, l_dram);
-                    combo_cost(dram_words, e_part, l_dram, gb_u, latc_u, en, lat);
-                    const double val = o == 0 ? en : (o == 1 ? lat : en * lat);
-                    const unsigned long long hits = __ballot(val == wave_v);
+                    double en, lat, kp, ks;
+                    costs_of(row_words(row_offs[row_lo + i]), gb_u, latc_u, en, lat);
+                    key_of(o, en, lat, kp, ks);
+                    const unsigned long long hits = __ballot((kp == wave_p) & (ks == wave_s));
                     if (!hits) continue;
                     const uint64_t idx = (uint64_t)t0 + ((uint32_t)__ffsll((long long)hits) - 1u) +
                                          (uint64_t)T * (index_row_base(row_df[row_lo + i]) + combo_rows);
-                    if (wave_v < run_p[o] || idx < run_idx[o]) {
-                        run_p[o] = wave_v; run_idx[o] = idx; run_c[o] = c_u; run_i[o] = row_lo + i; run_t0[o] = t0;
+                    if (wave_p < run_p[o] || wave_s < run_s[o] || idx < run_idx[o]) {
+                        run_p[o] = wave_p; run_s[o] = wave_s; run_idx[o] = idx; run_c[o] = c_u; run_i[o] = row_lo + i; run_t0[o] = t0;
                     }
                     break;
                 }
-            }
-            if constexpr (MASK & 4) {
-                Key k;
-                k.p = inf; k.s = 0.0; k.idx = ~0ull;
-#pragma unroll
-                for (int c9 = 0; c9 < 9; ++c9) {
-                    // ascending combination = ascending index
-                    if (bestLE_l[c9] < k.p || (bestLE_l[c9] == k.p && bestLE_e[c9] < k.s)) {
-                        const uint32_t dfrow = a.row_df[row_lo + codeLE[c9]];
-                        k.p = bestLE_l[c9];
-                        k.s = bestLE_e[c9];
-                        k.idx = (uint64_t)(t0 + lane) + (uint64_t)T * (index_row_base(dfrow) + 30000u * (c9 % 3) + 90000u * (c9 / 3));
-                    }
-                }
-                if (!(k.p < inf)) { k.s = 0.0; k.idx = ~0ull; }
-                k = wave_min(k);
-                k.p = uniform_f64(k.p); k.s = uniform_f64(k.s);
-                if (key_less(k, run_le)) run_le = k;
             }
         }
 
@@ -577,8 +571,7 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
             for (int o = 0; o < N_OBJ; ++o) {
                 if (!((MASK >> o) & 1)) continue;
                 Key k;
-                if (o == 2) k = run_le;
-                else { k.p = run_p[o]; k.s = 0.0; k.idx = run_idx[o]; }
+                k.p = run_p[o]; k.s = run_s[o]; k.idx = run_idx[o];
                 wave_best[o][wave] = k;
             }
         }
