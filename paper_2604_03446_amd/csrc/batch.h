@@ -49,7 +49,7 @@ struct BatchArgs {
     uint32_t n_rows, n_used;
     // A chunk's rows are shared out over `split` work items (1 in a large launch; more when the launch
     // would otherwise leave most of the chip idle), and inside a work item over the waves of the block.
-    uint32_t split;
+    uint32_t split, split_log2;                 // a power of two
     uint32_t task_lo[BATCH_MAX_SPLIT * BATCH_WAVES];     // per (share, wave): its first row in the lists,
     uint32_t task_cnt[BATCH_MAX_SPLIT * BATCH_WAVES];    //                    how many rows it takes,
     uint32_t task_g[BATCH_MAX_SPLIT * BATCH_WAVES];      //                    and the group g = r + 2 f they belong to
@@ -127,20 +127,19 @@ __device__ __forceinline__ double table_entry(uint32_t ent, const TilingF &v, co
     return c >= 4 ? 0.0 : bh * (X[DI] * X[DL]) * (spill + fetch + 2.0);
 }
 
-// ceil(a / b) for a 32-bit a; b may exceed 32 bits (then one fold suffices)
-__device__ __forceinline__ double cdiv_f64(uint32_t a, uint64_t b) { return b > a ? 1.0 : (double)((a - 1u) / (uint32_t)b + 1u); }
+// ceil(a / b) for a whole number 1 <= a < 2^32 held in fp64, given 1 / b rounded once (ModelConst)
+__device__ __forceinline__ double cdiv_f64(double a, double rcp_b) { return __builtin_floor((a - 0.5) * rcp_b) + 1.0; }
 
 // words crossing buffer<->RF and cycles of one tile matmul m x r x n; mode 0 WS, 1 IS, 2 OS
-__device__ __forceinline__ void tile_cost_f64(uint32_t m, uint32_t r, uint32_t n, uint32_t mode, const ModelConst &mc,
+__device__ __forceinline__ void tile_cost_f64(double m, double r, double n, uint32_t mode, const ModelConst &mc,
                                               double &words, double &cycles)
 {
-    const uint32_t rows_dim = mode == 0 ? r : m;             // spread over PE rows
-    const uint32_t cols_dim = mode == 1 ? r : n;             // spread over PE columns
-    const double time_dim = (double)(mode == 0 ? m : (mode == 1 ? n : r));
-    const double row_folds = cdiv_f64(rows_dim, mc.pe_rows);
-    const double rd = (double)rows_dim, cd = (double)cols_dim;
-    words = rd * cd + time_dim * rd * cdiv_f64(cols_dim, (uint64_t)mc.pe_cols * mc.g_words) + time_dim * cd * row_folds;
-    cycles = row_folds * cdiv_f64(cols_dim, mc.pe_cols) * time_dim;
+    const double rd = mode == 0 ? r : m;                     // spread over PE rows
+    const double cd = mode == 1 ? r : n;                     // spread over PE columns
+    const double time_dim = mode == 0 ? m : (mode == 1 ? n : r);
+    const double row_folds = cdiv_f64(rd, mc.rcp_rows);
+    words = rd * cd + time_dim * rd * cdiv_f64(cd, mc.rcp_cols_g) + time_dim * cd * row_folds;
+    cycles = row_folds * cdiv_f64(cd, mc.rcp_cols) * time_dim;
 }
 
 // what one stationary combination (s1, s2) and recomputation choice r contribute for one tiling
@@ -161,7 +160,8 @@ __device__ __forceinline__ ComboTerms combo_terms_from(const TilingF &v, const d
     o.cyc = st1 * cy1 + st2 * cy2;
     o.mac = rho * X[DI] * X[DK] * X[DL] + X[DI] * X[DL] * X[DJ];
     o.sm = rho * X[DI] * X[DL];
-    const double t_gb = mc.gb_bw > 0.0 ? (o.br * mc.word) / mc.gb_bw : 0.0;
+    // a power-of-two bandwidth: the quotient is the product with one exactly representable constant
+    const double t_gb = mc.gb_pow2 ? o.br * mc.gb_k : (mc.gb_bw > 0.0 ? (o.br * mc.word) / mc.gb_bw : 0.0);
     o.lat_part = mc.c_lat * fmax(o.cyc, t_gb);
     o.e_rf_part = mc.e_rf * (mc.BH * 3.0 * o.mac);
     o.e_mac_part = mc.e_mac * (mc.BH * (o.mac + (double)mc.c_softmax * o.sm));
@@ -172,8 +172,8 @@ __device__ __forceinline__ ComboTerms combo_terms(const TilingF &v, const double
                                                   uint32_t s1, uint32_t s2)
 {
     double br1, cy1, br2, cy2;
-    tile_cost_f64((uint32_t)v.G[DI], (uint32_t)v.G[DK], (uint32_t)v.G[DL], s1, mc, br1, cy1);
-    tile_cost_f64((uint32_t)v.G[DI], (uint32_t)v.G[DL], (uint32_t)v.G[DJ], s2, mc, br2, cy2);
+    tile_cost_f64(v.G[DI], v.G[DK], v.G[DL], s1, mc, br1, cy1);
+    tile_cost_f64(v.G[DI], v.G[DL], v.G[DJ], s2, mc, br2, cy2);
     return combo_terms_from(v, X, mc, r, br1, cy1, br2, cy2);
 }
 
@@ -267,8 +267,7 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
     ConstPtr<u32x8> row_offs = (ConstPtr<u32x8>)a.row_off;
     ConstPtr<uint32_t> cmap_c = as_constant(a.cmap);
 
-    const uint32_t per_block = (a.n_items + gridDim.x - 1) / gridDim.x;
-    const uint32_t item_lo = blockIdx.x * per_block, item_hi = min(item_lo + per_block, a.n_items);
+    const uint32_t item_lo = blockIdx.x * a.per_block, item_hi = min(item_lo + a.per_block, a.n_items);
     if (item_lo >= item_hi) return;
     // the first item's problem: the last p with first_items[p] <= item; later items move p on
     ConstPtr<uint32_t> firsts = as_constant(a.first_items);
@@ -308,8 +307,9 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
           while (stride < seg_len && gcd(stride, seg_len) != 1) ++stride;
           if (stride >= seg_len) stride = 1;
       }
-      for (uint32_t visit = 0; visit < seg_len; ++visit) {
-        const uint32_t item = seg_first + (uint32_t)(((uint64_t)visit * stride) % seg_len);
+      uint32_t place = 0;                                    // (visit * stride) mod seg_len, kept by addition
+      for (uint32_t visit = 0; visit < seg_len; ++visit, place = place + stride >= seg_len ? place + stride - seg_len : place + stride) {
+        const uint32_t item = seg_first + place;
         const BatchProblem *pr = a.prob + p;
         // the descriptors are read-only while the kernel runs: wave-uniform fields through scalar loads
         ModelConst mc;
@@ -322,9 +322,9 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
         }
         ConstPtr<uint32_t> tail = as_constant(&pr->first_item);
         const uint32_t work = item - tail[0];
-        const uint32_t t0 = work / a.split * BATCH_TC;
+        const uint32_t t0 = (work >> a.split_log2) * BATCH_TC;
         // this wave's piece of one group's rows, within the work item's share of the chunk's rows
-        const uint32_t task = (work % a.split) * BATCH_WAVES + wave;
+        const uint32_t task = (work & (a.split - 1)) * BATCH_WAVES + wave;
         const uint32_t n_rows = a.task_cnt[task], row_lo = a.task_lo[task], r = a.task_g[task] & 1;
         const uint32_t T = mc.T;
         const uint32_t nt = min((uint32_t)BATCH_TC, T - t0);
@@ -357,8 +357,8 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
         const double X[4] = {(double)dvw[0], (double)dvw[1], (double)dvw[2], (double)dvw[3]};
         if (wave < 6) {
             double words, cycles;
-            if (wave < 3) tile_cost_f64((uint32_t)v.G[DI], (uint32_t)v.G[DK], (uint32_t)v.G[DL], wave, mc, words, cycles);
-            else tile_cost_f64((uint32_t)v.G[DI], (uint32_t)v.G[DL], (uint32_t)v.G[DJ], wave - 3, mc, words, cycles);
+            if (wave < 3) tile_cost_f64(v.G[DI], v.G[DK], v.G[DL], wave, mc, words, cycles);
+            else tile_cost_f64(v.G[DI], v.G[DL], v.G[DJ], wave - 3, mc, words, cycles);
             tc[(wave * 2) * BATCH_TC + lane] = words;
             tc[(wave * 2 + 1) * BATCH_TC + lane] = cycles;
         }
@@ -456,25 +456,32 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
             const double dram_words = w[5] + w[6] + w[7];                            // B*H * Eq. (7)
             return ok ? dram_words : inf;
         };
-        // energy and latency of the candidate (row with traffic dram_words, combination constants gb_c, latc_c)
-        auto costs_of = [&](double dram_words, double gb_c, double latc_c, double &en, double &lat) {
+        // the row side of a candidate's costs, from its traffic: DRAM energy (regrouped: DRAM and buffer
+        // energy of the DRAM words) and DRAM time, +inf both when no row fits; the words themselves (0 then)
+        struct RowSide { double d, e_part, l_dram; };
+        auto row_side = [&](double dram_words) {
+            RowSide rs;
             const bool feasible = dram_words < inf;
-            const double d = feasible ? dram_words : 0.0;
-            const double e_part = (REGROUP ? mc.e_sum : mc.e_dram) * d;
+            rs.d = feasible ? dram_words : 0.0;
+            const double over = feasible ? 0.0 : inf;
+            rs.e_part = fmax((REGROUP ? mc.e_sum : mc.e_dram) * rs.d, over);
             double l_dram;
-            if constexpr (FAST) l_dram = d * mc.dram_k;
-            else l_dram = mc.dram_bw > 0.0 ? mc.c_lat * (((d / mc.BH) * mc.word) / mc.dram_bw) : 0.0;
+            if constexpr (FAST) l_dram = rs.d * mc.dram_k;
+            else l_dram = mc.dram_bw > 0.0 ? mc.c_lat * (((rs.d / mc.BH) * mc.word) / mc.dram_bw) : 0.0;
+            rs.l_dram = fmax(l_dram, over);
+            return rs;
+        };
+        // ... joined with a combination's constants: energy and latency of the candidate
+        auto costs_of = [&](const RowSide &rs, double gb_c, double latc_c, double &en, double &lat) {
             if constexpr (REGROUP) {
-                en = e_part + gb_c;
+                en = rs.e_part + gb_c;
             } else {
-                const double gb_words = d + gb_c;
-                en = e_part + mc.e_gb * gb_words;
+                const double gb_words = rs.d + gb_c;
+                en = rs.e_part + mc.e_gb * gb_words;
                 en = en + e_rf_part;
                 en = en + e_mac_part;
             }
-            lat = fmax(l_dram, latc_c);
-            en = feasible ? en : inf;
-            lat = feasible ? lat : inf;
+            lat = fmax(rs.l_dram, latc_c);
         };
         // key o of a candidate as a (primary, secondary) pair; the secondary is 0 for the scalar keys
         auto key_of = [&](int o, double en, double lat, double &kp, double &ks) {
@@ -485,6 +492,7 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
         double min_d = inf;
         {
             u32x8 off_next = row_offs[min(row_lo, a.n_rows - 1)];
+#pragma unroll 2
             for (uint32_t i = 0; i < n_rows; ++i) {
                 const u32x8 off_now = off_next;
                 off_next = row_offs[row_lo + min(i + 1, n_rows - 1)];
@@ -495,8 +503,9 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
         // ---- fold the item into the wave's running best
         if (n_rows) {
             double en9[9], lat9[9];
+            const RowSide best_row = row_side(min_d);
 #pragma unroll
-            for (int c9 = 0; c9 < 9; ++c9) costs_of(min_d, gb[c9], latc[c9], en9[c9], lat9[c9]);
+            for (int c9 = 0; c9 < 9; ++c9) costs_of(best_row, gb[c9], latc[c9], en9[c9], lat9[c9]);
 #pragma unroll
             for (int o = 0; o < N_OBJ; ++o) {
                 if (!((MASK >> o) & 1)) continue;
@@ -544,9 +553,12 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
                     latc_u = c_u == (uint32_t)c9 ? latc[c9] : latc_u;
                 }
                 // the first row (index order) in which a tiling reaches it, at its lowest such tiling
+                u32x8 scan_next = row_offs[row_lo];
                 for (uint32_t i = 0; i < scan; ++i) {
                     double en, lat, kp, ks;
-                    costs_of(row_words(row_offs[row_lo + i]), gb_u, latc_u, en, lat);
+                    const u32x8 scan_now = scan_next;
+                    scan_next = row_offs[row_lo + min(i + 1, n_rows - 1)];
+                    costs_of(row_side(row_words(scan_now)), gb_u, latc_u, en, lat);
                     key_of(o, en, lat, kp, ks);
                     const unsigned long long hits = __ballot((kp == wave_p) & (ks == wave_s));
                     if (!hits) continue;

@@ -79,7 +79,13 @@ struct ModelConst {
     double dram_bw, gb_bw;
     double dram_k;      // word / dram_bw / n_arrays when that is exact (powers of two), else unused
     double eval_k;      // word / dram_bw when the bandwidth is a power of two (or 0), else unused
+    double gb_k;        // word / gb_bw when the buffer bandwidth is a power of two, else unused
+    // 1 / pe_rows, 1 / pe_cols, 1 / (pe_cols * g_words), rounded once: floor((a - 0.5) * 1/b) + 1 is
+    // ceil(a / b) for every 1 <= a < 2^32 (a - 0.5 over b stays 0.5 / b away from whole numbers, the two
+    // roundings move it by less than that)
+    double rcp_rows, rcp_cols, rcp_cols_g;
     uint32_t bw_pow2;   // the DRAM bandwidth is 0 or a power of two
+    uint32_t gb_pow2;   // the buffer bandwidth is a power of two
     // The four energies are whole numbers and the largest total energy stays below 2^53: every
     // product and partial sum of the energy is then an exact integer, the order of the additions
     // cannot change a bit of the result, and the search adds one row part and one tiling part.

@@ -246,6 +246,11 @@ int make_plan(const mmee_chain *w, const mmee_hw *hw, Plan &p)
     mc.bw_pow2 = bw_pow2 ? 1u : 0u;
     mc.pe_rows = hw->pe_rows; mc.pe_cols = hw->pe_cols;
     mc.g_words = hw->rf_bytes / w->word_bytes / 2;
+    mc.gb_pow2 = hw->gb_bw > 0.0 && std::frexp(hw->gb_bw, &ex) == 0.5 ? 1u : 0u;
+    mc.gb_k = mc.gb_pow2 ? mc.word / hw->gb_bw : 0.0;
+    mc.rcp_rows = 1.0 / (double)mc.pe_rows;
+    mc.rcp_cols = 1.0 / (double)mc.pe_cols;
+    mc.rcp_cols_g = 1.0 / ((double)mc.pe_cols * (double)mc.g_words);
     mc.c_softmax = w->c_softmax;
     mc.T = (uint32_t)p.T;
     mc.tpad = (uint32_t)((p.T + 63) & ~63ull);
@@ -803,6 +808,7 @@ int enqueue_batches(std::vector<BatchEntry> &entries, uint32_t flags, size_t ev_
         a.n_rows = S.batch_rows; a.n_used = S.batch_n_used;
         // every wave's piece of its group's list, cut once more into one sub-piece per row share
         a.split = v.split;
+        for (a.split_log2 = 0; (1u << a.split_log2) < v.split; ++a.split_log2) {}
         for (uint32_t sh = 0; sh < v.split; ++sh)
             for (int wv = 0; wv < BATCH_WAVES; ++wv) {
                 const uint32_t n = S.task_cnt[wv], lo = n * sh / v.split, hi = n * (sh + 1) / v.split;
