@@ -28,13 +28,30 @@ constexpr int BATCH_MAX_USED = 80;           // table entries the row lists may 
 constexpr int BATCH_MAX_ROWS = 288;          // rows the lists may hold (the pruned lists hold 270)
 constexpr int BATCH_MAX_SPLIT = 4;           // blocks that may share the rows of one chunk (small launches)
 
-struct BatchProblem {                        // one problem, in device memory
-    DivTable dv;
+constexpr int BATCH_INLINE_DIVS = 448;       // divisors (all four lists together) of a problem that rides in the kernel arguments
+
+struct BatchProblemHead {
     ModelConst mc;
     uint32_t first_item;                     // its first work item in the launch
     uint32_t n_work;                         // its work items: chunks of 64 tilings x row shares
     uint32_t slot;                           // where its N_OBJ final records go
     uint32_t pad_;
+    uint32_t X[4], ndiv[4];                  // extents and divisor counts of i, k, l, j
+};
+
+struct BatchProblem {                        // one problem, in device memory
+    BatchProblemHead h;
+    uint32_t list[4 * MAXDIV];               // the four divisor lists one after the other, ndiv[q] entries each
+};
+
+// A launch of one problem carries it inside the kernel arguments: no descriptor copy has to reach the
+// device before the kernel may start.  Same layout as the front of a BatchProblem, then the launch's
+// two-entry first-item table.
+struct BatchInline {
+    BatchProblemHead h;
+    uint32_t list[BATCH_INLINE_DIVS];
+    uint32_t firsts[2];
+    uint32_t on, pad_;
 };
 
 struct BatchArgs {
@@ -56,7 +73,21 @@ struct BatchArgs {
     Key *item_keys;                          // [n_items][N_OBJ]; written at the first item of every (block, problem) stretch
     uint32_t per_block;                      // items per block of the search launch (the finish kernel needs it)
     FinalRecord *final_out;                  // [result slot][N_OBJ]
+    BatchInline inl;                         // inl.on: the launch's only problem is here, prob and first_items are unused
 };
+
+// Where a launch's problems and first-item table are: in device memory, or inside the kernel
+// arguments themselves (which are ordinary read-only memory to the kernel).
+__device__ __forceinline__ void batch_tables(const BatchArgs &a, const BatchProblem *&probs, ConstPtr<uint32_t> &firsts)
+{
+    probs = a.prob;
+    firsts = as_constant(a.first_items);
+    if (a.inl.on) {
+        ConstPtr<char> args = (ConstPtr<char>)__builtin_amdgcn_kernarg_segment_ptr();
+        probs = (const BatchProblem *)(args + offsetof(BatchArgs, inl));
+        firsts = (ConstPtr<uint32_t>)(args + offsetof(BatchArgs, inl) + offsetof(BatchInline, firsts));
+    }
+}
 
 // ---- the boundary side, one value at a time ---------------------------------------------------
 // Every count of the model is an integer below 2^53 (the host refuses workloads where it is not),
@@ -270,7 +301,9 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
     const uint32_t item_lo = blockIdx.x * a.per_block, item_hi = min(item_lo + a.per_block, a.n_items);
     if (item_lo >= item_hi) return;
     // the first item's problem: the last p with first_items[p] <= item; later items move p on
-    ConstPtr<uint32_t> firsts = as_constant(a.first_items);
+    const BatchProblem *probs;
+    ConstPtr<uint32_t> firsts;
+    batch_tables(a, probs, firsts);
     uint32_t p;
     {
         uint32_t lo = 0, hi = a.n_prob;
@@ -310,17 +343,17 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
       uint32_t place = 0;                                    // (visit * stride) mod seg_len, kept by addition
       for (uint32_t visit = 0; visit < seg_len; ++visit, place = place + stride >= seg_len ? place + stride - seg_len : place + stride) {
         const uint32_t item = seg_first + place;
-        const BatchProblem *pr = a.prob + p;
+        const BatchProblem *pr = probs + p;
         // the descriptors are read-only while the kernel runs: wave-uniform fields through scalar loads
         ModelConst mc;
         {
-            ConstPtr<uint32_t> words = as_constant(reinterpret_cast<const uint32_t *>(&pr->mc));
+            ConstPtr<uint32_t> words = as_constant(reinterpret_cast<const uint32_t *>(&pr->h.mc));
             uint32_t buf[sizeof(ModelConst) / 4];
 #pragma unroll
             for (uint32_t k = 0; k < sizeof(ModelConst) / 4; ++k) buf[k] = words[k];
             __builtin_memcpy(&mc, buf, sizeof(ModelConst));
         }
-        ConstPtr<uint32_t> tail = as_constant(&pr->first_item);
+        ConstPtr<uint32_t> tail = as_constant(&pr->h.first_item);
         const uint32_t work = item - tail[0];
         const uint32_t t0 = (work >> a.split_log2) * BATCH_TC;
         // this wave's piece of one group's rows, within the work item's share of the chunk's rows
@@ -328,12 +361,12 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
         const uint32_t n_rows = a.task_cnt[task], row_lo = a.task_lo[task], r = a.task_g[task] & 1;
         const uint32_t T = mc.T;
         const uint32_t nt = min((uint32_t)BATCH_TC, T - t0);
-        ConstPtr<uint32_t> dvw = as_constant(reinterpret_cast<const uint32_t *>(&pr->dv));   // X[4], ndiv[4], div[4][MAXDIV]
+        ConstPtr<uint32_t> dvw = as_constant(pr->h.X);       // X[4], ndiv[4]
         const uint32_t nd0 = dvw[4], nd1 = dvw[5], nd2 = dvw[6], nd3 = dvw[7];
         if (staged_p != p) {
             // a new problem: its divisor lists into LDS (the previous item's barriers have passed)
-            const uint32_t *src = reinterpret_cast<const uint32_t *>(&pr->dv) + 8;
-            for (uint32_t k = threadIdx.x; k < 4 * MAXDIV; k += BATCH_THREADS) div_lds[k] = src[k];
+            const uint32_t n_list = nd0 + nd1 + nd2 + nd3;
+            for (uint32_t k = threadIdx.x; k < n_list; k += BATCH_THREADS) div_lds[k] = pr->list[k];
             staged_p = p;
             __syncthreads();
         }
@@ -344,7 +377,8 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
             const uint32_t t = t0 + min(lane, nt - 1);
             const uint32_t radix = wave == 0 ? 1u : (wave == 1 ? nd0 : (wave == 2 ? nd0 * nd1 : nd0 * nd1 * nd2));
             const uint32_t nq = wave == 0 ? nd0 : (wave == 1 ? nd1 : (wave == 2 ? nd2 : nd3));
-            const uint32_t g = div_lds[wave * MAXDIV + (t / radix) % nq];
+            const uint32_t list0 = wave == 0 ? 0u : (wave == 1 ? nd0 : (wave == 2 ? nd0 + nd1 : nd0 + nd1 + nd2));
+            const uint32_t g = div_lds[list0 + (t / radix) % nq];
             gd[wave * BATCH_TC + lane] = (double)g;
             gd[(4 + wave) * BATCH_TC + lane] = (double)(dvw[wave] / g);
         }
@@ -613,16 +647,28 @@ template <int MASK>
 __global__ __launch_bounds__(256) void k_batch_finish(BatchArgs a)
 {
     __shared__ Key wave_best[N_OBJ][4];
-    __shared__ BatchProblem prob_s;                          // the problem's description, fetched while the records arrive
+    __shared__ BatchProblemHead head_s;                      // the problem's description, fetched while the records arrive
+    __shared__ DivTable dv_s;
     const double inf = pos_inf();
     const uint32_t p = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const BatchProblem *probs;
+    ConstPtr<uint32_t> firsts;
+    batch_tables(a, probs, firsts);
+    const BatchProblem *pr = probs + p;
     {
-        const uint32_t *src = reinterpret_cast<const uint32_t *>(a.prob + p);
-        uint32_t *dst = reinterpret_cast<uint32_t *>(&prob_s);
-        for (uint32_t k = threadIdx.x; k < sizeof(BatchProblem) / 4; k += 256) dst[k] = src[k];
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(&pr->h);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(&head_s);
+        for (uint32_t k = threadIdx.x; k < sizeof(BatchProblemHead) / 4; k += 256) dst[k] = src[k];
+        // the packed lists back into the table form the decoding helpers take
+        uint32_t first = 0;
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t n = pr->h.ndiv[q];
+            for (uint32_t k = threadIdx.x; k < n; k += 256) dv_s.div[q][k] = pr->list[first + k];
+            first += n;
+        }
+        if (threadIdx.x < 4) { dv_s.X[threadIdx.x] = pr->h.X[threadIdx.x]; dv_s.ndiv[threadIdx.x] = pr->h.ndiv[threadIdx.x]; }
     }
-    const BatchProblem *pr = a.prob + p;
-    const uint32_t item0 = pr->first_item, n_work = pr->n_work;
+    const uint32_t item0 = pr->h.first_item, n_work = pr->h.n_work;
     const uint32_t inner0 = item0 / a.per_block + 1;         // first block boundary after the problem's first item
 #pragma unroll
     for (int o = 0; o < N_OBJ; ++o) {
@@ -643,13 +689,13 @@ __global__ __launch_bounds__(256) void k_batch_finish(BatchArgs a)
         Key k = wave_best[o][0];
         for (int wv = 1; wv < 4; ++wv)
             if (key_less(wave_best[o][wv], k)) k = wave_best[o][wv];
-        FinalRecord *fr = a.final_out + (uint64_t)prob_s.slot * N_OBJ + o;
+        FinalRecord *fr = a.final_out + (uint64_t)head_s.slot * N_OBJ + o;
         fr->key = k;
         mmee_cost c;
         mmee_mapping m;
         if (k.p < inf) {
-            eval_candidate_direct(a.enc, prob_s.dv, prob_s.mc, k.idx, c);
-            decode_candidate(prob_s.dv, prob_s.mc.T, k.idx, m);
+            eval_candidate_direct(a.enc, dv_s, head_s.mc, k.idx, c);
+            decode_candidate(dv_s, head_s.mc.T, k.idx, m);
         } else {
             c.bs_words = c.da_words = c.br_words = c.mac_total = c.comp_cycles = 0;
             c.energy_pj = inf; c.latency_cycles = inf; c.valid = 0; c.reason = 0;

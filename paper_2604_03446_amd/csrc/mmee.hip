@@ -685,6 +685,8 @@ int enqueue_search(const Plan &p, int mask, uint32_t flags, size_t slot, uint64_
     return enqueue_search_in(b, p, mask, flags, evaluated, e_limit, build_tables, bs_da_step, unproven);
 }
 
+static_assert(sizeof(BatchArgs) <= 4096, "kernel arguments are limited to 4 KiB");
+
 // ---- batched search over the pruned rows -----------------------------------------------------
 
 // masks the batched kernel is built for; other key sets take the per-problem kernels
@@ -759,49 +761,72 @@ int enqueue_batches(std::vector<BatchEntry> &entries, uint32_t flags, size_t ev_
         total_items += v.items;
     }
     if (total_items > 0x7fffffffull) return MMEE_EINVAL;
-    // blob: per variant its problem descriptors, then its first-item table
+    auto fill_head = [&](BatchProblemHead &h, uint32_t *list, const BatchEntry &e, uint32_t first_item, uint32_t split) {
+        h.mc = e.mc;
+        h.first_item = first_item;
+        h.n_work = (uint32_t)((e.plan->T + BATCH_TC - 1) / BATCH_TC) * split;
+        h.slot = (uint32_t)e.slot;
+        h.pad_ = 0;
+        uint32_t at = 0;
+        for (int q = 0; q < 4; ++q) {
+            h.X[q] = e.plan->dv.X[q];
+            h.ndiv[q] = e.plan->dv.ndiv[q];
+            for (uint32_t k = 0; k < h.ndiv[q]; ++k) list[at++] = e.plan->dv.div[q][k];
+        }
+    };
+    auto list_len = [](const Plan &pl) { return pl.dv.ndiv[0] + pl.dv.ndiv[1] + pl.dv.ndiv[2] + pl.dv.ndiv[3]; };
+    // A variant with one problem whose divisor lists fit carries it in the kernel arguments; the others'
+    // descriptors go through one blob: per variant its problem descriptors, then its first-item table.
+    auto rides_in_arguments = [&](const Variant &v) {
+        return v.members.size() == 1 && list_len(*entries[v.members[0]].plan) <= (uint32_t)BATCH_INLINE_DIVS;
+    };
     size_t blob = 0;
-    for (const Variant &v : variants) blob += sizeof(BatchProblem) * v.members.size() + sizeof(uint32_t) * ((v.members.size() + 1 + 3) & ~(size_t)3);
+    for (const Variant &v : variants)
+        if (!rides_in_arguments(v))
+            blob += sizeof(BatchProblem) * v.members.size() + sizeof(uint32_t) * ((v.members.size() + 1 + 3) & ~(size_t)3);
     int rc = ensure_batch(blob, total_items);
     if (rc) return rc;
-    size_t off = 0, prob0 = 0;
+    size_t off = 0;
     uint64_t item0 = 0;
-    struct Launch { size_t desc_off, firsts_off, n_prob, prob0; uint64_t item0, n_items; };
+    struct Launch { size_t desc_off, firsts_off, n_prob; uint64_t item0, n_items; bool in_args; };
     std::vector<Launch> launches;
     for (const Variant &v : variants) {
         Launch L;
-        L.desc_off = off; L.n_prob = v.members.size(); L.prob0 = prob0; L.item0 = item0; L.n_items = v.items;
-        BatchProblem *bp = reinterpret_cast<BatchProblem *>(S.batch_host + off);
-        off += sizeof(BatchProblem) * v.members.size();
-        L.firsts_off = off;
-        uint32_t *firsts = reinterpret_cast<uint32_t *>(S.batch_host + off);
-        off += sizeof(uint32_t) * ((v.members.size() + 1 + 3) & ~(size_t)3);
-        uint32_t item = 0;
-        for (size_t k = 0; k < v.members.size(); ++k) {
-            const BatchEntry &e = entries[v.members[k]];
-            bp[k].dv = e.plan->dv;
-            bp[k].mc = e.mc;
-            bp[k].first_item = item;
-            bp[k].n_work = (uint32_t)((e.plan->T + BATCH_TC - 1) / BATCH_TC) * v.split;
-            bp[k].slot = (uint32_t)e.slot;
-            bp[k].pad_ = 0;
-            firsts[k] = item;
-            item += bp[k].n_work;
-        }
-        firsts[v.members.size()] = item;
-        prob0 += v.members.size();
+        L.desc_off = L.firsts_off = 0;
+        L.n_prob = v.members.size(); L.item0 = item0; L.n_items = v.items; L.in_args = rides_in_arguments(v);
         item0 += v.items;
+        if (!L.in_args) {
+            L.desc_off = off;
+            BatchProblem *bp = reinterpret_cast<BatchProblem *>(S.batch_host + off);
+            off += sizeof(BatchProblem) * v.members.size();
+            L.firsts_off = off;
+            uint32_t *firsts = reinterpret_cast<uint32_t *>(S.batch_host + off);
+            off += sizeof(uint32_t) * ((v.members.size() + 1 + 3) & ~(size_t)3);
+            uint32_t item = 0;
+            for (size_t k = 0; k < v.members.size(); ++k) {
+                fill_head(bp[k].h, bp[k].list, entries[v.members[k]], item, v.split);
+                firsts[k] = item;
+                item += bp[k].h.n_work;
+            }
+            firsts[v.members.size()] = item;
+        }
         launches.push_back(L);
     }
-    HIP_TRY(hipMemcpyAsync(S.batch_dev, S.batch_host, off, hipMemcpyHostToDevice, S.stream));
     HIP_TRY(hipEventRecord(S.events[2 * ev_slot], S.stream));
+    if (off) HIP_TRY(hipMemcpyAsync(S.batch_dev, S.batch_host, off, hipMemcpyHostToDevice, S.stream));
     for (size_t k = 0; k < variants.size(); ++k) {
         const Variant &v = variants[k];
         const Launch &L = launches[k];
         BatchArgs a;
         std::memset(&a, 0, sizeof(a));
-        a.prob = reinterpret_cast<const BatchProblem *>(S.batch_dev + L.desc_off);
-        a.first_items = reinterpret_cast<const uint32_t *>(S.batch_dev + L.firsts_off);
+        if (L.in_args) {
+            fill_head(a.inl.h, a.inl.list, entries[v.members[0]], 0, v.split);
+            a.inl.firsts[0] = 0; a.inl.firsts[1] = a.inl.h.n_work;
+            a.inl.on = 1;
+        } else {
+            a.prob = reinterpret_cast<const BatchProblem *>(S.batch_dev + L.desc_off);
+            a.first_items = reinterpret_cast<const uint32_t *>(S.batch_dev + L.firsts_off);
+        }
         a.n_prob = (uint32_t)L.n_prob; a.n_items = (uint32_t)L.n_items;
         a.enc = S.enc;
         a.row_off = S.batch_row_off; a.row_df = S.batch_row_df; a.cmap = S.batch_cmap;

@@ -407,6 +407,27 @@ def test_search_widest_divisor_lists(M):
         M.mmee_space_size(dict(w, N=1441440), h)
 
 
+@pytest.mark.parametrize("pe,rf,gb_bw,dram_bw", [((12, 20), 50, 5.0, 3.0), ((7, 3), 7, 96.0, 64.0), ((24, 9), 200, 128.0, 6.0),
+                                                 ((1, 1), 6, 1.0, 0.0)])
+def test_search_odd_array_shapes_pruned_equals_exhaustive(M, pe, rf, gb_bw, dram_bw):
+    """PE arrays, register files and bandwidths that are no powers of two, on a shape with many
+    divisors (N = 720, d = 60: tiles of every size fold raggedly onto the array).  The pruned pass
+    builds its tables per chunk with reciprocal-based ceilings, the exhaustive pass reads the stored
+    tables built with integer division: same winners for every key, and the winners' records --
+    buffer<->RF words and cycles included -- are the oracle's."""
+    w = dict(B=1, H=2, N=720, d=60, word_bytes=2, tiling_mode=1, c_softmax=10)
+    h = dict(pe_rows=pe[0], pe_cols=pe[1], n_arrays=3, rf_bytes=rf, gb_bytes=1 << 17,
+             e_dram=187.5, e_gb=6.25, e_rf=1.0, e_mac=0.75, dram_bw=dram_bw, gb_bw=gb_bw)
+    ow, oh = O.workload(w), O.hw(h)
+    full = M.mmee_search_multi(w, h, [0, 1, 2, 3], M.SEARCH_EXHAUSTIVE)
+    pruned = M.mmee_search_multi(w, h, [0, 1, 2, 3], M.SEARCH_PRUNED)
+    for obj in range(4):
+        single = M.mmee_search_ex(w, h, obj, M.SEARCH_PRUNED)
+        assert full[obj].best.idx == pruned[obj].best.idx == single.best.idx, obj
+        check_result_against_oracle(pruned[obj], ow, oh)
+        check_result_against_oracle(single, ow, oh)
+
+
 def random_small_cases(count, seed):
     """Seeded small problems whose whole space the oracle enumerates in well under a second:
     every mix of whole-number / fractional energies, power-of-two / other bandwidths and array
@@ -429,7 +450,8 @@ def random_small_cases(count, seed):
         e = [float(1 + rng.next() % 300), float(1 + rng.next() % 20), float(rng.next() % 4), float(rng.next() % 3)]
         if not whole:
             e = [v + (rng.next() % 16) / 16.0 for v in e]
-        h = dict(pe_rows=1 << (rng.next() % 4), pe_cols=1 << (rng.next() % 4), n_arrays=(1, 2, 3, 4)[rng.next() % 4],
+        h = dict(pe_rows=(1, 2, 3, 4, 5, 8, 12, 16)[rng.next() % 8], pe_cols=(1, 2, 3, 4, 6, 7, 8, 16)[rng.next() % 8],
+                 n_arrays=(1, 2, 3, 4)[rng.next() % 4],
                  rf_bytes=3 * w["word_bytes"] + rng.next() % 200, gb_bytes=w["word_bytes"] * (4 + rng.next() % (N * d * 6 + 8)),
                  e_dram=e[0], e_gb=e[1], e_rf=e[2], e_mac=e[3],
                  dram_bw=(0.0, 1.0, 2.0, 3.0, 0.5, 64.0, 6.0)[rng.next() % 7], gb_bw=(0.0, 4.0, 5.0, 128.0)[rng.next() % 4])
