@@ -269,6 +269,13 @@ __device__ __forceinline__ void stage_pair_sums(double *tab_lane, ConstPtr<uint3
         }
 }
 
+// lane l's value of x, l wave-uniform
+__device__ __forceinline__ double lane_value_f64(double x, uint32_t l)
+{
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), (int)l), hi = __builtin_amdgcn_readlane(__double2hiint(x), (int)l);
+    return __hiloint2double(hi, lo);
+}
+
 // footprints of one operand under its five options (4 = takes no space)
 __device__ __forceinline__ void footprints(double (&o)[5], double tile, double d0, double d1)
 {
@@ -506,16 +513,19 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
             return rs;
         };
         // ... joined with a combination's constants: energy and latency of the candidate
-        auto costs_of = [&](const RowSide &rs, double gb_c, double latc_c, double &en, double &lat) {
+        auto costs_with = [&](const RowSide &rs, double gb_c, double latc_c, double rf_part, double mac_part, double &en, double &lat) {
             if constexpr (REGROUP) {
                 en = rs.e_part + gb_c;
             } else {
                 const double gb_words = rs.d + gb_c;
                 en = rs.e_part + mc.e_gb * gb_words;
-                en = en + e_rf_part;
-                en = en + e_mac_part;
+                en = en + rf_part;
+                en = en + mac_part;
             }
             lat = fmax(rs.l_dram, latc_c);
+        };
+        auto costs_of = [&](const RowSide &rs, double gb_c, double latc_c, double &en, double &lat) {
+            costs_with(rs, gb_c, latc_c, e_rf_part, e_mac_part, en, lat);
         };
         // key o of a candidate as a (primary, secondary) pair; the secondary is 0 for the scalar keys
         auto key_of = [&](int o, double en, double lat, double &kp, double &ks) {
@@ -526,7 +536,7 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
         double min_d = inf;
         {
             u32x8 off_next = row_offs[min(row_lo, a.n_rows - 1)];
-#pragma unroll 2
+#pragma unroll 4
             for (uint32_t i = 0; i < n_rows; ++i) {
                 const u32x8 off_now = off_next;
                 off_next = row_offs[row_lo + min(i + 1, n_rows - 1)];
@@ -586,22 +596,57 @@ __global__ __launch_bounds__(BATCH_THREADS, 4) void k_search_batch(BatchArgs a)
                     gb_u = c_u == (uint32_t)c9 ? gb[c9] : gb_u;
                     latc_u = c_u == (uint32_t)c9 ? latc[c9] : latc_u;
                 }
-                // the first row (index order) in which a tiling reaches it, at its lowest such tiling
-                u32x8 scan_next = row_offs[row_lo];
-                for (uint32_t i = 0; i < scan; ++i) {
-                    double en, lat, kp, ks;
-                    const u32x8 scan_now = scan_next;
-                    scan_next = row_offs[row_lo + min(i + 1, n_rows - 1)];
-                    costs_of(row_side(row_words(scan_now)), gb_u, latc_u, en, lat);
-                    key_of(o, en, lat, kp, ks);
-                    const unsigned long long hits = __ballot((kp == wave_p) & (ks == wave_s));
-                    if (!hits) continue;
-                    const uint64_t idx = (uint64_t)t0 + ((uint32_t)__ffsll((long long)hits) - 1u) +
-                                         (uint64_t)T * (index_row_base(row_df[row_lo + i]) + combo_rows);
-                    if (wave_p < run_p[o] || wave_s < run_s[o] || idx < run_idx[o]) {
-                        run_p[o] = wave_p; run_s[o] = wave_s; run_idx[o] = idx; run_c[o] = c_u; run_i[o] = row_lo + i; run_t0[o] = t0;
+                // The first row (index order) in which a tiling reaches it, at its lowest such tiling.  Only a
+                // tiling whose least-traffic row reaches the value can hold it at all.
+                uint32_t found_i = 0xFFFFFFFFu, found_lane = 0;
+                double en_u, lat_u, kp_u, ks_u;
+                costs_of(best_row, gb_u, latc_u, en_u, lat_u);
+                key_of(o, en_u, lat_u, kp_u, ks_u);
+                unsigned long long cands = __ballot((kp_u == wave_p) & (ks_u == wave_s));
+                if (n_rows <= 64 && 2u * (uint32_t)__popcll(cands) <= scan) {
+                    // Few such tilings: take them one by one with lane = row, all rows of the piece at once.
+                    const uint4 *ro = reinterpret_cast<const uint4 *>(a.row_off) + 2 * (row_lo + min(lane, n_rows - 1));
+                    const uint4 oa = ro[0], ob = ro[1];
+                    const uint32_t off[NSEL] = {oa.x, oa.y, oa.z, oa.w, ob.x, ob.y, ob.z, ob.w};
+                    while (cands) {
+                        const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)__ffsll((long long)cands) - 1u);
+                        cands &= cands - 1;
+                        const char *col = reinterpret_cast<const char *>(tab) + l * 8;
+                        double w[NSEL];
+#pragma unroll
+                        for (int k = 0; k < NSEL; ++k) w[k] = *reinterpret_cast<const double *>(col + off[k]);
+                        // (a tiling beyond the chunk's end is never among them: plain capacity)
+                        const bool ok = fmax(w[0] + w[2] + w[1], w[3] + w[2] + w[4]) <= mc.cap_words;
+                        double en, lat, kp, ks;
+                        costs_with(row_side(ok ? w[5] + w[6] + w[7] : inf), lane_value_f64(gb_u, l), lane_value_f64(latc_u, l),
+                                   lane_value_f64(e_rf_part, l), lane_value_f64(e_mac_part, l), en, lat);
+                        key_of(o, en, lat, kp, ks);
+                        const unsigned long long hits = __ballot((lane < scan) & (kp == wave_p) & (ks == wave_s));
+                        if (!hits) continue;
+                        const uint32_t i = (uint32_t)__ffsll((long long)hits) - 1u;
+                        if (i < found_i) { found_i = i; found_lane = l; }     // ascending tilings: the lower one stays on equal rows
+                        if (found_i == 0) break;
                     }
-                    break;
+                } else {
+                    u32x8 scan_next = row_offs[row_lo];
+                    for (uint32_t i = 0; i < scan; ++i) {
+                        double en, lat, kp, ks;
+                        const u32x8 scan_now = scan_next;
+                        scan_next = row_offs[row_lo + min(i + 1, n_rows - 1)];
+                        costs_of(row_side(row_words(scan_now)), gb_u, latc_u, en, lat);
+                        key_of(o, en, lat, kp, ks);
+                        const unsigned long long hits = __ballot((kp == wave_p) & (ks == wave_s));
+                        if (!hits) continue;
+                        found_i = i;
+                        found_lane = (uint32_t)__ffsll((long long)hits) - 1u;
+                        break;
+                    }
+                }
+                if (found_i != 0xFFFFFFFFu) {
+                    const uint64_t idx = (uint64_t)t0 + found_lane + (uint64_t)T * (index_row_base(row_df[row_lo + found_i]) + combo_rows);
+                    if (wave_p < run_p[o] || wave_s < run_s[o] || idx < run_idx[o]) {
+                        run_p[o] = wave_p; run_s[o] = wave_s; run_idx[o] = idx; run_c[o] = c_u; run_i[o] = row_lo + found_i; run_t0[o] = t0;
+                    }
                 }
             }
         }
