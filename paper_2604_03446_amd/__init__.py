@@ -222,16 +222,26 @@ def mmee_search_multi(w, h, objectives, flags: int = SEARCH_PRUNED):
     return list(out)
 
 
+class ManyPoints:
+    """The argument arrays of mmee_search_many, marshalled once for repeated calls."""
+
+    def __init__(self, points):
+        n = self.n = len(points)
+        self.ws = (Workload * n)(*[workload(p[0]) for p in points])
+        self.hs = (Hw * n)(*[hw(p[1]) for p in points])
+        self.objs = (C.c_int * n)(*[p[2] for p in points])
+        self.out = (Result * n)()
+        self.codes = (C.c_int * n)()
+
+
 def mmee_search_many(points, flags: int = SEARCH_PRUNED):
-    """points: sequence of (workload, hw, objective).  Returns (results, codes)."""
-    n = len(points)
-    ws = (Workload * n)(*[workload(p[0]) for p in points])
-    hs = (Hw * n)(*[hw(p[1]) for p in points])
-    objs = (C.c_int * n)(*[p[2] for p in points])
-    out = (Result * n)()
-    codes = (C.c_int * n)()
-    _check(_lib.mmee_search_many(ws, hs, objs, n, flags, out, codes), "mmee_search_many", allow=(ENOFEASIBLE,))
-    return list(out), list(codes)
+    """points: sequence of (workload, hw, objective), or a ManyPoints made from one (its result
+    arrays are then reused by the next call).  Returns (results, codes)."""
+    m = points if isinstance(points, ManyPoints) else ManyPoints(points)
+    _check(_lib.mmee_search_many(m.ws, m.hs, m.objs, m.n, flags, m.out, m.codes), "mmee_search_many", allow=(ENOFEASIBLE,))
+    if m is points:
+        return m.out, m.codes                   # the arrays themselves: valid until the next call with this ManyPoints
+    return list(m.out), list(m.codes)
 
 
 def mmee_chain_space_size(c, h) -> int:
