@@ -638,7 +638,12 @@ struct SearchArgs {
     const Key *lat_cap;          // LATCAP kernels only: candidates with a latency above lat_cap->p are left out
     const uint64_t *ctab_e;
     DivTable const *dv;          // device copy, for the final record's mapping
+    // k_search_dense, scalar keys: per key the lowest value any wave of the launch has recorded so far, as
+    // the bit pattern of the (non-negative) double; +inf between launches.  Null: no sharing between blocks.
+    unsigned long long *hints;
 };
+
+constexpr unsigned long long INF_BITS = 0x7ff0000000000000ull;
 
 constexpr int BLOCKS_PER_CU = 2;       // what LDS (64 KB per block) lets a CU hold
 constexpr int TC = 64;                 // tilings per coarse item
@@ -846,6 +851,7 @@ __device__ __forceinline__ void finish_grid(const SearchArgs &a, Key (*wave_best
         for (int q = 0; q < 7; ++q) fr->map[q] = mbuf[q];
     }
     if (threadIdx.x == 0) { *a.ticket = 0; *a.work_counter = 0; }   // ready for the next launch on this stream
+    if (threadIdx.x < N_OBJ && a.hints) a.hints[threadIdx.x] = INF_BITS;
 }
 
 // MASK: bit0 energy, bit1 latency, bit2 latency-then-energy, bit3 energy-delay product (Sec. VII-K).
@@ -1203,12 +1209,20 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
     __shared__ Key wave_best[N_OBJ][DENSE_WAVES];
     __shared__ uint32_t is_last;
     __shared__ uint32_t s_item;
+    // Scalar keys: the lowest value any wave of this block has recorded (bit pattern; the keys are
+    // non-negative, so the patterns order like the values), refreshed once per item from the launch-wide
+    // one.  A wave whose values all lie strictly above it cannot hold the optimum and recovers no position.
+    __shared__ unsigned long long hint_bits[N_OBJ];
 
     constexpr bool LAZY = !(MASK & 4);             // the energy bound of LIMIT masks values, which the lazy argmin handles too
     const double inf = pos_inf();
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (lane < N_OBJ) { wave_best[lane][wave].p = inf; wave_best[lane][wave].s = 0.0; wave_best[lane][wave].idx = ~0ull; }
+    if (threadIdx.x < N_OBJ) hint_bits[threadIdx.x] = INF_BITS;
+    unsigned long long hint_seen[N_OBJ];          // thread 0: the launch-wide values as last read
+#pragma unroll
+    for (int o = 0; o < N_OBJ; ++o) hint_seen[o] = INF_BITS;
     double run_p[N_OBJ];
     uint64_t run_idx[N_OBJ];
 #pragma unroll
@@ -1233,12 +1247,36 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
 
     uint32_t upcoming = blockIdx.x;
     while (true) {
-        if (threadIdx.x == 0) s_item = upcoming;
+        if (threadIdx.x == 0) {
+            s_item = upcoming;
+            if constexpr (LAZY) {
+                // exchange with the launch-wide values read during the previous item: take what is lower there,
+                // hand over what is lower here (no reply awaited)
+                if (a.hints) {
+#pragma unroll
+                    for (int o = 0; o < N_OBJ; ++o) {
+                        if (!((MASK >> o) & 1)) continue;
+                        const unsigned long long here = hint_bits[o];
+                        if (hint_seen[o] < here) atomicMin(&hint_bits[o], hint_seen[o]);
+                        else if (here < hint_seen[o])
+                            (void)__hip_atomic_fetch_min(a.hints + o, here, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
+            }
+        }
         __syncthreads();                          // also: the previous item's LDS readers are done
         const uint32_t item = s_item;
         if (item >= a.n_items) break;
-        if (threadIdx.x == 0)
+        if (threadIdx.x == 0) {
             upcoming = gridDim.x + __hip_atomic_fetch_add(a.work_counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if constexpr (LAZY) {
+                if (a.hints) {
+#pragma unroll
+                    for (int o = 0; o < N_OBJ; ++o)
+                        if ((MASK >> o) & 1) hint_seen[o] = __hip_atomic_load(a.hints + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
         const bool fine = item >= a.n_coarse_items;
         uint32_t chunk, group;
         if (!fine) { chunk = item / a.d_gc; group = item % a.d_gc; }
@@ -1401,7 +1439,8 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
                 double mine_v = best[0];
 #pragma unroll
                 for (int c9 = 1; c9 < 9; ++c9) mine_v = fmin(mine_v, best[c9]);
-                if (!__ballot(mine_v <= run_p[o] && mine_v < inf)) continue;   // the usual case: nothing new here
+                const double hint = __longlong_as_double((long long)hint_bits[o]);
+                if (!__ballot(mine_v <= run_p[o] && mine_v < inf && mine_v <= hint)) continue;   // the usual case: nothing new here
                 const double wave_v = uniform_f64(wave_min_f64(mine_v));
                 // the lowest combination in which some tiling reaches the minimum: its candidates
                 // precede those of every higher combination
@@ -1460,7 +1499,10 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
                     if (!hits) continue;
                     const uint64_t idx = (uint64_t)t0 + ((uint32_t)__ffsll((long long)hits) - 1u) +
                                          (uint64_t)a.mc.T * (index_row_of(code) + combo_rows);
-                    if (wave_v < run_p[o] || idx < run_idx[o]) { run_p[o] = wave_v; run_idx[o] = idx; }
+                    if (wave_v < run_p[o] || idx < run_idx[o]) {
+                        run_p[o] = wave_v; run_idx[o] = idx;
+                        if (lane == 0) atomicMin(&hint_bits[o], (unsigned long long)__double_as_longlong(wave_v));
+                    }
                     break;
                 }
             }

@@ -83,6 +83,7 @@ struct State {
     Key *partials = nullptr;
     size_t partials_cap = 0;
     uint32_t *ticket = nullptr;
+    unsigned long long *hints = nullptr;
     // result records: pinned host memory that the search's last block writes directly
     FinalRecord *final_host = nullptr, *final_map = nullptr;     // host address / device address
     DivTable *dv_dev = nullptr;
@@ -117,6 +118,7 @@ struct Bufs {
     Key *partials = nullptr;
     size_t partials_cap = 0;                    // blocks the partial records have room for
     uint32_t *ticket = nullptr;                 // [0] finish ticket, [1] work counter
+    unsigned long long *hints = nullptr;        // [N_OBJ] launch-wide lowest values of the dense kernel; null: not shared
     Key *key_dev = nullptr;
     FinalRecord *final_dev = nullptr;           // device address of this pass's N_OBJ records
     DivTable *dv_dev = nullptr;                 // this pass's copy of the divisor lists
@@ -281,6 +283,12 @@ int ensure_ready()
     HIP_TRY(hipMalloc(&S.counts_dev, sizeof(uint32_t) * 8));
     HIP_TRY(hipMalloc(&S.key_dev, sizeof(Key) * N_OBJ));
     HIP_TRY(hipMalloc(&S.ticket, 2 * sizeof(uint32_t)));        // [0] finish ticket, [1] work counter
+    HIP_TRY(hipMalloc(&S.hints, N_OBJ * sizeof(unsigned long long)));
+    {
+        // +inf until a launch lowers them; the last block of every launch puts +inf back
+        static const unsigned long long inf_bits[N_OBJ] = {INF_BITS, INF_BITS, INF_BITS, INF_BITS};
+        HIP_TRY(hipMemcpyAsync(S.hints, inf_bits, sizeof(inf_bits), hipMemcpyHostToDevice, S.stream));
+    }
     // on the library's stream, like the kernels that follow: a caller's non-blocking stream is not
     // ordered against the null stream
     HIP_TRY(hipMemsetAsync(S.ticket, 0, 2 * sizeof(uint32_t), S.stream));
@@ -484,7 +492,7 @@ int state_bufs(const Plan &p, size_t slot, Bufs &b)
     b.cls_dev = S.cls_dev; b.n_cls = S.n_cls;
     b.btab = S.btab; b.ctab_s = S.ctab_s; b.ctab_e = S.ctab_e;
     b.partials = S.partials; b.partials_cap = S.partials_cap;
-    b.ticket = S.ticket; b.key_dev = S.key_dev;
+    b.ticket = S.ticket; b.hints = S.hints; b.key_dev = S.key_dev;
     b.final_dev = S.final_map + N_OBJ * slot;
     b.dv_dev = S.dv_dev + slot;
     b.ev_begin = S.events[2 * slot]; b.ev_end = S.events[2 * slot + 1];
@@ -606,7 +614,7 @@ int enqueue_search_in(const Bufs &B, const Plan &p, int mask, uint32_t flags, ui
     const uint64_t nblocks = std::min<uint64_t>(
         n_items, dense ? (uint64_t)B.resident_blocks / BLOCKS_PER_CU * DENSE_BLOCKS_PER_CU : (uint64_t)B.resident_blocks);
     if (nblocks > B.partials_cap) return MMEE_EINVAL;
-    a.partials = B.partials; a.ticket = B.ticket; a.work_counter = B.ticket + 1;
+    a.partials = B.partials; a.ticket = B.ticket; a.work_counter = B.ticket + 1; a.hints = B.hints;
     a.final_out = B.final_dev;
     a.dv = B.dv_dev;
     if (B.ev_begin) HIP_TRY(hipEventRecord(B.ev_begin, S.stream));
@@ -1441,7 +1449,7 @@ void mmee_shutdown(void)
     (void)hipFree(S.rows[0]); (void)hipFree(S.rows[1]); (void)hipFree(S.counts_dev);
     (void)hipFree(S.row_enc[0]); (void)hipFree(S.row_enc[1]);
     (void)hipFree(S.btab); (void)hipFree(S.ctab_s); (void)hipFree(S.ctab_e);
-    (void)hipFree(S.partials); (void)hipFree(S.ticket);
+    (void)hipFree(S.partials); (void)hipFree(S.ticket); (void)hipFree(S.hints);
     (void)hipFree(S.dv_dev); (void)hipFree(S.eval_dev);
     if (S.final_host) (void)hipHostFree(S.final_host);
     if (S.batch_host) (void)hipHostFree(S.batch_host);
