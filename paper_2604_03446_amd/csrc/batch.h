@@ -269,13 +269,6 @@ __device__ __forceinline__ void stage_pair_sums(double *tab_lane, ConstPtr<uint3
         }
 }
 
-// lane l's value of x, l wave-uniform
-__device__ __forceinline__ double lane_value_f64(double x, uint32_t l)
-{
-    const int lo = __builtin_amdgcn_readlane(__double2loint(x), (int)l), hi = __builtin_amdgcn_readlane(__double2hiint(x), (int)l);
-    return __hiloint2double(hi, lo);
-}
-
 // footprints of one operand under its five options (4 = takes no space)
 __device__ __forceinline__ void footprints(double (&o)[5], double tile, double d0, double d1)
 {

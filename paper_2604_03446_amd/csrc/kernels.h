@@ -97,6 +97,13 @@ __device__ __forceinline__ uint32_t wave_min_u32(uint32_t x)
     return x;
 }
 
+// lane l's value of x, l wave-uniform
+__device__ __forceinline__ double lane_value_f64(double x, uint32_t l)
+{
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), (int)l), hi = __builtin_amdgcn_readlane(__double2hiint(x), (int)l);
+    return __hiloint2double(hi, lo);
+}
+
 __device__ __forceinline__ double uniform_f64(double x)
 {
     unsigned long long b = (unsigned long long)__double_as_longlong(x);
@@ -1451,23 +1458,29 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
                 const uint32_t combo_rows = 30000u * (c_u % 3) + 90000u * (c_u / 3);
                 const uint64_t lowest_possible = (uint64_t)t0 + (uint64_t)a.mc.T * (index_row_of(0) + combo_rows);
                 if (!(wave_v < run_p[o] || lowest_possible < run_idx[o])) continue;
-                // Recover the row: go through the task's rows in index order and cost them again for
-                // combination c_u, with the very operations of the loop above; the first row in which
-                // a tiling reaches the minimum holds the lowest index, at its lowest such tiling.
-                double gb_u = gb[0], latc_u = latc[0], slow_u = too_slow[0];
+                // Make the value known before its position is: of the waves of a block that reach this point
+                // together, only those holding the lowest value go on (the holder of the lowest value always
+                // passes its own mark, so what the others leave out is recorded by it).
+                if (lane == 0) atomicMin(&hint_bits[o], (unsigned long long)__double_as_longlong(wave_v));
+                if (wave_v > __longlong_as_double((long long)hint_bits[o])) continue;
+                // Recover the row: the first row of the task (index order) in which a tiling reaches the
+                // minimum under combination c_u holds the lowest index, at its lowest such tiling.  Rows are
+                // costed again with the very operations of the loop above.
+                double gb_u = gb[0], latc_u = latc[0], slow_u = too_slow[0], best_u = best[0];
 #pragma unroll
                 for (int c9 = 1; c9 < 9; ++c9) {
                     gb_u = c_u == (uint32_t)c9 ? gb[c9] : gb_u;
                     latc_u = c_u == (uint32_t)c9 ? latc[c9] : latc_u;
                     slow_u = c_u == (uint32_t)c9 ? too_slow[c9] : slow_u;
+                    best_u = c_u == (uint32_t)c9 ? best[c9] : best_u;
                 }
-                for (uint32_t code = 0; code < npd * 25u; ++code) {
-                    const uint4 e_de = enc[row_de0 + 25u * (code / 25u)];
-                    const uint4 e_ab = enc[row0 + code % 25u];
-                    const double bs1 = (col[sel_of(e_ab, 0) * LDS_ENT] + c_bs) + col[sel_of(e_de, 1) * LDS_ENT];
-                    const double bs2 = col[sel_of(e_de, 3) * LDS_ENT] + (c_bs + col[sel_of(e_ab, 4) * LDS_ENT]);
-                    const double dram2 = (col[sel_of(e_ab, 5) * LDS_ENT] + c_da) + col[sel_of(e_de, 6) * LDS_ENT];
-                    bool ok2 = fmax(bs1, bs2) <= cap;
+                // one row of one tiling: table values x (A, B), y (D, E), the class's C terms, the tiling's constants
+                auto recost = [&](double x_bs, double x_ret, double x_da, double y_ret, double y_bs, double y_da, double cbs,
+                                  double cda, double cap_t, double gb_t, double latc_t, double slow_t, double rf_t, double mac_t) {
+                    const double bs1 = (x_bs + cbs) + y_ret;
+                    const double bs2 = y_bs + (cbs + x_ret);
+                    const double dram2 = (x_da + cda) + y_da;
+                    bool ok2 = fmax(bs1, bs2) <= cap_t;
                     double e2 = (REGROUP ? a.mc.e_sum : a.mc.e_dram) * dram2;
                     double l2;
                     if constexpr (FAST) l2 = dram2 * a.mc.dram_k;
@@ -1480,30 +1493,69 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
                     pin(l2);
                     double en2;
                     if constexpr (REGROUP) {
-                        en2 = e2 + gb_u;
+                        en2 = e2 + gb_t;
                     } else {
-                        double gb2 = dram2 + gb_u;
+                        double gb2 = dram2 + gb_t;
                         en2 = e2 + a.mc.e_gb * gb2;
-                        en2 = en2 + e_rf_part;
-                        en2 = en2 + e_mac_part;
-                        if constexpr (LATCAP) en2 = fmax(en2, slow_u);
+                        en2 = en2 + rf_t;
+                        en2 = en2 + mac_t;
+                        if constexpr (LATCAP) en2 = fmax(en2, slow_t);
                     }
-                    double lat2 = fmax(l2, latc_u);
+                    double lat2 = fmax(l2, latc_t);
                     if constexpr (LIMIT) {
                         const bool out_of_range = !(en2 < a.e_limit);
                         en2 = out_of_range ? inf : en2;
                         lat2 = out_of_range ? inf : lat2;
                     }
-                    const double val2 = o == 0 ? en2 : (o == 1 ? lat2 : en2 * lat2);
-                    const unsigned long long hits = __ballot(val2 == wave_v);
-                    if (!hits) continue;
-                    const uint64_t idx = (uint64_t)t0 + ((uint32_t)__ffsll((long long)hits) - 1u) +
-                                         (uint64_t)a.mc.T * (index_row_of(code) + combo_rows);
-                    if (wave_v < run_p[o] || idx < run_idx[o]) {
-                        run_p[o] = wave_v; run_idx[o] = idx;
-                        if (lane == 0) atomicMin(&hint_bits[o], (unsigned long long)__double_as_longlong(wave_v));
+                    return o == 0 ? en2 : (o == 1 ? lat2 : en2 * lat2);
+                };
+                const uint32_t n_codes = npd * 25u;
+                uint32_t found_code = 0xFFFFFFFFu, found_lane = 0;
+                // only a tiling whose own minimum under c_u is the wave's can hold it
+                unsigned long long cands = __ballot(best_u == wave_v);
+                if (__popcll(cands) <= 4) {
+                    // few such tilings: one at a time with lane = row (64 rows of the task per step)
+                    while (cands) {
+                        const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)__ffsll((long long)cands) - 1u);
+                        cands &= cands - 1;
+                        const double *col_l = tab + l;                  // l < nt: a lane beyond the chunk holds +inf
+                        const double cbs_l = lane_value_f64(c_bs, l), cda_l = lane_value_f64(c_da, l);
+                        const double gb_l = lane_value_f64(gb_u, l), latc_l = lane_value_f64(latc_u, l), slow_l = lane_value_f64(slow_u, l);
+                        const double rf_l = lane_value_f64(e_rf_part, l), mac_l = lane_value_f64(e_mac_part, l);
+                        for (uint32_t code0 = 0; code0 < n_codes && code0 < found_code; code0 += 64) {
+                            const uint32_t code = min(code0 + lane, n_codes - 1);
+                            const uint4 e_de = a.enc[row_de0 + 25u * (code / 25u)];
+                            const uint4 e_ab = a.enc[row0 + code % 25u];
+                            const double val2 = recost(col_l[sel_of(e_ab, 0) * LDS_ENT], col_l[sel_of(e_ab, 4) * LDS_ENT],
+                                                       col_l[sel_of(e_ab, 5) * LDS_ENT], col_l[sel_of(e_de, 1) * LDS_ENT],
+                                                       col_l[sel_of(e_de, 3) * LDS_ENT], col_l[sel_of(e_de, 6) * LDS_ENT], cbs_l, cda_l,
+                                                       a.mc.cap_words, gb_l, latc_l, slow_l, rf_l, mac_l);
+                            const unsigned long long hits = __ballot(code0 + lane < n_codes && val2 == wave_v);
+                            if (!hits) continue;
+                            const uint32_t c_hit = code0 + (uint32_t)__ffsll((long long)hits) - 1u;
+                            if (c_hit < found_code) { found_code = c_hit; found_lane = l; }   // ascending tilings: the lower one stays
+                            break;
+                        }
+                        if (found_code == 0) break;
                     }
-                    break;
+                } else {
+                    for (uint32_t code = 0; code < n_codes; ++code) {
+                        const uint4 e_de = enc[row_de0 + 25u * (code / 25u)];
+                        const uint4 e_ab = enc[row0 + code % 25u];
+                        const double val2 = recost(col[sel_of(e_ab, 0) * LDS_ENT], col[sel_of(e_ab, 4) * LDS_ENT],
+                                                   col[sel_of(e_ab, 5) * LDS_ENT], col[sel_of(e_de, 1) * LDS_ENT],
+                                                   col[sel_of(e_de, 3) * LDS_ENT], col[sel_of(e_de, 6) * LDS_ENT], c_bs, c_da, cap,
+                                                   gb_u, latc_u, slow_u, e_rf_part, e_mac_part);
+                        const unsigned long long hits = __ballot(val2 == wave_v);
+                        if (!hits) continue;
+                        found_code = code;
+                        found_lane = (uint32_t)__ffsll((long long)hits) - 1u;
+                        break;
+                    }
+                }
+                if (found_code != 0xFFFFFFFFu) {
+                    const uint64_t idx = (uint64_t)t0 + found_lane + (uint64_t)a.mc.T * (index_row_of(found_code) + combo_rows);
+                    if (wave_v < run_p[o] || idx < run_idx[o]) { run_p[o] = wave_v; run_idx[o] = idx; }
                 }
             }
             continue;
