@@ -11,6 +11,7 @@
 //   k_decode         online:   index -> mapping
 #pragma once
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include <math.h>
 #include "../../include/mmee.h"
 #include "layout.h"
@@ -1410,16 +1411,21 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
             double x_bs = col[sel_of(e_c, 0) * LDS_ENT], x_ret = col[sel_of(e_c, 4) * LDS_ENT],
                    x_da = col[sel_of(e_c, 5) * LDS_ENT];                  // row0 is (p_A, p_B) = 0
             uint4 e_ab = enc[row0 + 1];
-            for (uint32_t ab = 0; ab < 25; ++ab) {
-                const double now_bs = x_bs, now_ret = x_ret, now_da = x_da;
-                x_bs = col[sel_of(e_ab, 0) * LDS_ENT];
-                x_ret = col[sel_of(e_ab, 4) * LDS_ENT];
-                x_da = col[sel_of(e_ab, 5) * LDS_ENT];
-                e_ab = enc[row0 + min(ab + 2, 24u)];
+            // the loop over (p_A, p_B), for a task of five p_D values or of one: no branch between the rows
+            auto ab_loop = [&](auto five) {
+                constexpr int NPD = decltype(five)::value ? 5 : 1;
+                for (uint32_t ab = 0; ab < 25; ++ab) {
+                    const double now_bs = x_bs, now_ret = x_ret, now_da = x_da;
+                    x_bs = col[sel_of(e_ab, 0) * LDS_ENT];
+                    x_ret = col[sel_of(e_ab, 4) * LDS_ENT];
+                    x_da = col[sel_of(e_ab, 5) * LDS_ENT];
+                    e_ab = enc[row0 + min(ab + 2, 24u)];
 #pragma unroll
-                for (int q = 0; q < 5; ++q)
-                    if ((uint32_t)q < npd) cost_row(now_bs + y_ret[q], y_bs[q] + now_ret, now_da + y_da[q], 0);
-            }
+                    for (int q = 0; q < NPD; ++q) cost_row(now_bs + y_ret[q], y_bs[q] + now_ret, now_da + y_da[q], 0);
+                }
+            };
+            if (npd == 5) ab_loop(std::true_type{});
+            else ab_loop(std::false_type{});
         } else {
             // index order (p_D, then (p_A, p_B)): a strict < then keeps the lowest index on ties
             for (uint32_t q = 0; q < npd; ++q) {
