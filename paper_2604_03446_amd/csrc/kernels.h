@@ -1209,11 +1209,35 @@ constexpr int DENSE_THREADS = 512;           // eight waves, two blocks per CU
 constexpr int DENSE_BLOCKS_PER_CU = 2;
 constexpr int DENSE_WAVES = DENSE_THREADS / 64;
 
+// k_search_dense keeps its table slice as pairs of entries: the direct global-to-LDS load writes one
+// contiguous KiB per wave instruction (lane l's 16 bytes at base + 16 l), i.e. the 64 tilings of two
+// entries; 16 bytes of padding per pair spread the pairs over the banks for the reads that go across
+// entries.  Entry e of tiling t: tab[dense_at(e) + t].
+constexpr int DENSE_PAIRS = (NENT + 1) / 2;
+constexpr int DENSE_PAIR_F64 = 2 * TC + 2;
+__device__ __forceinline__ uint32_t dense_at(uint32_t e) { return e * (DENSE_PAIR_F64 / 2) - (e & 1u); }
+
+// The chunk's 64 tilings of every entry, straight from the global table into LDS: no registers, no
+// LDS write instructions, all of a wave's loads in flight at once.  Columns beyond the last tiling exist
+// in the global table (it is padded to whole chunks and repeats its last tiling there); so does the
+// entry after the last one of an odd count.
+template <int WAVES>
+__device__ __forceinline__ void stage_tables_direct(const SearchArgs &a, double *tab, uint32_t t0, uint32_t wave, uint32_t lane)
+{
+    static_assert(NENT + 1 <= NENT_ALL, "the pair of the last entry reads one entry beyond it");
+    for (uint32_t pair = wave; pair < (uint32_t)DENSE_PAIRS; pair += WAVES) {
+        const uint32_t e = 2 * pair + (lane >> 5);
+        const double *src = a.btab + (uint64_t)e * a.mc.tpad + t0 + 2 * (lane & 31);
+        __builtin_amdgcn_global_load_lds(src, tab + pair * DENSE_PAIR_F64, 16, 0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0);               // the loads count as vector memory operations: all of them have landed
+}
+
 template <int MASK, bool FAST, bool LIMIT = false, bool REGROUP = false, bool LATCAP = false>
 __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
 {
     static_assert(!LATCAP || (MASK == 1 && !LIMIT), "the latency cap goes with the energy key alone");
-    __shared__ double tab[NENT * LDS_ENT];
+    __shared__ double tab[DENSE_PAIRS * DENSE_PAIR_F64];
     __shared__ Key wave_best[N_OBJ][DENSE_WAVES];
     __shared__ uint32_t is_last;
     __shared__ uint32_t s_item;
@@ -1291,7 +1315,7 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
         else { const uint32_t j = item - a.n_coarse_items; chunk = a.d_ncc + j / a.d_gf; group = j % a.d_gf; }
         const uint32_t t0 = chunk * TC;
         const uint32_t nt = min((uint32_t)TC, a.mc.T - t0);
-        stage_tables<TC / 2, DENSE_THREADS>(a, tab, t0, nt);
+        stage_tables_direct<DENSE_WAVES>(a, tab, t0, wave, lane);
         __syncthreads();
 
         const uint32_t per_class = fine ? 25u : 5u;
@@ -1317,14 +1341,14 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
             too_slow[c] = LATCAP && !(latc[c] <= lat_cap && lat_cap < inf) ? inf : 0.0;   // no cap found: nothing qualifies
             if constexpr (LATCAP && REGROUP) gb[c] = fmax(gb[c], too_slow[c]);
         }
-        const double *col = tab + tl;                         // entry e of this tiling: col[e * LDS_ENT]
+        const double *col = tab + tl;                         // entry e of this tiling: col[dense_at(e)]
 
         // the class row and the task's (D, E) rows: all requested before the first is used
         const uint4 e_c = enc[row0];
         uint4 e_de5[5];
 #pragma unroll
         for (int q = 0; q < 5; ++q) e_de5[q] = enc[row_de0 + 25u * min((uint32_t)q, npd - 1)];
-        const double c_bs = col[sel_of(e_c, 2) * LDS_ENT], c_da = col[sel_of(e_c, 7) * LDS_ENT];
+        const double c_bs = col[dense_at(sel_of(e_c, 2))], c_da = col[dense_at(sel_of(e_c, 7))];
 
         double bestE[9], bestL[9], bestLE_l[9], bestLE_e[9], bestP[9];
         uint32_t codeE[9], codeL[9], codeLE[9], codeP[9];
@@ -1404,21 +1428,22 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
 #pragma unroll
             for (int q = 0; q < 5; ++q) {
                 // the class's C terms ride on the (D, E) parts
-                y_ret[q] = c_bs + col[sel_of(e_de5[q], 1) * LDS_ENT];
-                y_bs[q] = col[sel_of(e_de5[q], 3) * LDS_ENT] + c_bs;
-                y_da[q] = c_da + col[sel_of(e_de5[q], 6) * LDS_ENT];
+                y_ret[q] = c_bs + col[dense_at(sel_of(e_de5[q], 1))];
+                y_bs[q] = col[dense_at(sel_of(e_de5[q], 3))] + c_bs;
+                y_da[q] = c_da + col[dense_at(sel_of(e_de5[q], 6))];
             }
-            double x_bs = col[sel_of(e_c, 0) * LDS_ENT], x_ret = col[sel_of(e_c, 4) * LDS_ENT],
-                   x_da = col[sel_of(e_c, 5) * LDS_ENT];                  // row0 is (p_A, p_B) = 0
+            double x_bs = col[dense_at(sel_of(e_c, 0))], x_ret = col[dense_at(sel_of(e_c, 4))],
+                   x_da = col[dense_at(sel_of(e_c, 5))];                  // row0 is (p_A, p_B) = 0
             uint4 e_ab = enc[row0 + 1];
             // the loop over (p_A, p_B), for a task of five p_D values or of one: no branch between the rows
             auto ab_loop = [&](auto five) {
                 constexpr int NPD = decltype(five)::value ? 5 : 1;
+#pragma unroll 5
                 for (uint32_t ab = 0; ab < 25; ++ab) {
                     const double now_bs = x_bs, now_ret = x_ret, now_da = x_da;
-                    x_bs = col[sel_of(e_ab, 0) * LDS_ENT];
-                    x_ret = col[sel_of(e_ab, 4) * LDS_ENT];
-                    x_da = col[sel_of(e_ab, 5) * LDS_ENT];
+                    x_bs = col[dense_at(sel_of(e_ab, 0))];
+                    x_ret = col[dense_at(sel_of(e_ab, 4))];
+                    x_da = col[dense_at(sel_of(e_ab, 5))];
                     e_ab = enc[row0 + min(ab + 2, 24u)];
 #pragma unroll
                     for (int q = 0; q < NPD; ++q) cost_row(now_bs + y_ret[q], y_bs[q] + now_ret, now_da + y_da[q], 0);
@@ -1430,12 +1455,12 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
             // index order (p_D, then (p_A, p_B)): a strict < then keeps the lowest index on ties
             for (uint32_t q = 0; q < npd; ++q) {
                 const uint4 e_de = enc[row_de0 + 25u * q];
-                const double y_ret = col[sel_of(e_de, 1) * LDS_ENT], y_bs = col[sel_of(e_de, 3) * LDS_ENT],
-                             y_da = col[sel_of(e_de, 6) * LDS_ENT];
+                const double y_ret = col[dense_at(sel_of(e_de, 1))], y_bs = col[dense_at(sel_of(e_de, 3))],
+                             y_da = col[dense_at(sel_of(e_de, 6))];
                 for (uint32_t ab = 0; ab < 25; ++ab) {
                     const uint4 e_ab = enc[row0 + ab];
-                    const double x_bs = col[sel_of(e_ab, 0) * LDS_ENT], x_ret = col[sel_of(e_ab, 4) * LDS_ENT],
-                                 x_da = col[sel_of(e_ab, 5) * LDS_ENT];
+                    const double x_bs = col[dense_at(sel_of(e_ab, 0))], x_ret = col[dense_at(sel_of(e_ab, 4))],
+                                 x_da = col[dense_at(sel_of(e_ab, 5))];
                     cost_row((x_bs + c_bs) + y_ret, (y_bs + c_bs) + x_ret, (x_da + y_da) + c_da, q * 25u + ab);
                 }
             }
@@ -1532,9 +1557,9 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
                             const uint32_t code = min(code0 + lane, n_codes - 1);
                             const uint4 e_de = a.enc[row_de0 + 25u * (code / 25u)];
                             const uint4 e_ab = a.enc[row0 + code % 25u];
-                            const double val2 = recost(col_l[sel_of(e_ab, 0) * LDS_ENT], col_l[sel_of(e_ab, 4) * LDS_ENT],
-                                                       col_l[sel_of(e_ab, 5) * LDS_ENT], col_l[sel_of(e_de, 1) * LDS_ENT],
-                                                       col_l[sel_of(e_de, 3) * LDS_ENT], col_l[sel_of(e_de, 6) * LDS_ENT], cbs_l, cda_l,
+                            const double val2 = recost(col_l[dense_at(sel_of(e_ab, 0))], col_l[dense_at(sel_of(e_ab, 4))],
+                                                       col_l[dense_at(sel_of(e_ab, 5))], col_l[dense_at(sel_of(e_de, 1))],
+                                                       col_l[dense_at(sel_of(e_de, 3))], col_l[dense_at(sel_of(e_de, 6))], cbs_l, cda_l,
                                                        a.mc.cap_words, gb_l, latc_l, slow_l, rf_l, mac_l);
                             const unsigned long long hits = __ballot(code0 + lane < n_codes && val2 == wave_v);
                             if (!hits) continue;
@@ -1548,9 +1573,9 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
                     for (uint32_t code = 0; code < n_codes; ++code) {
                         const uint4 e_de = enc[row_de0 + 25u * (code / 25u)];
                         const uint4 e_ab = enc[row0 + code % 25u];
-                        const double val2 = recost(col[sel_of(e_ab, 0) * LDS_ENT], col[sel_of(e_ab, 4) * LDS_ENT],
-                                                   col[sel_of(e_ab, 5) * LDS_ENT], col[sel_of(e_de, 1) * LDS_ENT],
-                                                   col[sel_of(e_de, 3) * LDS_ENT], col[sel_of(e_de, 6) * LDS_ENT], c_bs, c_da, cap,
+                        const double val2 = recost(col[dense_at(sel_of(e_ab, 0))], col[dense_at(sel_of(e_ab, 4))],
+                                                   col[dense_at(sel_of(e_ab, 5))], col[dense_at(sel_of(e_de, 1))],
+                                                   col[dense_at(sel_of(e_de, 3))], col[dense_at(sel_of(e_de, 6))], c_bs, c_da, cap,
                                                    gb_u, latc_u, slow_u, e_rf_part, e_mac_part);
                         const unsigned long long hits = __ballot(val2 == wave_v);
                         if (!hits) continue;
