@@ -42,10 +42,10 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (summaries under profiles/), scaled by
 # what the same counters read for a 1 GiB device-to-device copy (x2.0 and x1.0).  Valid only for the kernel
 # sources they were taken with: any change to the sources turns "traffic" into null.
-COUNTERS_TAKEN_WITH = "3364bc1ec41a721f3a89eadf52c3566f1d652e69d239b6ca4bc0d5fc9a46f1ae"
-TRAFFIC = {"k_search_dense_long": (2 * 62977.625 + 362.5625) * 1024.0,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB per dispatch
-           "k_search_bert": (2 * 29113.616 + 325.0625) * 1024.0,
-           "k_eval_batch": (2 * 20256.0 + 4195168.893) * 1024.0}
+COUNTERS_TAKEN_WITH = "b7beeaca18f62854b66925fb55d348076c9f00daea29a7ebc38d363729060256"
+TRAFFIC = {"k_search_dense_long": (2 * 58681.518 + 384.478) * 1024.0,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB per dispatch
+           "k_search_bert": (2 * 27769.446 + 325.094) * 1024.0,
+           "k_eval_batch": (2 * 20241.402 + 4195058.446) * 1024.0}
 TRAFFIC_SOURCE = {"k_search_dense_long": "profiles/k_search_dense_long.md", "k_search_bert": "profiles/k_search_bert_exhaustive.md",
                   "k_eval_batch": "profiles/k_eval_batch_bert.md"}
 
