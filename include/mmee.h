@@ -181,8 +181,11 @@ int mmee_search_multi(const mmee_workload *w, const mmee_hw *hw, const int *obje
 /* A helper for sweeps over hardware designs and sequence lengths (Sec. VII-I, Table IV; Sec. VII-H):
  * count independent searches (arrays of count workloads, hws, objectives, results) enqueued
  * back to back on one stream with a single synchronisation at the end.  Neighbouring entries
- * with identical workload and hw share one pass.  Returns the first non-zero per-entry code
- * (per-entry codes are stored in rc[i] when rc is not null). */
+ * with identical workload and hw share one pass.  Pruned passes for one key, or for energy and
+ * latency together, share kernel launches across problems (one per kind of pass present); the
+ * other passes run problem by problem.  mmee_result::kernel_seconds of a pass that shared
+ * launches is the device time of all the launches it shared.  Returns the first non-zero
+ * per-entry code (per-entry codes are stored in rc[i] when rc is not null). */
 int mmee_search_many(const mmee_workload *w, const mmee_hw *hw, const int *objectives,
                      uint32_t count, uint32_t flags, mmee_result *out, int *rc);
 

@@ -568,3 +568,18 @@ def test_search_many_mixed_small_problems_in_one_call(M):
             assert res.cost.energy_pj == exp[1].energy_pj and res.cost.latency_cycles == exp[1].latency_cycles
             for fld in INT_FIELDS:
                 assert getattr(res.cost, fld) == getattr(exp[1], fld)
+
+
+def test_search_many_prepared_arguments_reused(M):
+    """ManyPoints marshals the argument arrays once; calling with it repeatedly gives what the
+    plain call gives, also after a call with other flags in between."""
+    cases = random_small_cases(12, 0x9A7E)
+    points = [(w, h, obj) for k, (w, h) in enumerate(cases) for obj in ((0, 1) if k % 2 else (2,))]
+    want, want_codes = M.mmee_search_many(points, M.SEARCH_PRUNED)
+    prepared = M.ManyPoints(points)
+    for flags in (M.SEARCH_PRUNED, M.SEARCH_EXHAUSTIVE, M.SEARCH_PRUNED):
+        got, codes = M.mmee_search_many(prepared, flags)
+        assert list(codes) == list(want_codes)
+        for g, w_, c in zip(got, want, want_codes):
+            if c == 0:
+                assert g.best.idx == w_.best.idx and g.cost.energy_pj == w_.cost.energy_pj
