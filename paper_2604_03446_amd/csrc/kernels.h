@@ -9,6 +9,7 @@
 //   k_front_step     online:   one point of the buffer-size / DRAM-access front
 //   k_eval_batch     online:   the same model, one 64-byte record per candidate
 //   k_decode         online:   index -> mapping
+// (k_search_batch and k_batch_finish, the pruned search over many problems per launch: batch.h)
 #pragma once
 #include <hip/hip_runtime.h>
 #include <type_traits>
@@ -1200,7 +1201,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, (popcount4(MASK) >= 3 || (MASK & 4 
 // are lane registers for the whole task.  All of these sums are exact integers below 2^53 (the
 // host refuses a workload where they are not), so their association is free.
 //
-// A block stages one chunk of TC tilings, as k_search does, and its waves take neighbouring tasks.
+// A block stages one chunk of TC tilings (stage_tables_direct below) and its waves take neighbouring tasks.
 // Persistent blocks, global work counter and grid finish as in k_search; the last chunks are handed
 // out in fifths of tasks (one p_D each) to even out the end.  The host sends single-key passes
 // here: the 18 per-tiling constants, the (D, E) parts and one key's nine minima fit 128 registers
