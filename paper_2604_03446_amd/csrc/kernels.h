@@ -1368,11 +1368,15 @@ __global__ __launch_bounds__(DENSE_THREADS, 4) void k_search_dense(SearchArgs a)
             if constexpr (FAST) l_dram = dram_words * a.mc.dram_k;
             else l_dram = a.mc.dram_bw > 0.0 ? a.mc.c_lat * (((dram_words / a.mc.BH) * a.mc.word) / a.mc.dram_bw) : 0.0;
             if constexpr (LATCAP) ok = ok & (l_dram <= lat_cap);
-            const double over = __hiloint2double(ok ? 0 : 0x7ff00000, 0);
-            e_part = fmax(e_part, over);
-            l_dram = fmax(l_dram, over);
+            if constexpr (MASK == 1) {
+                e_part = ok ? e_part : inf;             // the energy alone: one select, the DRAM time is not needed
+            } else {
+                const double over = __hiloint2double(ok ? 0 : 0x7ff00000, 0);
+                e_part = fmax(e_part, over);
+                l_dram = fmax(l_dram, over);
+                pin(l_dram);
+            }
             pin(e_part);
-            pin(l_dram);
 #pragma unroll
             for (int c9 = 0; c9 < 9; ++c9) {
                 double en;
