@@ -235,3 +235,23 @@ def test_reconfigurable_array_shapes_on_bert_against_stored_oracle_optima(M):
         best_gpu = min(range(5), key=lambda k: (edp(results[k].cost.energy_pj, results[k].cost.latency_cycles), k))
         assert best_gpu == best_oracle
     print("best shape on bert:", shapes[best_oracle], flush=True)
+
+
+def test_register_file_capacity_moves_the_optimum(M):
+    """rf_bytes is a live capacity (stationary words per PE, Sec. V-D): on bert's shape the optimal
+    energy falls as the file grows and another mapping wins; pruned == exhaustive at every size and
+    the winners' records are the oracle's."""
+    cfg = CONFIGS["bert"]
+    ow = O.workload(cfg["workload"])
+    energies, winners = [], []
+    for rf in (8, 32, 256, 4096):
+        h = dict(cfg["hw"], rf_bytes=rf)
+        pruned = M.mmee_search_multi(cfg["workload"], h, [0, 1], M.SEARCH_PRUNED)
+        full = M.mmee_search_multi(cfg["workload"], h, [0, 1], M.SEARCH_EXHAUSTIVE)
+        for a, b in zip(pruned, full):
+            assert a.best.idx == b.best.idx
+            check_result_against_oracle(a, ow, O.hw(h))
+        energies.append(pruned[0].cost.energy_pj)
+        winners.append(pruned[0].best.idx)
+    assert all(a >= b for a, b in zip(energies, energies[1:])) and energies[0] > energies[-1]
+    assert winners[0] != winners[-1]
