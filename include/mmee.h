@@ -248,7 +248,7 @@ int mmee_search_noalloc(const mmee_workload *w, const mmee_hw *hw, int objective
  * reports its counts. */
 int mmee_offline_stats(mmee_row_stats *out);
 
-/* The offline stage's row lists (Sec. VI-A "enumerated offline", Sec. VI-B): the rows of group
+/* The offline stage's row lists (Sec. VI-A: listed ahead of time; Sec. VI-B): the rows of group
  * g = r + 2 f that denote a dataflow (which = 0) or that survive the symbolic pruning of Eq. (12)
  * (which = 1), ascending, as row numbers inside the group: p_A + 5 p_B + 25 p_D + 125 p_E +
  * 625 * order.  rows_out (host) receives at most `capacity` numbers, *n_rows the length of the

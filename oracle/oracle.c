@@ -86,7 +86,7 @@ enum { DIM_I = 0, DIM_K = 1, DIM_L = 2, DIM_J = 3 };
 enum { OPD_A = 0, OPD_B = 1, OPD_C = 2, OPD_D = 3, OPD_E = 4 };
 enum { OBJ_ENERGY = 0, OBJ_LATENCY = 1, OBJ_LATENCY_THEN_ENERGY = 2, OBJ_EDP = 3, N_OBJ = 4 };
 
-/* Own dimensions of each operand (Sec. V-A "Operand's dimensions"). */
+/* Own dimensions of each operand (Sec. V-A, the paragraph on an operand's dimensions). */
 static const int OWN[5][2] = {
     {DIM_I, DIM_K}, {DIM_K, DIM_L}, {DIM_I, DIM_L}, {DIM_L, DIM_J}, {DIM_I, DIM_J}};
 

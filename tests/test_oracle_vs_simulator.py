@@ -69,7 +69,7 @@ def test_every_order_level_recompute_fusion(X, xD):
                 assert sum(da_o) == c.da_words
                 # Buffer size, Eq. (1), (2), (4).  Each operand's BS_X is the largest fill its block
                 # reaches in the run; with the retained operands' measured footprints reserved for the
-                # whole run (Sec. IV-A: allocated and retained) the peak over the stages IS the
+                # whole run (Sec. IV-A: the space is set aside and kept) the peak over the stages IS the
                 # requirement, on every row and every shape, single-iteration loops included.
                 assert list(s.footprint) == list(dt.bs), (order, level, r, f)
                 assert s.max_reserved == c.bs_words, (order, level, r, f)
