@@ -1,7 +1,7 @@
 """Writes tests/golden/expected_optima.json: the optimal mapping of every
 benchmark configuration, of seed-chosen hardware-sweep points (every sequence length up to
-16384 included), of the two-GEMM / convolution-chain shapes and of a few logical PE-array
-shapes, for all four objectives, found by the CPU oracle's exhaustive search; plus the two
+16384 included), of the two-GEMM / convolution-chain shapes, of a few logical PE-array
+shapes and of three shapes on arrays that are no powers of two, for all four objectives, found by the CPU oracle's exhaustive search; plus the two
 Pareto fronts of the BERT-like configuration over its whole space.
 
 Calls only oracle/ and the shared input module.  Full enumeration: about
@@ -91,6 +91,20 @@ def sweep_choice(seed=0x5EED):
 # logical shapes of a 256-PE array (the BERT-like configuration has 16 x 16)
 ARRAY_SHAPES = [(4, 64), (8, 32), (32, 8), (64, 4)]
 
+# shapes with many divisors on arrays, register files and bandwidths that are no powers of two: tiles fold
+# raggedly onto the array, energies are fractional, one bandwidth term takes the general (division) form
+ODD = {
+    "odd_60x12_pe12x20": (dict(B=1, H=2, N=60, d=12, word_bytes=2, tiling_mode=1, c_softmax=10),
+                          dict(pe_rows=12, pe_cols=20, n_arrays=3, rf_bytes=50, gb_bytes=3000,
+                               e_dram=187.5, e_gb=6.25, e_rf=1.0, e_mac=0.75, dram_bw=3.0, gb_bw=5.0)),
+    "odd_72x10_pe7x3": (dict(B=2, H=1, N=72, d=10, word_bytes=4, tiling_mode=1, c_softmax=3),
+                        dict(pe_rows=7, pe_cols=3, n_arrays=1, rf_bytes=28, gb_bytes=9000,
+                             e_dram=120.0, e_gb=5.0, e_rf=2.0, e_mac=1.0, dram_bw=64.0, gb_bw=96.0)),
+    "odd_48x18_pe24x9": (dict(B=1, H=3, N=48, d=18, word_bytes=2, tiling_mode=1, c_softmax=10),
+                         dict(pe_rows=24, pe_cols=9, n_arrays=2, rf_bytes=200, gb_bytes=1 << 13,
+                              e_dram=251.0625, e_gb=7.5, e_rf=0.5, e_mac=1.25, dram_bw=6.0, gb_bw=128.0)),
+}
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -103,6 +117,7 @@ def main():
     bert = CONFIGS["bert"]
     todo += [(f"shape_bert_{r}x{c}", bert["workload"], dict(bert["hw"], pe_rows=r, pe_cols=c)) for r, c in ARRAY_SHAPES]
     todo += [("fronts_bert", bert["workload"], bert["hw"])]
+    todo += [(name, w, h) for name, (w, h) in ODD.items()]
     if args.only:
         keep = set(args.only.split(","))
         todo = [t for t in todo if t[0] in keep]

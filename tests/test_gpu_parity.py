@@ -598,3 +598,26 @@ def test_repeated_searches_return_the_same_candidate(M):
             for rep in range(30):
                 got = [M.mmee_search_ex(cfg["workload"], cfg["hw"], obj, flags).best.idx for obj in range(4)]
                 assert got == want, (name, flags, rep, got, want)
+
+
+@pytest.mark.parametrize("name", ["odd_60x12_pe12x20", "odd_72x10_pe7x3", "odd_48x18_pe24x9"])
+def test_odd_shapes_against_stored_oracle_optima(M, name):
+    """Arrays, register files and bandwidths that are no powers of two, fractional energies, shapes
+    with many divisors (1.2e9 to 2.8e9 candidates): every key, pruned and exhaustive, term-by-term
+    sum included, against the optima that the oracle's full enumeration stored."""
+    exp = load_expected()[name]
+    w, h = exp["workload"], exp["hw"]
+    ow, oh = O.workload(w), O.hw(h)
+    keys = ("energy", "latency", "latency_then_energy", "edp")
+    for flags in (M.SEARCH_PRUNED, M.SEARCH_EXHAUSTIVE, M.SEARCH_EXHAUSTIVE | M.SEARCH_ORDERED_SUM):
+        four = M.mmee_search_multi(w, h, [0, 1, 2, 3], flags)
+        singles = [M.mmee_search_ex(w, h, obj, flags) for obj in range(4)]
+        for obj, key in enumerate(keys):
+            want = exp["best"][key]
+            for res in (four[obj], singles[obj]):
+                assert res.best.idx == want["idx"], (name, flags, key)
+                assert res.cost.energy_pj == float.fromhex(want["energy_pj"])
+                assert res.cost.latency_cycles == float.fromhex(want["latency_cycles"])
+                for fld in INT_FIELDS:
+                    assert getattr(res.cost, fld) == want[fld], (name, flags, key, fld)
+            check_result_against_oracle(singles[obj], ow, oh)
